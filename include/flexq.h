@@ -1,0 +1,176 @@
+/*
+ * flexq.h -- C ABI of the MI355X (gfx950) W6A6 / W6A8 quantized linear layer.
+ *
+ * The operation (paper Section 4.2, Eq. 5 and Eq. 7; Section 4.1.3):
+ *
+ *     Y[M,N] (fp16) = dequant( Xq[M,K] . Wq[N,K]^T )
+ *
+ * with Wq signed 6-bit codes in [-32,31] (one fp16 scale per output channel,
+ * or per group of 128 consecutive k), Xq signed 6- or 8-bit codes carried in
+ * int8 (one fp16 scale per token), the integer product accumulated exactly in
+ * int32, and the scales applied in the kernel's epilogue.  Weights are
+ * quantized and packed once, offline; activations are quantized online
+ * (Section 4.1.3, "FlexQ System Runtime").
+ *
+ * Conventions for every entry point:
+ *   - every pointer marked "dev" is DEVICE memory owned by the caller; the
+ *     library allocates nothing and frees nothing;
+ *   - `stream` is a hipStream_t (NULL = the null stream); calls only enqueue
+ *     work on it and never synchronize;
+ *   - fp16 values travel as their 16-bit patterns (uint16_t);
+ *   - the return value is FLEXQ_OK or a negative error; arguments are checked
+ *     on the host BEFORE any GPU call, so a bad argument never launches work;
+ *   - inputs must be finite; codes outside their stated range are a caller
+ *     error that is not detected on the device.
+ */
+#ifndef FLEXQ_H
+#define FLEXQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int flexq_status;
+
+enum {
+    FLEXQ_OK = 0,
+    FLEXQ_EINVAL = -1, /* null pointer, M < 1, bad act_bits / group / mode    */
+    FLEXQ_ESHAPE = -2, /* N % 32 != 0, K % 128 != 0, or K > FLEXQ_MAX_K       */
+    FLEXQ_EALIGN = -3, /* a pointer is not 16-byte aligned                    */
+    FLEXQ_EHIP = -4,   /* the HIP runtime reported an error at launch         */
+    FLEXQ_EWORKSPACE = -5 /* workspace missing or smaller than required       */
+};
+
+/* Largest reduction length: keeps 4 * 32 * 128 * K below 2^31 with margin
+ * (the kernels accumulate 4x the product and shift it back, exactly).       */
+#define FLEXQ_MAX_K 65536
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char *flexq_status_string(flexq_status s);
+
+/* Version of the packed-weight layout; a packed buffer is only valid for the
+ * library version that wrote it. */
+int flexq_layout_version(void);
+
+/*
+ * Size in bytes of the packed form of Wq[N,K]: exactly N*K*6/8 bytes of codes
+ * followed by the fp16 scales (N of them, or N*K/128 in group mode), rounded
+ * up to 256 bytes.  group: 0 = one scale per output channel, 128 = one per 128
+ * consecutive k.  Returns 0 for an invalid shape or group.
+ * (Section 4.3.1: weights are bit-packed offline; Section 4.1.1: group 128.)
+ */
+size_t flexq_packed_bytes(int N, int K, int group);
+
+/*
+ * Offline weight quantization (Section 2.1 symmetric, Section 4.1.1 groups):
+ * per channel (group = 0) or per 128-group, scale = fp16(absmax / 31), 1.0 if
+ * that is zero; code = clamp(round_half_even(w / scale), -32, 31) with an IEEE
+ * fp32 division.
+ *   w   dev, fp32 [N,K] row-major (K contiguous)
+ *   wq  dev, int8 [N,K], out
+ *   sw  dev, fp16 [N] or [N, K/128], out
+ */
+flexq_status flexq_quant_w6(const float *w, int N, int K, int group, int8_t *wq,
+                            uint16_t *sw, void *stream);
+
+/*
+ * Offline packing (Section 4.3.1, "Bit-level Data Packing", re-designed for
+ * 16-byte-per-lane loads that cover whole 128-byte lines): a bijective repack
+ * of the 6-bit two's-complement codes plus a copy of the scales.
+ *   wq      dev, int8 [N,K], codes in [-32,31]
+ *   sw      dev, fp16 [N] (group 0) or [N, K/128] (group 128)
+ *   packed  dev, out, flexq_packed_bytes(N,K,group) bytes, 16-byte aligned
+ */
+flexq_status flexq_pack_w6(const int8_t *wq, const uint16_t *sw, int N, int K,
+                           int group, void *packed, void *stream);
+
+/* Inverse of flexq_pack_w6 (for round-trip checks): packed -> wq, sw. */
+flexq_status flexq_unpack_w6(const void *packed, int N, int K, int group,
+                             int8_t *wq, uint16_t *sw, void *stream);
+
+/*
+ * Online activation quantization (Section 4.1.3; Section 2.1): per token,
+ * sx = fp16(absmax / qmax) (1.0 if zero), xq = clamp(round_half_even(x / sx))
+ * with qmax = 31 (act_bits 6, range [-32,31]) or 127 (act_bits 8, [-128,127]).
+ *   x   dev, fp16 [M,K] row-major, 16-byte aligned
+ *   xq  dev, int8 [M,K], out, 16-byte aligned
+ *   sx  dev, fp16 [M], out
+ * K must be a multiple of 128.
+ */
+flexq_status flexq_quant_act(const uint16_t *x, int M, int K, int act_bits,
+                             int8_t *xq, uint16_t *sx, void *stream);
+
+/*
+ * Bytes of workspace the GEMM / GEMV entry points need for (M,N,K): room for
+ * split-K partial sums and their arrival counters, and for the quantized
+ * activations when the quantize prologue is requested.  Never 0 for a valid
+ * shape.  The workspace must be 256-byte aligned, and its first
+ * FLEXQ_WORKSPACE_COUNTER_BYTES bytes must be zero before the first call that
+ * uses it (flexq_workspace_init does that); every call leaves them zero again.
+ * Calls that share a workspace must be ordered on one stream.
+ */
+#define FLEXQ_WORKSPACE_COUNTER_BYTES 16384
+size_t flexq_workspace_bytes(int M, int N, int K);
+
+/* Zero the counter area of a fresh workspace (a small fill kernel). */
+flexq_status flexq_workspace_init(void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/*
+ * The quantized linear layer (Section 4.2 Eq. 5, Eq. 7; Section 4.3.4 fused
+ * dequantization).  W6A6 and W6A8 differ only in the activation code range.
+ *
+ *   packed     dev, from flexq_pack_w6 with the same N, K, group
+ *   group      0 or 128, as packed
+ *   xq, sx     dev, quantized activations int8 [M,K] and fp16 scales [M];
+ *              ignored (may be NULL) when x_fp16 is given
+ *   x_fp16     dev or NULL.  Non-NULL: fp16 activations [M,K]; the call first
+ *              quantizes them per token (6 bits for *_w6a6, 8 for *_w6a8) into
+ *              the workspace, then multiplies
+ *   y          dev, out, fp16 [M,N] row-major
+ *   acc_out    dev or NULL.  Non-NULL (group 0 only): receives the exact int32
+ *              accumulators [M,N]
+ *   workspace  dev, flexq_workspace_bytes(M,N,K) bytes, counters zeroed
+ *
+ * y[m,n] = fp16( float(acc[m,n]) * (sx[m]*sw[n]) ) for group 0 (the product
+ * of two fp16 scales is exact in fp32), and
+ * y[m,n] = fp16( sx[m] * sum_g sw[n,g]*float(acc_g[m,n]) ) in fp32 for
+ * group 128.  Any M >= 1 is accepted; flexq_gemm_* pick the kernel from M,
+ * flexq_gemv_* use the bandwidth-bound streaming kernel whenever M <= 128.
+ */
+flexq_status flexq_gemm_w6a6(const void *packed, int group, const int8_t *xq,
+                             const uint16_t *sx, const uint16_t *x_fp16, int M,
+                             int N, int K, uint16_t *y, int32_t *acc_out,
+                             void *workspace, size_t workspace_bytes,
+                             void *stream);
+flexq_status flexq_gemm_w6a8(const void *packed, int group, const int8_t *xq,
+                             const uint16_t *sx, const uint16_t *x_fp16, int M,
+                             int N, int K, uint16_t *y, int32_t *acc_out,
+                             void *workspace, size_t workspace_bytes,
+                             void *stream);
+flexq_status flexq_gemv_w6a6(const void *packed, int group, const int8_t *xq,
+                             const uint16_t *sx, const uint16_t *x_fp16, int M,
+                             int N, int K, uint16_t *y, int32_t *acc_out,
+                             void *workspace, size_t workspace_bytes,
+                             void *stream);
+flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq,
+                             const uint16_t *sx, const uint16_t *x_fp16, int M,
+                             int N, int K, uint16_t *y, int32_t *acc_out,
+                             void *workspace, size_t workspace_bytes,
+                             void *stream);
+
+/*
+ * Tuning hook for experiments and tests: force the kernel the next calls use.
+ * which: 0 = automatic, 1 = streaming (skinny) kernel, 2 = tiled GEMM kernel.
+ * split_k: 0 = automatic, else the number of K splits of the streaming kernel.
+ * Process-wide; returns FLEXQ_EINVAL for unknown values.
+ */
+flexq_status flexq_set_dispatch(int which, int split_k);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXQ_H */

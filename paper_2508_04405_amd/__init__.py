@@ -1,1 +1,8 @@
-"""MI355X-native W6A6 / W6A8 quantized linear layer (GEMM + decode GEMV)."""
+"""MI355X-native W6A6 / W6A8 quantized linear layer (GEMM + decode GEMV).
+
+`binding` is the thin ctypes layer over the C ABI in include/flexq.h; `synth`
+draws the seeded synthetic inputs; `build` compiles the HIP sources.
+"""
+from .binding import (FlexQError, gemm_w6a6, gemm_w6a8, gemv_w6a6, gemv_w6a8,  # noqa: F401
+                      layout_version, load, make_workspace, pack_w6, packed_bytes, quant_act,
+                      quant_w6, set_dispatch, unpack_w6, workspace_bytes)

@@ -1,0 +1,189 @@
+"""ctypes binding of libflexq.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their
+device pointers and the current HIP stream through the C ABI declared in
+include/flexq.h, and returns torch tensors.  There is no CPU fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflexq.so")
+_lib = None
+
+
+class FlexQError(RuntimeError):
+    pass
+
+
+def load():
+    """Load libflexq.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    c_int, c_size, vp = ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
+    lib.flexq_status_string.restype = ctypes.c_char_p
+    lib.flexq_status_string.argtypes = [c_int]
+    lib.flexq_layout_version.restype = c_int
+    lib.flexq_layout_version.argtypes = []
+    lib.flexq_packed_bytes.restype = c_size
+    lib.flexq_packed_bytes.argtypes = [c_int, c_int, c_int]
+    lib.flexq_quant_w6.restype = c_int
+    lib.flexq_quant_w6.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
+    lib.flexq_pack_w6.restype = c_int
+    lib.flexq_pack_w6.argtypes = [vp, vp, c_int, c_int, c_int, vp, vp]
+    lib.flexq_unpack_w6.restype = c_int
+    lib.flexq_unpack_w6.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
+    lib.flexq_quant_act.restype = c_int
+    lib.flexq_quant_act.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
+    lib.flexq_workspace_bytes.restype = c_size
+    lib.flexq_workspace_bytes.argtypes = [c_int, c_int, c_int]
+    lib.flexq_workspace_init.restype = c_int
+    lib.flexq_workspace_init.argtypes = [vp, c_size, vp]
+    for name in ("flexq_gemm_w6a6", "flexq_gemm_w6a8", "flexq_gemv_w6a6", "flexq_gemv_w6a8"):
+        fn = getattr(lib, name)
+        fn.restype = c_int
+        fn.argtypes = [vp, c_int, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp, c_size, vp]
+    lib.flexq_set_dispatch.restype = c_int
+    lib.flexq_set_dispatch.argtypes = [c_int, c_int]
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise FlexQError(f"flexq: {load().flexq_status_string(status).decode()} ({status})")
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dev(t, dtype):
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), (t.device, t.dtype)
+    return t
+
+
+def layout_version():
+    return load().flexq_layout_version()
+
+
+def packed_bytes(N, K, group=0):
+    return load().flexq_packed_bytes(N, K, group)
+
+
+def set_dispatch(which=0, split_k=0):
+    _check(load().flexq_set_dispatch(which, split_k))
+
+
+def quant_w6(w, group=0):
+    """fp32 W[N,K] -> (int8 codes [N,K], fp16 scales [N] or [N,K/128])."""
+    lib = load()
+    _dev(w, torch.float32)
+    N, K = w.shape
+    wq = torch.empty((N, K), dtype=torch.int8, device=w.device)
+    sw = torch.empty((N,) if group == 0 else (N, K // 128), dtype=torch.float16, device=w.device)
+    _check(lib.flexq_quant_w6(_ptr(w), N, K, group, _ptr(wq), _ptr(sw), _stream()))
+    return wq, sw
+
+
+def pack_w6(wq, sw, group=0):
+    """int8 codes [N,K] + fp16 scales -> opaque packed buffer (uint8)."""
+    lib = load()
+    _dev(wq, torch.int8)
+    _dev(sw, torch.float16)
+    N, K = wq.shape
+    nbytes = lib.flexq_packed_bytes(N, K, group)
+    if nbytes == 0:
+        _check(lib.flexq_pack_w6(_ptr(wq), _ptr(sw), N, K, group, _ptr(wq), _stream()))
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=wq.device)
+    _check(lib.flexq_pack_w6(_ptr(wq), _ptr(sw), N, K, group, _ptr(packed), _stream()))
+    return packed
+
+
+def unpack_w6(packed, N, K, group=0):
+    lib = load()
+    _dev(packed, torch.uint8)
+    wq = torch.empty((N, K), dtype=torch.int8, device=packed.device)
+    sw = torch.empty((N,) if group == 0 else (N, K // 128), dtype=torch.float16,
+                     device=packed.device)
+    _check(lib.flexq_unpack_w6(_ptr(packed), N, K, group, _ptr(wq), _ptr(sw), _stream()))
+    return wq, sw
+
+
+def quant_act(x, act_bits):
+    """fp16 X[M,K] -> (int8 codes [M,K], fp16 scales [M])."""
+    lib = load()
+    _dev(x, torch.float16)
+    M, K = x.shape
+    xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    sx = torch.empty((M,), dtype=torch.float16, device=x.device)
+    _check(lib.flexq_quant_act(_ptr(x), M, K, act_bits, _ptr(xq), _ptr(sx), _stream()))
+    return xq, sx
+
+
+def workspace_bytes(M, N, K):
+    return load().flexq_workspace_bytes(M, N, K)
+
+
+def make_workspace(M, N, K, device="cuda", extra=0):
+    """Allocate (with torch) and zero-initialise a workspace for (M,N,K)."""
+    lib = load()
+    nbytes = lib.flexq_workspace_bytes(M, N, K) + extra
+    if nbytes == extra:
+        raise FlexQError("flexq: invalid shape for workspace")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    _check(lib.flexq_workspace_init(_ptr(ws), nbytes, _stream()))
+    return ws
+
+
+def _linear(name, packed, N, K, group, xq, sx, x_fp16, workspace, want_acc, out):
+    lib = load()
+    _dev(packed, torch.uint8)
+    if x_fp16 is not None:
+        _dev(x_fp16, torch.float16)
+        M = x_fp16.shape[0]
+        dev = x_fp16.device
+    else:
+        _dev(xq, torch.int8)
+        _dev(sx, torch.float16)
+        M = xq.shape[0]
+        dev = xq.device
+    if workspace is None:
+        workspace = make_workspace(M, N, K, dev)
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=dev)
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    _check(getattr(lib, name)(_ptr(packed), group, _ptr(xq), _ptr(sx), _ptr(x_fp16), M, N, K,
+                              _ptr(y), _ptr(acc), _ptr(workspace), workspace.numel(), _stream()))
+    return (y, acc) if want_acc else y
+
+
+def gemm_w6a6(packed, N, K, group=0, xq=None, sx=None, x_fp16=None, workspace=None,
+              want_acc=False, out=None):
+    return _linear("flexq_gemm_w6a6", packed, N, K, group, xq, sx, x_fp16, workspace, want_acc, out)
+
+
+def gemm_w6a8(packed, N, K, group=0, xq=None, sx=None, x_fp16=None, workspace=None,
+              want_acc=False, out=None):
+    return _linear("flexq_gemm_w6a8", packed, N, K, group, xq, sx, x_fp16, workspace, want_acc, out)
+
+
+def gemv_w6a6(packed, N, K, group=0, xq=None, sx=None, x_fp16=None, workspace=None,
+              want_acc=False, out=None):
+    return _linear("flexq_gemv_w6a6", packed, N, K, group, xq, sx, x_fp16, workspace, want_acc, out)
+
+
+def gemv_w6a8(packed, N, K, group=0, xq=None, sx=None, x_fp16=None, workspace=None,
+              want_acc=False, out=None):
+    return _linear("flexq_gemv_w6a8", packed, N, K, group, xq, sx, x_fp16, workspace, want_acc, out)

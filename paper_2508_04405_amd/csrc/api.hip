@@ -1,0 +1,281 @@
+// C ABI of the library: argument checks on the host, then kernel dispatch.
+// Nothing here allocates, frees or synchronizes.
+#include "../../include/flexq.h"
+#include "flexq_kernels.h"
+
+#include <atomic>
+
+namespace {
+
+std::atomic<int> g_force_kernel{0};
+std::atomic<int> g_force_split{0};
+
+constexpr int kMaxRowBlocks = FLEXQ_WORKSPACE_COUNTER_BYTES / 4;
+constexpr int kSkinnyMaxM = 128;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+flexq_status check_shape(int N, int K, int group)
+{
+    if (N < 1 || K < 1) return FLEXQ_EINVAL;
+    if (group != 0 && group != 128) return FLEXQ_EINVAL;
+    if (N % 32 != 0 || K % 128 != 0 || K > FLEXQ_MAX_K || N / 32 > kMaxRowBlocks) return FLEXQ_ESHAPE;
+    return FLEXQ_OK;
+}
+
+size_t scale_count(int N, int K, int group) { return group == 0 ? (size_t)N : (size_t)N * (K / 128); }
+
+// K splits of the streaming kernel: enough workgroups to keep every CU's
+// memory pipeline full, at least two tiles per wavefront, and partial-sum
+// traffic (8 bytes per split, token and column) well under the weight stream.
+int choose_split(int M, int N, int K)
+{
+    const int forced = g_force_split.load();
+    const int kt = K / 128;
+    int ks;
+    if (forced > 0) {
+        ks = forced;
+    } else {
+        const int blocks_wanted = 2048;
+        ks = (blocks_wanted + N / 32 - 1) / (N / 32);
+        const int by_traffic = (int)((long)K / (96L * M));  // partial bytes <= ~1/9 of weights
+        if (ks > by_traffic) ks = by_traffic;
+        if (ks > kt / 8) ks = kt / 8;
+    }
+    if (ks > kt) ks = kt;
+    if (ks > 64) ks = 64;
+    if (ks < 1) ks = 1;
+    return ks;
+}
+
+struct Workspace {
+    unsigned *counters;
+    int8_t *xq;
+    uint16_t *sx;
+    void *partial;
+    size_t partial_capacity;  // bytes
+};
+
+size_t fixed_bytes(int M, int K)
+{
+    return FLEXQ_WORKSPACE_COUNTER_BYTES + round_up((size_t)M * K, 256) + round_up((size_t)M * 2, 256);
+}
+
+Workspace carve(void *ws, size_t bytes, int M, int K)
+{
+    Workspace w;
+    uint8_t *p = (uint8_t *)ws;
+    w.counters = (unsigned *)p;
+    p += FLEXQ_WORKSPACE_COUNTER_BYTES;
+    w.xq = (int8_t *)p;
+    p += round_up((size_t)M * K, 256);
+    w.sx = (uint16_t *)p;
+    p += round_up((size_t)M * 2, 256);
+    w.partial = p;
+    w.partial_capacity = bytes - fixed_bytes(M, K);
+    return w;
+}
+
+flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int group, const int8_t *xq,
+                    const uint16_t *sx, const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
+                    int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!packed || !y || M < 1) return FLEXQ_EINVAL;
+    if (!x_fp16 && (!xq || !sx)) return FLEXQ_EINVAL;
+    flexq_status s = check_shape(N, K, group);
+    if (s != FLEXQ_OK) return s;
+    if (group != 0 && acc_out) return FLEXQ_EINVAL;
+    if (!aligned16(packed) || !aligned16(y) || (acc_out && !aligned16(acc_out)) ||
+        (x_fp16 && !aligned16(x_fp16)) || (!x_fp16 && !aligned16(xq)))
+        return FLEXQ_EALIGN;
+    if (!workspace || workspace_bytes < flexq_workspace_bytes(M, N, K)) return FLEXQ_EWORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return FLEXQ_EALIGN;
+
+    hipStream_t st = (hipStream_t)stream;
+    Workspace ws = carve(workspace, workspace_bytes, M, K);
+    if (x_fp16) {
+        if (flexq::launch_quant_act(x_fp16, M, K, act_bits, ws.xq, ws.sx, st) != hipSuccess)
+            return FLEXQ_EHIP;
+        xq = ws.xq;
+        sx = ws.sx;
+    }
+
+    flexq::LinearArgs a;
+    a.packed = packed;
+    a.scales = (const uint16_t *)((const uint8_t *)packed + (size_t)N * K * 6 / 8);
+    a.N = N;
+    a.K = K;
+    a.group = group;
+    a.counters = ws.counters;
+    a.partial = ws.partial;
+
+    const int forced = g_force_kernel.load();
+    bool stream_kernel = prefer_stream ? (M <= kSkinnyMaxM) : (M <= 64);
+    if (forced == 1) stream_kernel = true;
+    if (forced == 2) stream_kernel = false;
+
+    if (!stream_kernel) {
+        a.xq = xq;
+        a.sx = sx;
+        a.M = M;
+        a.y = y;
+        a.acc_out = acc_out;
+        a.split_k = 1;
+        return flexq::launch_gemm(a, st) == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
+    }
+    for (int m0 = 0; m0 < M; m0 += kSkinnyMaxM) {
+        const int rows = M - m0 < kSkinnyMaxM ? M - m0 : kSkinnyMaxM;
+        a.xq = xq + (size_t)m0 * K;
+        a.sx = sx + m0;
+        a.M = rows;
+        a.y = y + (size_t)m0 * N;
+        a.acc_out = acc_out ? acc_out + (size_t)m0 * N : nullptr;
+        a.split_k = choose_split(rows, N, K);
+        // never outgrow the partial-sum area the caller provided
+        const size_t per_split = (size_t)rows * N * 4;
+        if ((size_t)a.split_k * per_split > ws.partial_capacity)
+            a.split_k = (int)(ws.partial_capacity / per_split);
+        if (a.split_k < 1) a.split_k = 1;
+        if (flexq::launch_skinny(a, st) != hipSuccess) return FLEXQ_EHIP;
+    }
+    return FLEXQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *flexq_status_string(flexq_status s)
+{
+    switch (s) {
+    case FLEXQ_OK: return "ok";
+    case FLEXQ_EINVAL: return "invalid argument";
+    case FLEXQ_ESHAPE: return "unsupported shape (need N % 32 == 0, K % 128 == 0, K <= 65536)";
+    case FLEXQ_EALIGN: return "pointer not sufficiently aligned";
+    case FLEXQ_EHIP: return "HIP runtime error";
+    case FLEXQ_EWORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+    }
+}
+
+int flexq_layout_version(void) { return 1; }
+
+size_t flexq_packed_bytes(int N, int K, int group)
+{
+    if (check_shape(N, K, group) != FLEXQ_OK) return 0;
+    return round_up((size_t)N * K * 6 / 8 + 2 * scale_count(N, K, group), 256);
+}
+
+flexq_status flexq_quant_w6(const float *w, int N, int K, int group, int8_t *wq, uint16_t *sw,
+                            void *stream)
+{
+    if (!w || !wq || !sw) return FLEXQ_EINVAL;
+    flexq_status s = check_shape(N, K, group);
+    if (s != FLEXQ_OK) return s;
+    return flexq::launch_quant_w6(w, N, K, group, wq, sw, (hipStream_t)stream) == hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
+flexq_status flexq_pack_w6(const int8_t *wq, const uint16_t *sw, int N, int K, int group,
+                           void *packed, void *stream)
+{
+    if (!wq || !sw || !packed) return FLEXQ_EINVAL;
+    flexq_status s = check_shape(N, K, group);
+    if (s != FLEXQ_OK) return s;
+    if (!aligned16(wq) || !aligned16(packed)) return FLEXQ_EALIGN;
+    return flexq::launch_pack_w6(wq, sw, N, K, group, packed, (hipStream_t)stream) == hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
+flexq_status flexq_unpack_w6(const void *packed, int N, int K, int group, int8_t *wq, uint16_t *sw,
+                             void *stream)
+{
+    if (!wq || !sw || !packed) return FLEXQ_EINVAL;
+    flexq_status s = check_shape(N, K, group);
+    if (s != FLEXQ_OK) return s;
+    if (!aligned16(wq) || !aligned16(packed)) return FLEXQ_EALIGN;
+    return flexq::launch_unpack_w6(packed, N, K, group, wq, sw, (hipStream_t)stream) == hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
+flexq_status flexq_quant_act(const uint16_t *x, int M, int K, int act_bits, int8_t *xq, uint16_t *sx,
+                             void *stream)
+{
+    if (!x || !xq || !sx || M < 1) return FLEXQ_EINVAL;
+    if (act_bits != 6 && act_bits != 8) return FLEXQ_EINVAL;
+    if (K < 1) return FLEXQ_EINVAL;
+    if (K % 128 != 0 || K > FLEXQ_MAX_K) return FLEXQ_ESHAPE;
+    if (!aligned16(x) || !aligned16(xq)) return FLEXQ_EALIGN;
+    return flexq::launch_quant_act(x, M, K, act_bits, xq, sx, (hipStream_t)stream) == hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
+size_t flexq_workspace_bytes(int M, int N, int K)
+{
+    if (M < 1 || check_shape(N, K, 0) != FLEXQ_OK) return 0;
+    size_t partial = 0;
+    const int top = M < kSkinnyMaxM ? M : kSkinnyMaxM;
+    for (int m = 1; m <= top; ++m) {
+        const size_t b = (size_t)choose_split(m, N, K) * m * N * 4;
+        if (b > partial) partial = b;
+    }
+    return fixed_bytes(M, K) + round_up(partial, 256);
+}
+
+flexq_status flexq_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return FLEXQ_EINVAL;
+    if (workspace_bytes < FLEXQ_WORKSPACE_COUNTER_BYTES) return FLEXQ_EWORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return FLEXQ_EALIGN;
+    return flexq::launch_fill_zero(workspace, FLEXQ_WORKSPACE_COUNTER_BYTES, (hipStream_t)stream) ==
+                   hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
+flexq_status flexq_gemm_w6a6(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
+                             const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
+                             int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return linear(6, false, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
+                  workspace_bytes, stream);
+}
+
+flexq_status flexq_gemm_w6a8(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
+                             const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
+                             int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return linear(8, false, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
+                  workspace_bytes, stream);
+}
+
+flexq_status flexq_gemv_w6a6(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
+                             const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
+                             int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return linear(6, true, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
+                  workspace_bytes, stream);
+}
+
+flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
+                             const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
+                             int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return linear(8, true, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
+                  workspace_bytes, stream);
+}
+
+flexq_status flexq_set_dispatch(int which, int split_k)
+{
+    if (which < 0 || which > 2 || split_k < 0 || split_k > 64) return FLEXQ_EINVAL;
+    g_force_kernel.store(which);
+    g_force_split.store(split_k);
+    return FLEXQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Device-side helpers shared by the gfx950 kernels: the packed 6-bit tile
+// layout, its in-register expansion to int8, and the i8 MFMA wrapper.
+//
+// Packed layout (this library's own; the paper's Section 4.3.1 packs 1-bit
+// planes for binary tensor cores, which CDNA4 does not need):
+//
+//   The matrix Wq[N,K] is cut into tiles of 32 rows x 128 k.  Tile (nb, kb)
+//   starts at byte (nb * K/128 + kb) * 3072, so the tiles of one 32-row block
+//   follow each other along k.  A tile is three planes of 1024 bytes; plane j
+//   gives lane l of a wavefront the 16 bytes at l*16, so one
+//   global_load_dwordx4 per plane reads 1 KiB contiguous (eight 128-byte
+//   lines) per wavefront.  Lane l serves row r = l & 31 and k-half h = l >> 5.
+//   Byte t of plane j at lane l holds
+//       bits 7..2 : the code of W[32nb + r][128kb + 32j + 16h + t]     (j=0,1,2)
+//       bits 1..0 : bits (5-2j)..(4-2j) of the code of
+//                   W[32nb + r][128kb + 96 + 16h + t]
+//   i.e. three of every four weights sit in the top six bits of a byte and the
+//   fourth is spread over the three spare bit pairs.  A byte whose low two
+//   bits are cleared IS the int8 value 4*w, so the MFMA runs on 4*w and the
+//   int32 sum is shifted right by two, exactly, afterwards.
+//
+//   After the 3072-byte tiles come the fp16 scales: [N] for per-channel mode,
+//   or [N/32][K/128][32] (tile order) for group-128 mode.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+#define FLEXQ_TILE_ROWS 32
+#define FLEXQ_TILE_K 128
+#define FLEXQ_TILE_BYTES 3072
+
+// One packed tile as a lane sees it: three 16-byte pieces.
+struct PackedTile {
+    v4i q0, q1, q2;
+};
+
+__device__ __forceinline__ PackedTile load_packed_tile(const v4i *tile_base, int lane)
+{
+    PackedTile t;
+    t.q0 = __builtin_nontemporal_load(tile_base + lane);
+    t.q1 = __builtin_nontemporal_load(tile_base + 64 + lane);
+    t.q2 = __builtin_nontemporal_load(tile_base + 128 + lane);
+    return t;
+}
+
+__device__ __forceinline__ PackedTile load_packed_tile_cached(const v4i *tile_base, int lane)
+{
+    PackedTile t;
+    t.q0 = tile_base[lane];
+    t.q1 = tile_base[64 + lane];
+    t.q2 = tile_base[128 + lane];
+    return t;
+}
+
+// k-step j (0..3) of a tile as the int8 MFMA operand of this lane: 16 values
+// 4*w for k = 32j + 16h + 0..15 of row r.
+__device__ __forceinline__ v4i unpack_kstep(const PackedTile &t, int j)
+{
+    const int top6 = (int)0xFCFCFCFC;
+    const int low2 = 0x03030303;
+    if (j == 0) return t.q0 & top6;
+    if (j == 1) return t.q1 & top6;
+    if (j == 2) return t.q2 & top6;
+    return ((t.q0 & low2) << 6) | ((t.q1 & low2) << 4) | ((t.q2 & low2) << 2);
+}
+
+// D[32x32] += A[32 x 32k] * B[32k x 32], int8 in, int32 out.  Lane l supplies
+// row (l & 31) of A and column (l & 31) of B, 16 consecutive k each, k-half
+// (l >> 5).  Register r of D at lane l is D[8*(r/4) + 4*(l>>5) + r%4][l & 31].
+__device__ __forceinline__ v16i mfma_i8(v4i a, v4i b, v16i c)
+{
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ int mfma_row(int r, int lane)
+{
+    return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+}
+
+__device__ __forceinline__ float h2f(uint16_t bits)
+{
+    _Float16 h;
+    __builtin_memcpy(&h, &bits, 2);
+    return (float)h;
+}
+
+__device__ __forceinline__ uint16_t f2h(float f)
+{
+    _Float16 h = (_Float16)f;          // v_cvt_f16_f32, round half to even
+    uint16_t bits;
+    __builtin_memcpy(&bits, &h, 2);
+    return bits;
+}

@@ -1,0 +1,39 @@
+// Host-side launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace flexq {
+
+// Everything a GEMM / GEMV launch needs.  Pointers are device pointers.
+struct LinearArgs {
+    const void *packed;      // tiles, then scales
+    const uint16_t *scales;  // = packed + N*K*6/8
+    const int8_t *xq;        // [M,K]
+    const uint16_t *sx;      // [M]
+    int M, N, K;
+    int group;               // 0 or 128
+    uint16_t *y;             // [M,N]
+    int32_t *acc_out;        // [M,N] or null
+    unsigned *counters;      // zero on entry, zero on exit
+    void *partial;           // split-K partial sums
+    int split_k;             // >= 1
+};
+
+hipError_t launch_quant_w6(const float *w, int N, int K, int group, int8_t *wq, uint16_t *sw,
+                           hipStream_t st);
+hipError_t launch_quant_act(const uint16_t *x, int M, int K, int act_bits, int8_t *xq,
+                            uint16_t *sx, hipStream_t st);
+hipError_t launch_pack_w6(const int8_t *wq, const uint16_t *sw, int N, int K, int group,
+                          void *packed, hipStream_t st);
+hipError_t launch_unpack_w6(const void *packed, int N, int K, int group, int8_t *wq, uint16_t *sw,
+                            hipStream_t st);
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
+
+// Streaming kernel, M <= 128 per launch (the caller loops over row chunks).
+hipError_t launch_skinny(const LinearArgs &a, hipStream_t st);
+// Tiled MFMA kernel for large M.
+hipError_t launch_gemm(const LinearArgs &a, hipStream_t st);
+
+}  // namespace flexq

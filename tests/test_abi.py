@@ -1,0 +1,92 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments on the host before any GPU call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2508_04405_amd as fq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P16 = ctypes.c_void_p(0x1000)          # a non-null, 256-byte aligned fake pointer
+ODD = ctypes.c_void_p(0x1008)          # 8-byte aligned only
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "flexq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(flexq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = fq.load()
+    names = _declared()
+    assert {"flexq_pack_w6", "flexq_quant_act", "flexq_gemm_w6a6", "flexq_gemm_w6a8",
+            "flexq_gemv_w6a8"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_sizes():
+    lib = fq.load()
+    assert lib.flexq_layout_version() >= 1
+    # exactly 0.75 bytes per weight, then the fp16 scales, rounded to 256
+    assert lib.flexq_packed_bytes(128, 256, 0) == 128 * 256 * 6 // 8 + 256
+    assert lib.flexq_packed_bytes(8192, 8192, 0) == 8192 * 8192 * 6 // 8 + 2 * 8192
+    assert lib.flexq_packed_bytes(5120, 5120, 128) == 5120 * 5120 * 6 // 8 + 2 * 5120 * 40
+    assert lib.flexq_packed_bytes(100, 256, 0) == 0
+    assert lib.flexq_packed_bytes(128, 200, 0) == 0
+    assert lib.flexq_packed_bytes(128, 256, 64) == 0
+    assert lib.flexq_workspace_bytes(1, 8192, 8192) >= 16384 + 8192
+    assert lib.flexq_workspace_bytes(0, 8192, 8192) == 0
+
+
+@pytest.mark.parametrize("fn", ["flexq_gemm_w6a6", "flexq_gemm_w6a8", "flexq_gemv_w6a6",
+                                "flexq_gemv_w6a8"])
+def test_linear_argument_errors(fn):
+    lib = fq.load()
+    f = getattr(lib, fn)
+    big = 1 << 30
+    ok = dict(packed=P16, group=0, xq=P16, sx=P16, x=None, M=4, N=128, K=256, y=P16, acc=None,
+              ws=P16, wsb=big)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["packed"], a["group"], a["xq"], a["sx"], a["x"], a["M"], a["N"], a["K"], a["y"],
+                 a["acc"], a["ws"], a["wsb"], None)
+
+    assert call(packed=None) == -1
+    assert call(y=None) == -1
+    assert call(xq=None) == -1
+    assert call(M=0) == -1
+    assert call(group=64) == -1
+    assert call(group=128, acc=P16) == -1
+    assert call(N=100) == -2
+    assert call(K=200) == -2
+    assert call(K=65536 + 128) == -2
+    assert call(packed=ODD) == -3
+    assert call(y=ODD) == -3
+    assert call(xq=ODD) == -3
+    assert call(ws=None) == -5
+    assert call(wsb=16) == -5
+    assert call(ws=ODD) == -3
+
+
+def test_other_entry_points_argument_errors():
+    lib = fq.load()
+    assert lib.flexq_quant_act(None, 1, 128, 8, P16, P16, None) == -1
+    assert lib.flexq_quant_act(P16, 1, 128, 7, P16, P16, None) == -1
+    assert lib.flexq_quant_act(P16, 1, 100, 8, P16, P16, None) == -2
+    assert lib.flexq_quant_act(ODD, 1, 128, 8, P16, P16, None) == -3
+    assert lib.flexq_pack_w6(P16, P16, 96, 256, 0, None, None) == -1
+    assert lib.flexq_pack_w6(P16, P16, 100, 256, 0, P16, None) == -2
+    assert lib.flexq_pack_w6(P16, P16, 96, 256, 0, ODD, None) == -3
+    assert lib.flexq_quant_w6(None, 96, 256, 0, P16, P16, None) == -1
+    assert lib.flexq_quant_w6(P16, 96, 256, 32, P16, P16, None) == -1
+    assert lib.flexq_unpack_w6(P16, 96, 300, 0, P16, P16, None) == -2
+    assert lib.flexq_workspace_init(None, 1 << 20, None) == -1
+    assert lib.flexq_workspace_init(P16, 16, None) == -5
+    assert lib.flexq_set_dispatch(3, 0) == -1
+    assert lib.flexq_set_dispatch(0, 0) == 0
+    assert b"shape" in lib.flexq_status_string(-2)

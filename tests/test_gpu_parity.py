@@ -1,0 +1,330 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Integer results (codes, scales' bit patterns, int32
+accumulators) must be bit-exact; fp16 outputs within one fp16 ulp (group mode:
+plus the fp32 summation bound stated at `assert_y_close`)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2508_04405_amd as fq
+from paper_2508_04405_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def ordered(h):
+    """Map fp16 bit patterns to integers that order like the values."""
+    b = h.view(np.uint16).astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7fff), b)
+
+
+def assert_y_close(got, want, slack=None):
+    """Within 1 fp16 ulp.  `slack` (absolute, per element) widens it where the
+    kernel sums fp32 group terms in its own order."""
+    got = np.asarray(got)
+    want = np.asarray(want)
+    d = np.abs(ordered(got) - ordered(want))
+    bad = d > 1
+    if slack is not None:
+        err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+        ulp = np.abs(want.astype(np.float64)) * 2.0**-10 + 2.0**-24
+        bad &= err > ulp + slack
+    assert not bad.any(), (int(bad.sum()), got[bad][:5], want[bad][:5])
+    rel = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    big = np.abs(want.astype(np.float64)) > 2.0**-14
+    if slack is None:
+        assert np.all(rel[big] <= 1e-3 * np.abs(want.astype(np.float64))[big])
+
+
+def prepare(w, group=0):
+    """fp32 weights -> GPU quantize + pack; returns (packed, wq, sw) on device."""
+    wq, sw = fq.quant_w6(to_dev(w), group)
+    return fq.pack_w6(wq, sw, group), wq, sw
+
+
+# ------------------------------------------------------------- quantizers
+
+@pytest.mark.parametrize("group", [0, 128])
+def test_quant_w6_bit_exact(group):
+    say(f"quant_w6 group={group}")
+    w = synth.weights(160, 640, 0.02, seed=5)
+    w[3] = 0.0                                  # an all-zero channel
+    w[4, :128] = 0.0                            # an all-zero group
+    w[5, 7] = 1e-8                              # scale underflows in fp16
+    w[6, :4] = [31 * 1.4 * 2.0**-24, -31 * 1.4 * 2.0**-24, 0.0, 1e-9]
+    w[6, 4:] = 0.0                              # subnormal scale, codes clamp to 31 / -32
+    wq, sw = fq.quant_w6(to_dev(w), group)
+    rq, rs = oracle.quantize(w, 6, group)
+    assert np.array_equal(wq.cpu().numpy(), rq)
+    assert np.array_equal(sw.cpu().numpy().view(np.uint16), rs.view(np.uint16))
+    assert rq[6, 1] == -32
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+def test_quant_act_bit_exact(bits):
+    say(f"quant_act bits={bits}")
+    qmax = 31 if bits == 6 else 127
+    x = synth.activations(37, 1152, seed=9, outlier_frac=0.02).astype(np.float32)
+    x[0] = 0.0
+    x[1] = 0.0
+    x[1, 5] = 6e-8                              # fp16 subnormal input
+    s = 0.5
+    ks = np.arange(1152) % (2 * qmax) - qmax
+    x[2] = (ks + 0.5) * s                       # every quotient is a tie
+    x[2, 0] = qmax * s
+    x[3] = 65504.0 * np.sign(x[3] + 0.1)        # fp16 max
+    x16 = x.astype(np.float16)
+    xq, sx = fq.quant_act(to_dev(x16), bits)
+    rq, rs = oracle.quantize(x16.astype(np.float32), bits, 0)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint16), rs.view(np.uint16))
+    assert np.array_equal(xq.cpu().numpy(), rq)
+
+
+def test_quant_act_large_rows():
+    say("quant_act K=28672 M=5")
+    x = synth.activations(5, 28672, seed=10, outlier_frac=0.01)
+    xq, sx = fq.quant_act(to_dev(x), 8)
+    rq, rs = oracle.quantize(x.astype(np.float32), 8, 0)
+    assert np.array_equal(xq.cpu().numpy(), rq)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint16), rs.view(np.uint16))
+
+
+# ------------------------------------------------------------------ packer
+
+@pytest.mark.parametrize("group", [0, 128])
+def test_pack_round_trip_all_codes(group):
+    say(f"pack round trip group={group}")
+    N, K = 96, 384
+    codes = np.arange(-32, 32, dtype=np.int8)
+    wq = np.stack([np.roll(np.tile(codes, K // 64), r) for r in range(N)])   # every code everywhere
+    rng = np.random.default_rng(0)
+    wq[64:] = rng.integers(-32, 32, (32, K))
+    sw = rng.uniform(1e-4, 1e-2, (N,) if group == 0 else (N, K // 128)).astype(np.float16)
+    packed = fq.pack_w6(to_dev(wq), to_dev(sw), group)
+    assert packed.numel() == fq.packed_bytes(N, K, group)
+    assert N * K * 6 // 8 + sw.size * 2 <= packed.numel() < N * K * 6 // 8 + sw.size * 2 + 256
+    wq2, sw2 = fq.unpack_w6(packed, N, K, group)
+    assert np.array_equal(wq2.cpu().numpy(), wq)
+    assert np.array_equal(sw2.cpu().numpy().view(np.uint16), sw.view(np.uint16))
+    # the code bytes are a bijection: distinct inputs give distinct packed bytes
+    wq_b = wq.copy()
+    wq_b[17, 200] ^= 1
+    packed_b = fq.pack_w6(to_dev(wq_b), to_dev(sw), group)
+    nb = N * K * 6 // 8
+    assert int((packed_b[:nb] != packed[:nb]).sum().item()) == 1
+
+
+# -------------------------------------------------------------- the layer
+
+def run_linear(fn, packed, N, K, group, xq, sx, want_acc, ws=None):
+    out = fn(packed, N, K, group, xq=xq, sx=sx, want_acc=want_acc, workspace=ws)
+    torch.cuda.synchronize()
+    if want_acc:
+        return out[0].cpu().numpy(), out[1].cpu().numpy()
+    return out.cpu().numpy(), None
+
+
+def group_slack(ref):
+    # fp32 sum of G terms in any order: at most G * 2^-23 * sum |term|, times sx
+    terms = np.abs(ref["acc_g"].astype(np.float64) * ref["sw"].astype(np.float64)[None, :, :])
+    G = terms.shape[2]
+    return ref["sx"].astype(np.float64)[:, None] * terms.sum(2) * G * 2.0**-23
+
+
+CASES = [
+    # M, K, N : the tiny configuration, then shapes spanning several tiles with ragged M
+    (4, 256, 128),
+    (1, 1024, 96),
+    (33, 640, 160),
+    (70, 1152, 288),
+    (128, 512, 64),
+    (130, 384, 320),
+    (300, 1280, 544),
+]
+
+
+@pytest.mark.parametrize("M,K,N", CASES)
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("kernel", ["stream", "tiled"])
+def test_linear_per_channel(M, K, N, bits, kernel):
+    say(f"linear per-channel M={M} K={K} N={N} A{bits} kernel={kernel}")
+    w = synth.weights(N, K, 0.02, seed=100 + M)
+    x = synth.activations(M, K, seed=200 + M, outlier_frac=0.02)
+    ref = oracle.linear(x, w, bits)
+    packed, wq, sw = prepare(w)
+    assert np.array_equal(wq.cpu().numpy(), ref["wq"])
+    xq, sx = fq.quant_act(to_dev(x), bits)
+    assert np.array_equal(xq.cpu().numpy(), ref["xq"])
+    fq.set_dispatch(1 if kernel == "stream" else 2, 0)
+    try:
+        fn = {6: fq.gemm_w6a6, 8: fq.gemm_w6a8}[bits]
+        y, acc = run_linear(fn, packed, N, K, 0, xq, sx, True)
+    finally:
+        fq.set_dispatch(0, 0)
+    assert np.array_equal(acc.astype(np.int64), ref["acc"])
+    assert_y_close(y.view(np.float16), ref["y"])
+
+
+@pytest.mark.parametrize("split", [1, 2, 3, 5, 8])
+@pytest.mark.parametrize("M", [1, 8, 40])
+def test_stream_kernel_k_splits(split, M):
+    say(f"stream kernel split={split} M={M}")
+    K, N = 1408, 192                            # 11 tiles along k: uneven splits
+    w = synth.weights(N, K, 0.02, seed=7)
+    x = synth.activations(M, K, seed=8, outlier_frac=0.02)
+    ref = oracle.linear(x, w, 8)
+    packed, _, _ = prepare(w)
+    xq, sx = fq.quant_act(to_dev(x), 8)
+    ws = fq.make_workspace(M, N, K, extra=split * M * N * 4)
+    fq.set_dispatch(1, split)
+    try:
+        for _ in range(3):                      # counters must return to zero each call
+            y, acc = run_linear(fq.gemv_w6a8, packed, N, K, 0, xq, sx, True, ws)
+            assert np.array_equal(acc.astype(np.int64), ref["acc"])
+            assert_y_close(y.view(np.float16), ref["y"])
+    finally:
+        fq.set_dispatch(0, 0)
+    assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
+
+
+@pytest.mark.parametrize("kernel", ["stream", "tiled"])
+def test_extreme_codes_exact(kernel):
+    say(f"extreme codes kernel={kernel}")
+    M, K, N = 3, 28672, 64                      # the longest reduction of the workloads
+    wq = np.full((N, K), -32, dtype=np.int8)
+    wq[1] = 31
+    xq = np.full((M, K), -128, dtype=np.int8)
+    xq[1] = 127
+    xq[2, ::2] = 0
+    sw = np.full(N, 2.0**-12, dtype=np.float16)
+    sx = np.full(M, 2.0**-9, dtype=np.float16)
+    packed = fq.pack_w6(to_dev(wq), to_dev(sw))
+    acc_ref = oracle.matmul(xq, wq)
+    y_ref = oracle.dequant(acc_ref, sx, sw)
+    fq.set_dispatch(1 if kernel == "stream" else 2, 0)
+    try:
+        y, acc = run_linear(fq.gemm_w6a8, packed, N, K, 0, to_dev(xq), to_dev(sx), True)
+    finally:
+        fq.set_dispatch(0, 0)
+    assert acc[0, 0] == 32 * 128 * K
+    assert np.array_equal(acc.astype(np.int64), acc_ref)
+    assert_y_close(y.view(np.float16), y_ref)
+
+
+@pytest.mark.parametrize("M,K,N", [(4, 256, 128), (32, 1280, 160), (100, 640, 96), (290, 1024, 320)])
+@pytest.mark.parametrize("kernel", ["stream", "tiled"])
+def test_linear_group128(M, K, N, kernel):
+    say(f"linear group-128 M={M} K={K} N={N} kernel={kernel}")
+    w = synth.weights(N, K, 0.02, seed=300 + M)
+    x = synth.activations(M, K, seed=400 + M, outlier_frac=0.02)
+    ref = oracle.linear(x, w, 8, group=128)
+    packed, wq, sw = prepare(w, 128)
+    assert np.array_equal(wq.cpu().numpy(), ref["wq"])
+    assert np.array_equal(sw.cpu().numpy().view(np.uint16), ref["sw"].view(np.uint16))
+    xq, sx = fq.quant_act(to_dev(x), 8)
+    fq.set_dispatch(1 if kernel == "stream" else 2, 0)
+    try:
+        y, _ = run_linear(fq.gemm_w6a8, packed, N, K, 128, xq, sx, False)
+    finally:
+        fq.set_dispatch(0, 0)
+    assert_y_close(y.view(np.float16), ref["y"], slack=group_slack(ref))
+    # the integer group partials: per-channel calls on 128-wide K slices
+    g = 1
+    sl = slice(128 * g, 128 * (g + 1))
+    pk = fq.pack_w6(to_dev(ref["wq"][:, sl]), to_dev(ref["sw"][:, g]))
+    _, acc = run_linear(fq.gemm_w6a8, pk, N, 128, 0, to_dev(ref["xq"][:, sl]), sx, True)
+    assert np.array_equal(acc.astype(np.int64), ref["acc_g"][:, :, g])
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("M", [1, 16, 200])
+def test_quantize_prologue(bits, M):
+    say(f"prologue A{bits} M={M}")
+    K, N = 1024, 256
+    w = synth.weights(N, K, 0.02, seed=11)
+    x = synth.activations(M, K, seed=12, outlier_frac=0.01)
+    ref = oracle.linear(x, w, bits)
+    packed, _, _ = prepare(w)
+    fn = {6: fq.gemm_w6a6, 8: fq.gemm_w6a8}[bits]
+    y, acc = fn(packed, N, K, 0, x_fp16=to_dev(x), want_acc=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
+    assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
+    # the two activation widths really differ
+    other = oracle.linear(x, w, 14 - bits)
+    assert not np.array_equal(other["acc"], ref["acc"])
+
+
+def test_repeatable():
+    say("determinism")
+    M, K, N = 16, 2048, 512
+    w = synth.weights(N, K, 0.02, seed=1)
+    x = synth.activations(M, K, seed=2)
+    packed, _, _ = prepare(w)
+    xq, sx = fq.quant_act(to_dev(x), 8)
+    ws = fq.make_workspace(M, N, K)
+    a = fq.gemv_w6a8(packed, N, K, xq=xq, sx=sx, workspace=ws).clone()
+    b = fq.gemv_w6a8(packed, N, K, xq=xq, sx=sx, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+# ------------------------------------------- full-size shapes, sampled outputs
+
+FULL = [
+    # name, K, N, sigma, M list (LLaMA-2-70B linears; 7B fused gate+up for a ragged N)
+    ("70b_o", 8192, 8192, 0.015, [1, 16, 128, 1024]),
+    ("70b_down", 28672, 8192, 0.015, [1, 16, 4096]),
+    ("7b_gate_up", 4096, 22016, 0.02, [1, 8, 512]),
+]
+
+
+@pytest.mark.parametrize("name,K,N,sigma,Ms", FULL)
+def test_full_size_sampled(name, K, N, sigma, Ms):
+    seed = 4000 + K + N
+    say(f"full size {name}: generating W[{N},{K}]")
+    rng = np.random.default_rng(seed)
+    cols = np.unique(np.concatenate([[0, 31, 32, N - 1], rng.integers(0, N, 124)]))
+    # quantize + pack on the GPU in row blocks to bound host memory
+    wq = torch.empty((N, K), dtype=torch.int8, device=DEV)
+    sw = torch.empty((N,), dtype=torch.float16, device=DEV)
+    step = 4096
+    for r0 in range(0, N, step):
+        r1 = min(N, r0 + step)
+        q, s = fq.quant_w6(to_dev(synth.weight_rows(N, K, sigma, seed, r0, r1)))
+        wq[r0:r1] = q
+        sw[r0:r1] = s
+    packed = fq.pack_w6(wq, sw)
+    del wq
+    w_cols = synth.weight_rows_at(N, K, sigma, seed, cols)
+    for M in Ms:
+        say(f"full size {name}: M={M}")
+        x = synth.activations(M, K, seed=seed + M, outlier_frac=0.01)
+        rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 30)]))
+        ref = oracle.linear(x[rows], w_cols, 8)
+        xq, sx = fq.quant_act(to_dev(x), 8)
+        assert np.array_equal(xq.cpu().numpy()[rows], ref["xq"])
+        ws = fq.make_workspace(M, N, K)
+        fn = fq.gemv_w6a8 if M <= 128 else fq.gemm_w6a8
+        y, acc = fn(packed, N, K, 0, xq=xq, sx=sx, want_acc=True, workspace=ws)
+        torch.cuda.synchronize()
+        acc = acc.cpu().numpy()[np.ix_(rows, cols)]
+        y = y.cpu().numpy()[np.ix_(rows, cols)]
+        assert np.array_equal(acc.astype(np.int64), ref["acc"])
+        assert_y_close(y.view(np.float16), ref["y"])
+        # a property that holds at any size: negated activations negate every accumulator
+        neg = (-xq.to(torch.int16)).clamp(-128, 127).to(torch.int8)
+        _, acc2 = fn(packed, N, K, 0, xq=neg, sx=sx, want_acc=True, workspace=ws)
+        _, acc1 = fn(packed, N, K, 0, xq=xq, sx=sx, want_acc=True, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(acc2, -acc1)

@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the W6A6 / W6A8 linear-layer hot path on one MI355X.
+
+Workload: the four linear layers of one LLaMA-2-70B decoder block (fused QKV,
+attention output, fused gate+up, down projection) on seeded synthetic weights
+and outlier-channel activations.  One step = one pass over the four layers:
+per-token activation quantization, then the packed-6-bit GEMM with the fused
+scale epilogue; W6A6 everywhere except W6A8 on the down projection, the
+paper's policy (Section 4.1.2).
+
+Two timed regions, each of exactly --steps steps after --warmup warm-ups:
+  prefill  M = 4096 tokens  -> GEMM TOPS (2*M*N*K per layer), the headline value
+  decode   M = 1 token      -> GEMV GB/s of algorithmic bytes
+Prints ONE JSON line.  Inputs are resident in HBM before timing starts.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "W6A8/W6A6 GEMM TOPS (M>=1024) + decode GEMV HBM GB/s, LLaMA-2-70B linears"
+PEAK_I8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
+SIGMA = 0.015
+LAYERS = [("qkv", 8192, 10240, 6), ("o", 8192, 8192, 6), ("gate_up", 8192, 57344, 6),
+          ("down", 28672, 8192, 8)]          # name, K, N, activation bits
+
+
+def algorithmic_bytes(M, N, K):
+    """Packed weights + weight scales + fp16 activations in + int8 codes out and in again
+    + activation scales + fp16 output."""
+    return 0.75 * N * K + 2 * N + 2 * M * K + 2 * M * K + 2 * M + 2 * M * N
+
+
+def gemm_bytes(M, N, K):
+    return 0.75 * N * K + 2 * N + M * K + 2 * M + 2 * M * N
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--prefill-m", type=int, default=4096)
+    ap.add_argument("--decode-m", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); "
+                 "there is no multi-GPU path to measure")
+
+    import numpy as np
+    import torch
+    import paper_2508_04405_amd as fq
+    from paper_2508_04405_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    fq.load()
+
+    # ---- resident inputs: packed weights, fp16 activations -----------------
+    gen = torch.Generator(device=dev)
+    layers = []
+    for i, (name, K, N, bits) in enumerate(LAYERS):
+        gen.manual_seed(3000 + 10 * i)
+        wq = torch.empty((N, K), dtype=torch.int8, device=dev)
+        sw = torch.empty((N,), dtype=torch.float16, device=dev)
+        for r0 in range(0, N, 8192):
+            r1 = min(N, r0 + 8192)
+            w = torch.randn((r1 - r0, K), generator=gen, device=dev, dtype=torch.float32) * SIGMA
+            q, s = fq.quant_w6(w)
+            wq[r0:r1], sw[r0:r1] = q, s
+            del w, q, s
+        packed = fq.pack_w6(wq, sw)
+        del wq, sw
+        layer = {"name": name, "K": K, "N": N, "bits": bits, "packed": packed}
+        for tag, M in (("prefill", args.prefill_m), ("decode", args.decode_m)):
+            x = torch.from_numpy(synth.activations(M, K, seed=3000 + 10 * i + 1,
+                                                   outlier_frac=0.01, outlier_scale=20.0)).to(dev)
+            layer[tag] = {
+                "M": M, "x": x,
+                "xq": torch.empty((M, K), dtype=torch.int8, device=dev),
+                "sx": torch.empty((M,), dtype=torch.float16, device=dev),
+                "y": torch.empty((M, N), dtype=torch.float16, device=dev),
+                "ws": fq.make_workspace(M, N, K, dev),
+            }
+        layers.append(layer)
+    torch.cuda.synchronize()
+
+    def run_layer(layer, tag, events=None):
+        b = layer[tag]
+        fq.quant_act(b["x"], layer["bits"], out=(b["xq"], b["sx"]))
+        gemm = fq.gemm_w6a6 if layer["bits"] == 6 else fq.gemm_w6a8
+        if tag == "decode":
+            gemm = fq.gemv_w6a6 if layer["bits"] == 6 else fq.gemv_w6a8
+        if events is not None:
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+        gemm(layer["packed"], layer["N"], layer["K"], 0, xq=b["xq"], sx=b["sx"],
+             workspace=b["ws"], out=b["y"])
+        if events is not None:
+            e1.record()
+            events.append((layer["name"], e0, e1))
+
+    def timed(tag, per_kernel_events):
+        for _ in range(args.warmup):
+            for layer in layers:
+                run_layer(layer, tag)
+        events = [] if per_kernel_events else None
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            for layer in layers:
+                run_layer(layer, tag, events)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) / args.steps, events
+
+    # ---- prefill: the headline ------------------------------------------------
+    Mp = args.prefill_m
+    step_s, events = timed("prefill", True)
+    ops_step = sum(2.0 * Mp * L["N"] * L["K"] for L in layers)
+    tops = ops_step / step_s / 1e12
+    per_layer = {}
+    for name, e0, e1 in events:
+        per_layer.setdefault(name, []).append(e0.elapsed_time(e1) * 1e-3)
+    gemm_s = sum(sum(v) for v in per_layer.values()) / args.steps       # the 4 GEMM launches
+    gemm_tops = ops_step / gemm_s / 1e12
+    launches = 4 * args.steps
+    roofline = {
+        "bound": "mfma", "kernel": "gemm_kernel (i8 MFMA 32x32x32, tiled)",
+        "achieved": round(gemm_tops, 2), "peak": PEAK_I8_TOPS / 1.0, "unit": "TOP/s",
+        "frac": round(gemm_tops / PEAK_I8_TOPS, 4),
+        "avg_launch_ms": round(gemm_s / 4 * 1e3, 4), "launches": launches,
+        "per_layer_tops": {n: round(2.0 * Mp * L["N"] * L["K"] / (sum(per_layer[n]) / args.steps) / 1e12, 2)
+                           for n, L in ((L["name"], L) for L in layers)},
+        "traffic": None,
+    }
+
+    # ---- decode: weight-streaming GEMV ---------------------------------------
+    Md = args.decode_m
+    dstep_s, _ = timed("decode", False)
+    dbytes = sum(algorithmic_bytes(Md, L["N"], L["K"]) for L in layers)
+    # kernel-only rate: the same four GEMV launches back to back, no quantize pass, one event pair
+    for layer in layers:
+        run_layer(layer, "decode")
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        for layer in layers:
+            b = layer["decode"]
+            (fq.gemv_w6a6 if layer["bits"] == 6 else fq.gemv_w6a8)(
+                layer["packed"], layer["N"], layer["K"], 0, xq=b["xq"], sx=b["sx"],
+                workspace=b["ws"], out=b["y"])
+    e1.record()
+    torch.cuda.synchronize()
+    gemv_s = e0.elapsed_time(e1) * 1e-3 / args.steps
+    gbytes = sum(gemm_bytes(Md, L["N"], L["K"]) for L in layers)
+    roofline_decode = {
+        "bound": "hbm", "kernel": "skinny_kernel (streaming GEMV, M=%d)" % Md,
+        "achieved": round(gbytes / gemv_s / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+        "frac": round(gbytes / gemv_s / 1e9 / PEAK_HBM_GBS, 4),
+        "avg_launch_us": round(gemv_s / 4 * 1e6, 2), "launches": 4 * args.steps,
+        "bytes_per_step": int(gbytes), "traffic": None,
+    }
+
+    # ---- the CPU oracle on a bounded sample of the same workload --------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        K, N = 8192, 8192
+        w = synth.weights(N, K, SIGMA, seed=3010)
+        wq, sw = oracle.quantize(w, 6, 0)
+        del w
+        rows = 1
+        x = synth.activations(64, K, seed=3011, outlier_frac=0.01)
+        t0 = time.perf_counter()
+        xq, sx = oracle.quantize(x[:rows].astype(np.float32), 6, 0)
+        oracle.dequant(oracle.matmul(xq, wq), sx, sw)
+        probe = time.perf_counter() - t0
+        rows = int(max(1, min(64, 15.0 / max(probe, 1e-3))))
+        t0 = time.perf_counter()
+        xq, sx = oracle.quantize(x[:rows].astype(np.float32), 6, 0)
+        oracle.dequant(oracle.matmul(xq, wq), sx, sw)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(2.0 * rows * N * K / dt / 1e12, 5), "unit": "TOPS",
+               "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "o_proj layer (K=8192, N=8192), %d of the %d prefill tokens: quantize + "
+                         "int64 matmul + fp64 dequant, %.1f s" % (rows, Mp, dt)}
+
+    out = {
+        "metric": METRIC, "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(step_s * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": "LLaMA-2-70B linears (configs[3]): qkv 8192x10240, o 8192x8192, "
+                               "gate_up 8192x57344 (W6A6), down 28672x8192 (W6A8); prefill M=%d, "
+                               "decode M=%d; step = quantize activations + GEMM for all four" % (Mp, Md),
+                   "prefill_tokens": Mp, "decode_tokens": Md},
+        "decode": {"value": round(dbytes / dstep_s / 1e9, 1), "unit": "GB/s",
+                   "us_per_step": round(dstep_s * 1e6, 2),
+                   "note": "algorithmic bytes of quantize + GEMV for the four layers / step time"},
+        "roofline": roofline, "roofline_decode": roofline_decode, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

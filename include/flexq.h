@@ -166,9 +166,10 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq,
  * Tuning hook for experiments and tests: force the kernel the next calls use.
  * which: 0 = automatic, 1 = streaming (skinny) kernel, 2 = tiled GEMM kernel.
  * split_k: 0 = automatic, else the number of K splits of the streaming kernel.
- * Process-wide; returns FLEXQ_EINVAL for unknown values.
+ * waves: 0 = automatic, else wavefronts per workgroup of the streaming kernel
+ * (4, 8 or 16).  Process-wide; returns FLEXQ_EINVAL for unknown values.
  */
-flexq_status flexq_set_dispatch(int which, int split_k);
+flexq_status flexq_set_dispatch(int which, int split_k, int waves);
 
 #ifdef __cplusplus
 }

@@ -52,7 +52,7 @@ def load():
         fn.restype = c_int
         fn.argtypes = [vp, c_int, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp, c_size, vp]
     lib.flexq_set_dispatch.restype = c_int
-    lib.flexq_set_dispatch.argtypes = [c_int, c_int]
+    lib.flexq_set_dispatch.argtypes = [c_int, c_int, c_int]
     _lib = lib
     return lib
 
@@ -83,8 +83,8 @@ def packed_bytes(N, K, group=0):
     return load().flexq_packed_bytes(N, K, group)
 
 
-def set_dispatch(which=0, split_k=0):
-    _check(load().flexq_set_dispatch(which, split_k))
+def set_dispatch(which=0, split_k=0, waves=0):
+    _check(load().flexq_set_dispatch(which, split_k, waves))
 
 
 def quant_w6(w, group=0):
@@ -122,13 +122,17 @@ def unpack_w6(packed, N, K, group=0):
     return wq, sw
 
 
-def quant_act(x, act_bits):
-    """fp16 X[M,K] -> (int8 codes [M,K], fp16 scales [M])."""
+def quant_act(x, act_bits, out=None):
+    """fp16 X[M,K] -> (int8 codes [M,K], fp16 scales [M]); `out` = (xq, sx) to reuse."""
     lib = load()
     _dev(x, torch.float16)
     M, K = x.shape
-    xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
-    sx = torch.empty((M,), dtype=torch.float16, device=x.device)
+    if out is not None:
+        xq, sx = _dev(out[0], torch.int8), _dev(out[1], torch.float16)
+        assert xq.shape == (M, K) and sx.shape == (M,)
+    else:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+        sx = torch.empty((M,), dtype=torch.float16, device=x.device)
     _check(lib.flexq_quant_act(_ptr(x), M, K, act_bits, _ptr(xq), _ptr(sx), _stream()))
     return xq, sx
 

@@ -9,6 +9,7 @@ namespace {
 
 std::atomic<int> g_force_kernel{0};
 std::atomic<int> g_force_split{0};
+std::atomic<int> g_force_waves{0};
 
 constexpr int kMaxRowBlocks = FLEXQ_WORKSPACE_COUNTER_BYTES / 4;
 constexpr int kSkinnyMaxM = 128;
@@ -26,9 +27,12 @@ flexq_status check_shape(int N, int K, int group)
 
 size_t scale_count(int N, int K, int group) { return group == 0 ? (size_t)N : (size_t)N * (K / 128); }
 
-// K splits of the streaming kernel: enough workgroups to keep every CU's
-// memory pipeline full, at least two tiles per wavefront, and partial-sum
-// traffic (8 bytes per split, token and column) well under the weight stream.
+// K splits of the streaming kernel.  Measured on MI355X: one workgroup of
+// eight wavefronts per 32-row block streams fastest as soon as there is at least
+// one such workgroup per CU; splitting K further only adds the cross-workgroup
+// hand-off.  So split just enough to give each of the 256 CUs a workgroup, keep
+// at least two tiles per wavefront, and keep the partial-sum traffic (8 bytes
+// per split, token and column) under a ninth of the weight stream.
 int choose_split(int M, int N, int K)
 {
     const int forced = g_force_split.load();
@@ -37,16 +41,26 @@ int choose_split(int M, int N, int K)
     if (forced > 0) {
         ks = forced;
     } else {
-        const int blocks_wanted = 2048;
-        ks = (blocks_wanted + N / 32 - 1) / (N / 32);
-        const int by_traffic = (int)((long)K / (96L * M));  // partial bytes <= ~1/9 of weights
+        const int row_blocks = N / 32;
+        ks = (256 + row_blocks - 1) / row_blocks;
+        const int by_traffic = (int)((long)K / (96L * M));
         if (ks > by_traffic) ks = by_traffic;
-        if (ks > kt / 8) ks = kt / 8;
+        if (ks > kt / 16) ks = kt / 16;
     }
     if (ks > kt) ks = kt;
     if (ks > 64) ks = 64;
     if (ks < 1) ks = 1;
     return ks;
+}
+
+// Wavefronts per workgroup of the streaming kernel.
+int choose_waves(int M, int N, int K, int ks)
+{
+    const int forced = g_force_waves.load();
+    if (forced > 0) return forced;
+    (void)N;
+    const int tiles = K / 128 / ks;
+    return tiles >= 16 ? 8 : 4;
 }
 
 struct Workspace {
@@ -137,7 +151,8 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
         if ((size_t)a.split_k * per_split > ws.partial_capacity)
             a.split_k = (int)(ws.partial_capacity / per_split);
         if (a.split_k < 1) a.split_k = 1;
-        if (flexq::launch_skinny(a, st) != hipSuccess) return FLEXQ_EHIP;
+        if (flexq::launch_skinny(a, choose_waves(rows, N, K, a.split_k), st) != hipSuccess)
+            return FLEXQ_EHIP;
     }
     return FLEXQ_OK;
 }
@@ -270,11 +285,13 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq, co
                   workspace_bytes, stream);
 }
 
-flexq_status flexq_set_dispatch(int which, int split_k)
+flexq_status flexq_set_dispatch(int which, int split_k, int waves)
 {
     if (which < 0 || which > 2 || split_k < 0 || split_k > 64) return FLEXQ_EINVAL;
+    if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return FLEXQ_EINVAL;
     g_force_kernel.store(which);
     g_force_split.store(split_k);
+    g_force_waves.store(waves);
     return FLEXQ_OK;
 }
 

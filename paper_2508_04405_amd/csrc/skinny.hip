@@ -10,46 +10,62 @@
 // i8 MFMA with the tokens as the row operand.  Rows beyond M are padding that
 // costs nothing: the matrix pipe is a few percent busy at HBM speed.
 //
-// Work split: one workgroup per (32-row block of W, K split); its four
-// wavefronts interleave over the tiles of that K range, and their partial
-// sums meet in LDS (the counterpart of the paper's Section 4.3.5 reduction:
-// exact integer sums, in any order).  With more than one K split the
-// workgroups leave partial sums in the workspace and the last one to arrive
-// at the block's counter adds them and runs the epilogue; it resets the
-// counter so the workspace is ready for the next call.
+// What decides the speed is how many bytes each CU keeps in flight and how few
+// dependent round trips to HBM a wavefront makes (the paper's Section 4.3.6
+// pipeline, in CDNA terms): a workgroup of W wavefronts owns one 32-row block
+// of W and one K range, the wavefronts interleave over its tiles with P tiles
+// (3 KiB each) in flight per wavefront, and the small activation slice the
+// workgroup needs is staged once in LDS (padded rows, conflict-free 16-byte
+// reads) when it fits.
+//
+// Partial sums of the wavefronts meet in LDS (the counterpart of the paper's
+// Section 4.3.5 reduction: exact integer sums, in any order).  With more than
+// one K split the workgroups leave partial sums in the workspace and the last
+// one to arrive at the block's counter adds them in split order and runs the
+// epilogue; it resets the counter so the workspace is ready for the next call.
 #include "flexq_device.h"
 #include "flexq_kernels.h"
 
 namespace {
 
-template <int MT>
+constexpr int kXldsBytes = 64 * 1024;  // activation slice staged in LDS up to this size
+
+template <int MT, bool XLDS>
 struct Stage {
     PackedTile w;
-    v4i a[MT][4];
+    v4i a[XLDS ? 1 : MT][XLDS ? 1 : 4];
     uint16_t gs;  // group scale of this lane's column (group mode)
 };
 
-template <int MT, bool GROUP>
-__device__ __forceinline__ void load_stage(Stage<MT> &s, const v4i *packed, const uint16_t *scales,
-                                           const int8_t *const (&xrow)[MT], long tile_index, int t,
-                                           int lane)
+template <int MT, bool GROUP, bool XLDS>
+__device__ __forceinline__ void load_stage(Stage<MT, XLDS> &s, const v4i *packed,
+                                           const uint16_t *scales, const int8_t *const (&xrow)[MT],
+                                           const bool (&xact)[MT], long tile_index, int t, int lane)
 {
     s.w = load_packed_tile(packed + tile_index * (FLEXQ_TILE_BYTES / 16), lane);
+    if (!XLDS) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt) {
+            if (xact[mt]) {  // lanes of padding rows load nothing
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            s.a[mt][j] = *reinterpret_cast<const v4i *>(xrow[mt] + (long)t * FLEXQ_TILE_K + 32 * j);
+                for (int j = 0; j < 4; ++j)
+                    s.a[XLDS ? 0 : mt][XLDS ? 0 : j] = *reinterpret_cast<const v4i *>(
+                        xrow[mt] + (long)t * FLEXQ_TILE_K + 32 * j);
+            }
+        }
+    }
     if (GROUP) s.gs = scales[tile_index * 32 + (lane & 31)];
 }
 
-template <int MT, bool GROUP, int P, int WAVES_PER_EU>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES_PER_EU, WAVES_PER_EU)))
+template <int MT, bool GROUP, bool XLDS, int P, int W, int WPE>
+__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void skinny_kernel(flexq::LinearArgs a)
 {
-    __shared__ int red[4][16][64];
+    __shared__ int red[W][4][64];
     __shared__ int s_last;
+    extern __shared__ __attribute__((aligned(16))) uint8_t xlds[];  // XLDS: M rows of (span + 16) bytes
 
+    constexpr int THREADS = 64 * W;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -64,13 +80,63 @@ void skinny_kernel(flexq::LinearArgs a)
     const v4i *packed = reinterpret_cast<const v4i *>(a.packed);
     const long tile_base = (long)nb * KT;
 
+    // ---- activations: this lane's token row, k-half ------------------------
     const int8_t *xrow[MT];
+    bool xact[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        int row = 32 * mt + (lane & 31);
-        row = row < M ? row : M - 1;
-        xrow[mt] = a.xq + (long)row * a.K + 16 * (lane >> 5);
+        const int row = 32 * mt + (lane & 31);
+        xact[mt] = row < M;
+        xrow[mt] = a.xq + (long)(xact[mt] ? row : 0) * a.K + 16 * (lane >> 5);
     }
+    const int span = (t1 - t0) * FLEXQ_TILE_K;  // bytes of k per token in this K range
+    const int xstride = span + 16;              // padded LDS row
+
+    v4i xstage[XLDS ? 4 : 1];
+    if (XLDS) {
+        // issue the slice's global loads first so they complete ahead of the weight stream
+        const int chunks_per_row = span >> 4;
+        const int total = M * chunks_per_row;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = tid + i * THREADS;
+            if (c < total) {
+                const int row = c / chunks_per_row, kc = c - row * chunks_per_row;
+                xstage[XLDS ? i : 0] = *reinterpret_cast<const v4i *>(
+                    a.xq + (long)row * a.K + (long)t0 * FLEXQ_TILE_K + 16 * kc);
+            }
+        }
+    }
+
+    Stage<MT, XLDS> st[P];
+    const int tw = t0 + wave;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int t = tw + W * p;
+        if (t < t1)
+            load_stage<MT, GROUP, XLDS>(st[p], packed, a.scales, xrow, xact, tile_base + t, t, lane);
+    }
+
+    if (XLDS) {
+        const int chunks_per_row = span >> 4;
+        const int total = M * chunks_per_row;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = tid + i * THREADS;
+            if (c < total) {
+                const int row = c / chunks_per_row, kc = c - row * chunks_per_row;
+                *reinterpret_cast<v4i *>(xlds + row * xstride + 16 * kc) = xstage[XLDS ? i : 0];
+            }
+        }
+        // slices larger than 4 chunks per thread: the rest, synchronously
+        for (int c = tid + 4 * THREADS; c < total; c += THREADS) {
+            const int row = c / chunks_per_row, kc = c - row * chunks_per_row;
+            *reinterpret_cast<v4i *>(xlds + row * xstride + 16 * kc) = *reinterpret_cast<const v4i *>(
+                a.xq + (long)row * a.K + (long)t0 * FLEXQ_TILE_K + 16 * kc);
+        }
+        __syncthreads();
+    }
+    const uint8_t *xl = xlds + (xact[0] ? (lane & 31) : 0) * xstride + 16 * (lane >> 5);
 
     v16i acc[MT];
     v16f facc[MT];
@@ -82,14 +148,6 @@ void skinny_kernel(flexq::LinearArgs a)
             facc[mt][r] = 0.0f;
         }
 
-    Stage<MT> st[P];
-    const int tw = t0 + wave;
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-        const int t = tw + 4 * p;
-        if (t < t1) load_stage<MT, GROUP>(st[p], packed, a.scales, xrow, tile_base + t, t, lane);
-    }
-
     for (int t = tw; t < t1;) {
 #pragma unroll
         for (int p = 0; p < P; ++p) {
@@ -97,6 +155,17 @@ void skinny_kernel(flexq::LinearArgs a)
                 v4i b[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) b[j] = unpack_kstep(st[p].w, j);
+                v4i af[MT][4];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (XLDS)
+                            af[mt][j] = *reinterpret_cast<const v4i *>(
+                                xl + (t - t0) * FLEXQ_TILE_K + 32 * j);
+                        else
+                            af[mt][j] = st[p].a[XLDS ? 0 : mt][XLDS ? 0 : j];
+                    }
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     if (GROUP) {
@@ -104,87 +173,103 @@ void skinny_kernel(flexq::LinearArgs a)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) part[r] = 0;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) part = mfma_i8(st[p].a[mt][j], b[j], part);
+                        for (int j = 0; j < 4; ++j) part = mfma_i8(af[mt][j], b[j], part);
                         const float gs = h2f(st[p].gs);
 #pragma unroll
                         for (int r = 0; r < 16; ++r) facc[mt][r] += (float)part[r] * gs;
                     } else {
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) acc[mt] = mfma_i8(st[p].a[mt][j], b[j], acc[mt]);
+                        for (int j = 0; j < 4; ++j) acc[mt] = mfma_i8(af[mt][j], b[j], acc[mt]);
                     }
                 }
-                const int tn = t + 4 * P;
+                const int tn = t + W * P;
                 if (tn < t1)
-                    load_stage<MT, GROUP>(st[p], packed, a.scales, xrow, tile_base + tn, tn, lane);
-                t += 4;
+                    load_stage<MT, GROUP, XLDS>(st[p], packed, a.scales, xrow, xact, tile_base + tn,
+                                                tn, lane);
+                t += W;
             }
         }
     }
 
-    // ---- meet in LDS, one 32-token slab at a time -------------------------
+    // ---- meet in LDS: 8 token rows (4 accumulator registers) at a time ------
     int *partial_i = reinterpret_cast<int *>(a.partial);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-            red[wave][r][lane] = GROUP ? __float_as_int(facc[mt][r]) : acc[mt][r];
-        __syncthreads();
+        for (int g = 0; g < 4; ++g) {
+            if (32 * mt + 8 * g >= M) break;  // these rows are padding (uniform)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + 256 * i;
-            const int r = idx >> 6, ln = idx & 63;
-            const int m = 32 * mt + mfma_row(r, ln);
-            const int n = 32 * nb + (ln & 31);
-            if (m < M) {
-                int v;
-                if (GROUP) {
-                    float f = __int_as_float(red[0][r][ln]) + __int_as_float(red[1][r][ln]) +
-                              __int_as_float(red[2][r][ln]) + __int_as_float(red[3][r][ln]);
-                    v = __float_as_int(f);
-                } else {
-                    v = red[0][r][ln] + red[1][r][ln] + red[2][r][ln] + red[3][r][ln];
-                }
-                if (KS == 1) {
+            for (int q = 0; q < 4; ++q)
+                red[wave][q][lane] = GROUP ? __float_as_int(facc[mt][4 * g + q]) : acc[mt][4 * g + q];
+            __syncthreads();
+            if (tid < 256) {
+                const int q = tid >> 6, ln = tid & 63;
+                const int m = 32 * mt + mfma_row(4 * g + q, ln);
+                const int n = 32 * nb + (ln & 31);
+                if (m < M) {
+                    int v;
                     if (GROUP) {
-                        a.y[(long)m * N + n] = f2h(__int_as_float(v) * 0.25f * h2f(a.sx[m]));
+                        float f = 0.0f;
+#pragma unroll
+                        for (int w = 0; w < W; ++w) f += __int_as_float(red[w][q][ln]);
+                        v = __float_as_int(f);
                     } else {
-                        const int q = v >> 2;
-                        if (a.acc_out) a.acc_out[(long)m * N + n] = q;
-                        a.y[(long)m * N + n] = f2h((float)q * (h2f(a.sx[m]) * h2f(a.scales[n])));
+                        v = 0;
+#pragma unroll
+                        for (int w = 0; w < W; ++w) v += red[w][q][ln];
                     }
-                } else {
-                    partial_i[((long)s * M + m) * N + n] = v;
+                    if (KS == 1) {
+                        if (GROUP) {
+                            a.y[(long)m * N + n] = f2h(__int_as_float(v) * 0.25f * h2f(a.sx[m]));
+                        } else {
+                            const int qv = v >> 2;
+                            if (a.acc_out) a.acc_out[(long)m * N + n] = qv;
+                            a.y[(long)m * N + n] = f2h((float)qv * (h2f(a.sx[m]) * h2f(a.scales[n])));
+                        }
+                    } else {
+                        // device-coherent write-through store: nothing stays dirty in
+                        // this XCD's L2, so publishing needs no cache write-back
+                        __hip_atomic_store(&partial_i[((long)s * M + m) * N + n], v, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
             }
+            __syncthreads();
         }
-        __syncthreads();
     }
     if (KS == 1) return;
 
     // ---- last workgroup of this row block adds the K splits ---------------
-    __threadfence();
+    // Every partial sum was written with a device-scope store; once this
+    // thread's stores are acknowledged (vmcnt 0) they are visible to every
+    // XCD, so the barrier plus one relaxed device-scope counter increment
+    // publishes them.  The reader uses device-scope loads, which never hit
+    // stale lines.  A full release/acquire fence would write back and
+    // invalidate the whole L2 for every workgroup -- far dearer than the GEMV.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
-        unsigned prev = __hip_atomic_fetch_add(&a.counters[nb], 1u, __ATOMIC_ACQ_REL,
+        unsigned prev = __hip_atomic_fetch_add(&a.counters[nb], 1u, __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT);
         s_last = (prev == (unsigned)(KS - 1));
     }
     __syncthreads();
     if (!s_last) return;
-    __threadfence();
     if (tid == 0)
         __hip_atomic_store(&a.counters[nb], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int n = 32 * nb + (tid & 31);
-    for (int m = tid >> 5; m < M; m += 8) {
+    for (int m = tid >> 5; m < M; m += THREADS / 32) {
         if (GROUP) {
             float f = 0.0f;
             for (int k = 0; k < KS; ++k)
-                f += __int_as_float(__builtin_nontemporal_load(&partial_i[((long)k * M + m) * N + n]));
+                f += __int_as_float(__hip_atomic_load(&partial_i[((long)k * M + m) * N + n],
+                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             a.y[(long)m * N + n] = f2h(f * 0.25f * h2f(a.sx[m]));
         } else {
             int v = 0;
             for (int k = 0; k < KS; ++k)
-                v += __builtin_nontemporal_load(&partial_i[((long)k * M + m) * N + n]);
+                v += __hip_atomic_load(&partial_i[((long)k * M + m) * N + n], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
             const int q = v >> 2;
             if (a.acc_out) a.acc_out[(long)m * N + n] = q;
             a.y[(long)m * N + n] = f2h((float)q * (h2f(a.sx[m]) * h2f(a.scales[n])));
@@ -192,24 +277,60 @@ void skinny_kernel(flexq::LinearArgs a)
     }
 }
 
-template <int MT, bool GROUP, int P, int WPE>
+template <int MT, bool GROUP, bool XLDS, int P, int W, int WPE>
 hipError_t launch_one(const flexq::LinearArgs &a, hipStream_t st)
 {
     const unsigned blocks = (unsigned)(a.N / 32) * (unsigned)a.split_k;
-    hipLaunchKernelGGL((skinny_kernel<MT, GROUP, P, WPE>), dim3(blocks), dim3(256), 0, st, a);
+    auto kern = skinny_kernel<MT, GROUP, XLDS, P, W, WPE>;
+    size_t dyn = 0;
+    if (XLDS) {
+        const int KT = a.K / 128;
+        const int max_tiles = (KT + a.split_k - 1) / a.split_k;
+        dyn = (size_t)a.M * (max_tiles * 128 + 16);
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               kXldsBytes + 32 * 16);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(64 * W), dyn, st, a);
     return hipGetLastError();
+}
+
+template <bool GROUP>
+hipError_t pick(const flexq::LinearArgs &a, int waves, hipStream_t st)
+{
+    const int KT = a.K / 128;
+    const int max_tiles = (KT + a.split_k - 1) / a.split_k;
+    const bool xlds = a.M <= 32 && (long)a.M * max_tiles * 128 <= kXldsBytes;
+    if (a.M <= 32) {
+        if (xlds) {
+            if (waves == 16) return launch_one<1, GROUP, true, 4, 16, 4>(a, st);
+            if (waves == 8) return launch_one<1, GROUP, true, 4, 8, 4>(a, st);
+            return launch_one<1, GROUP, true, 4, 4, 4>(a, st);
+        }
+        if (waves == 16) return launch_one<1, GROUP, false, 2, 16, 4>(a, st);
+        if (waves == 8) return launch_one<1, GROUP, false, 2, 8, 4>(a, st);
+        return launch_one<1, GROUP, false, 2, 4, 4>(a, st);
+    }
+    if (a.M <= 64) {
+        if (waves >= 8) return launch_one<2, GROUP, false, 2, 8, 2>(a, st);
+        return launch_one<2, GROUP, false, 2, 4, 2>(a, st);
+    }
+    if (waves >= 8) return launch_one<4, GROUP, false, 1, 8, 2>(a, st);
+    return launch_one<4, GROUP, false, 1, 4, 2>(a, st);
 }
 
 }  // namespace
 
 namespace flexq {
 
-hipError_t launch_skinny(const LinearArgs &a, hipStream_t st)
+hipError_t launch_skinny(const LinearArgs &a, int waves, hipStream_t st)
 {
-    const bool g = a.group != 0;
-    if (a.M <= 32) return g ? launch_one<1, true, 2, 4>(a, st) : launch_one<1, false, 2, 4>(a, st);
-    if (a.M <= 64) return g ? launch_one<2, true, 2, 2>(a, st) : launch_one<2, false, 2, 2>(a, st);
-    return g ? launch_one<4, true, 1, 2>(a, st) : launch_one<4, false, 1, 2>(a, st);
+    return a.group != 0 ? pick<true>(a, waves, st) : pick<false>(a, waves, st);
 }
 
 }  // namespace flexq

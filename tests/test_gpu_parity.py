@@ -176,9 +176,10 @@ def test_linear_per_channel(M, K, N, bits, kernel):
 
 
 @pytest.mark.parametrize("split", [1, 2, 3, 5, 8])
-@pytest.mark.parametrize("M", [1, 8, 40])
-def test_stream_kernel_k_splits(split, M):
-    say(f"stream kernel split={split} M={M}")
+@pytest.mark.parametrize("M", [1, 8, 40, 100])
+@pytest.mark.parametrize("waves", [4, 8, 16])
+def test_stream_kernel_k_splits(split, M, waves):
+    say(f"stream kernel split={split} M={M} waves={waves}")
     K, N = 1408, 192                            # 11 tiles along k: uneven splits
     w = synth.weights(N, K, 0.02, seed=7)
     x = synth.activations(M, K, seed=8, outlier_frac=0.02)
@@ -186,7 +187,7 @@ def test_stream_kernel_k_splits(split, M):
     packed, _, _ = prepare(w)
     xq, sx = fq.quant_act(to_dev(x), 8)
     ws = fq.make_workspace(M, N, K, extra=split * M * N * 4)
-    fq.set_dispatch(1, split)
+    fq.set_dispatch(1, split, waves)
     try:
         for _ in range(3):                      # counters must return to zero each call
             y, acc = run_linear(fq.gemv_w6a8, packed, N, K, 0, xq, sx, True, ws)

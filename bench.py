@@ -181,13 +181,13 @@ def main():
         w = synth.weights(N, K, SIGMA, seed=3010)
         wq, sw = oracle.quantize(w, 6, 0)
         del w
-        rows = 1
-        x = synth.activations(64, K, seed=3011, outlier_frac=0.01)
+        x = synth.activations(Mp, K, seed=3011, outlier_frac=0.01)
+        rows = min(32, Mp)
         t0 = time.perf_counter()
         xq, sx = oracle.quantize(x[:rows].astype(np.float32), 6, 0)
         oracle.dequant(oracle.matmul(xq, wq), sx, sw)
         probe = time.perf_counter() - t0
-        rows = int(max(1, min(64, 15.0 / max(probe, 1e-3))))
+        rows = int(max(1, min(Mp, rows * 15.0 / max(probe, 1e-3))))
         t0 = time.perf_counter()
         xq, sx = oracle.quantize(x[:rows].astype(np.float32), 6, 0)
         oracle.dequant(oracle.matmul(xq, wq), sx, sw)

@@ -167,9 +167,10 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq,
  * which: 0 = automatic, 1 = streaming (skinny) kernel, 2 = tiled GEMM kernel.
  * split_k: 0 = automatic, else the number of K splits of the streaming kernel.
  * waves: 0 = automatic, else wavefronts per workgroup of the streaming kernel
- * (4, 8 or 16).  Process-wide; returns FLEXQ_EINVAL for unknown values.
+ * (4, 8 or 16).  gemm_cfg: 0 = automatic, else a tile configuration of the
+ * tiled kernel.  Process-wide; returns FLEXQ_EINVAL for unknown values.
  */
-flexq_status flexq_set_dispatch(int which, int split_k, int waves);
+flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg);
 
 #ifdef __cplusplus
 }

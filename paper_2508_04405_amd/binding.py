@@ -52,7 +52,7 @@ def load():
         fn.restype = c_int
         fn.argtypes = [vp, c_int, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp, c_size, vp]
     lib.flexq_set_dispatch.restype = c_int
-    lib.flexq_set_dispatch.argtypes = [c_int, c_int, c_int]
+    lib.flexq_set_dispatch.argtypes = [c_int, c_int, c_int, c_int]
     _lib = lib
     return lib
 
@@ -83,8 +83,8 @@ def packed_bytes(N, K, group=0):
     return load().flexq_packed_bytes(N, K, group)
 
 
-def set_dispatch(which=0, split_k=0, waves=0):
-    _check(load().flexq_set_dispatch(which, split_k, waves))
+def set_dispatch(which=0, split_k=0, waves=0, gemm_cfg=0):
+    _check(load().flexq_set_dispatch(which, split_k, waves, gemm_cfg))
 
 
 def quant_w6(w, group=0):

@@ -10,6 +10,7 @@ namespace {
 std::atomic<int> g_force_kernel{0};
 std::atomic<int> g_force_split{0};
 std::atomic<int> g_force_waves{0};
+std::atomic<int> g_force_gemm_cfg{0};
 
 constexpr int kMaxRowBlocks = FLEXQ_WORKSPACE_COUNTER_BYTES / 4;
 constexpr int kSkinnyMaxM = 128;
@@ -136,7 +137,7 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
         a.y = y;
         a.acc_out = acc_out;
         a.split_k = 1;
-        return flexq::launch_gemm(a, st) == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
+        return flexq::launch_gemm(a, g_force_gemm_cfg.load(), st) == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
     }
     for (int m0 = 0; m0 < M; m0 += kSkinnyMaxM) {
         const int rows = M - m0 < kSkinnyMaxM ? M - m0 : kSkinnyMaxM;
@@ -285,8 +286,10 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq, co
                   workspace_bytes, stream);
 }
 
-flexq_status flexq_set_dispatch(int which, int split_k, int waves)
+flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg)
 {
+    if (gemm_cfg < 0 || gemm_cfg > 16) return FLEXQ_EINVAL;
+    g_force_gemm_cfg.store(gemm_cfg);
     if (which < 0 || which > 2 || split_k < 0 || split_k > 64) return FLEXQ_EINVAL;
     if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return FLEXQ_EINVAL;
     g_force_kernel.store(which);

@@ -34,6 +34,6 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
 // Streaming kernel, M <= 128 per launch (the caller loops over row chunks).
 hipError_t launch_skinny(const LinearArgs &a, int waves, hipStream_t st);
 // Tiled MFMA kernel for large M.
-hipError_t launch_gemm(const LinearArgs &a, hipStream_t st);
+hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st);
 
 }  // namespace flexq

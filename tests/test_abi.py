@@ -87,7 +87,7 @@ def test_other_entry_points_argument_errors():
     assert lib.flexq_unpack_w6(P16, 96, 300, 0, P16, P16, None) == -2
     assert lib.flexq_workspace_init(None, 1 << 20, None) == -1
     assert lib.flexq_workspace_init(P16, 16, None) == -5
-    assert lib.flexq_set_dispatch(3, 0, 0) == -1
-    assert lib.flexq_set_dispatch(0, 0, 5) == -1
-    assert lib.flexq_set_dispatch(0, 0, 0) == 0
+    assert lib.flexq_set_dispatch(3, 0, 0, 0) == -1
+    assert lib.flexq_set_dispatch(0, 0, 5, 0) == -1
+    assert lib.flexq_set_dispatch(0, 0, 0, 0) == 0
     assert b"shape" in lib.flexq_status_string(-2)

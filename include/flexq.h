@@ -138,7 +138,8 @@ flexq_status flexq_workspace_init(void *workspace, size_t workspace_bytes,
  * y[m,n] = fp16( float(acc[m,n]) * (sx[m]*sw[n]) ) for group 0 (the product
  * of two fp16 scales is exact in fp32), and
  * y[m,n] = fp16( sx[m] * sum_g sw[n,g]*float(acc_g[m,n]) ) in fp32 for
- * group 128.  Any M >= 1 is accepted; flexq_gemm_* pick the kernel from M,
+ * group 128.  Any M >= 1 is accepted (the tiled kernel needs (M+256)*K and
+ * 0.75*N*K below 2^32, else FLEXQ_ESHAPE); flexq_gemm_* pick the kernel from M,
  * flexq_gemv_* use the bandwidth-bound streaming kernel whenever M <= 128.
  */
 flexq_status flexq_gemm_w6a6(const void *packed, int group, const int8_t *xq,

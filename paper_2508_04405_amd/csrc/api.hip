@@ -131,6 +131,8 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     if (forced == 2) stream_kernel = false;
 
     if (!stream_kernel) {
+        // the tiled kernel addresses both operands with 32-bit buffer offsets
+        if ((long)(M + 256) * K >= (1L << 32) || (long)N * K / 4 * 3 >= (1L << 32)) return FLEXQ_ESHAPE;
         a.xq = xq;
         a.sx = sx;
         a.M = M;

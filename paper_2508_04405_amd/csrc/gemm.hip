@@ -53,6 +53,7 @@ template <int WM, int WN, int MT, int NT, bool GROUP, int WPE>
 __global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
 {
+#if defined(__HIP_DEVICE_COMPILE__)  // buffer-resource builtins exist in the device pass only
     constexpr int WAVES = WM * WN;
     constexpr int BM = WM * MT * 32;
     constexpr int BN = WN * NT * 32;
@@ -91,38 +92,43 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     // DMA load q of a stage fills LDS bytes [1024q, 1024q + 1024) = rows 8q..8q+7;
     // lane i lands at 16-byte slot i, i.e. row 8q + i/8, position i%8, and must
     // therefore FETCH the chunk the swizzle keeps at that position.
-    const int8_t *xsrc[XDMA];
+    // Buffer addressing keeps the per-stage address arithmetic on the scalar
+    // unit: a lane's offset is fixed for the whole kernel, the k offset is an
+    // SGPR, and rows beyond M fall outside the buffer and read as zero.
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.xq, 0, (unsigned)((long)M * K), 0x00020000);
+    unsigned xoff[XDMA];
 #pragma unroll
     for (int i = 0; i < XDMA; ++i) {
         const int q = wave * XDMA + i;
         const int row = 8 * q + (lane >> 3);
         const int c = (lane & 7) ^ ((row >> 1) & 7);
-        int m = bm0 + row;
-        m = m < M ? m : M - 1;
-        xsrc[i] = a.xq + (long)m * K + 16 * c;
+        xoff[i] = (unsigned)(bm0 + row) * (unsigned)K + 16u * c;
     }
     auto dma_x = [&](int kb, int buf) {
 #pragma unroll
         for (int i = 0; i < XDMA; ++i) {
             uint8_t *dst = lds + buf * XSTAGE + (wave * XDMA + i) * 1024;
-            __builtin_amdgcn_global_load_lds(
-                (const void __attribute__((address_space(1))) *)(xsrc[i] + (long)kb * FLEXQ_TILE_K),
-                (void __attribute__((address_space(3))) *)dst, 16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                xrsrc, (void __attribute__((address_space(3))) *)dst, 16, xoff[i],
+                kb * FLEXQ_TILE_K, 0, 0);
         }
     };
 
-    // ---- per-wave packed tiles ---------------------------------------------
-    const v4i *wsrc[NT];
+    // ---- per-wave packed tiles: SGPR tile offset + lane * 16 -----------------
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.packed, 0, (unsigned)((long)N * K / 4 * 3), 0x00020000);
     bool wvalid[NT];
     int wnb[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        int nb = bn0 / 32 + wn * NT + nt;
-        wvalid[nt] = nb < N / 32;
-        nb = wvalid[nt] ? nb : N / 32 - 1;
-        wnb[nt] = nb;
-        wsrc[nt] = reinterpret_cast<const v4i *>(a.packed) + (long)nb * KT * (FLEXQ_TILE_BYTES / 16);
+        wnb[nt] = bn0 / 32 + wn * NT + nt;
+        wvalid[nt] = wnb[nt] < N / 32;
+        // the SGPR offset is not range-checked: tiles past the last row block
+        // re-read the last one and are never stored
+        if (!wvalid[nt]) wnb[nt] = N / 32 - 1;
     }
+    const unsigned wlane = (unsigned)lane * 16u;
 
     v16i acc[MT][NT];
 #pragma unroll
@@ -147,7 +153,10 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
         constexpr int B = decltype(buf_tag)::value;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            wreg[B][nt] = load_packed_tile_cached(wsrc[nt] + (long)kb * (FLEXQ_TILE_BYTES / 16), lane);
+            const unsigned soff = (unsigned)(wnb[nt] * KT + kb) * FLEXQ_TILE_BYTES;
+            wreg[B][nt].q0 = (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, soff, 0);
+            wreg[B][nt].q1 = (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, soff + 1024, 0);
+            wreg[B][nt].q2 = (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, soff + 2048, 0);
             if (GROUP) gsreg[B][nt] = a.scales[((long)wnb[nt] * KT + kb) * 32 + (lane & 31)];
         }
     };
@@ -176,12 +185,19 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
         }
         const uint8_t *xs = lds + CUR * XSTAGE;
         v16i part[GROUP ? MT : 1][GROUP ? NT : 1];
+        // activation operands are read from LDS one k-step ahead of their MFMAs
+        v4i af[2][MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            af[0][mt] = *reinterpret_cast<const v4i *>(xs + lds_off(arow + 32 * mt, ahalf));
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            v4i af[MT];
+            if (j < 3) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                af[mt] = *reinterpret_cast<const v4i *>(xs + lds_off(arow + 32 * mt, 2 * j + ahalf));
+                for (int mt = 0; mt < MT; ++mt)
+                    af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
+                        xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
+            }
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 const v4i bf = unpack_kstep(wreg[CUR][nt], j);
@@ -193,9 +209,9 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
                             for (int r = 0; r < 16; ++r) part[GROUP ? mt : 0][GROUP ? nt : 0][r] = 0;
                         }
                         part[GROUP ? mt : 0][GROUP ? nt : 0] =
-                            mfma_i8(af[mt], bf, part[GROUP ? mt : 0][GROUP ? nt : 0]);
+                            mfma_i8(af[j & 1][mt], bf, part[GROUP ? mt : 0][GROUP ? nt : 0]);
                     } else {
-                        acc[mt][nt] = mfma_i8(af[mt], bf, acc[mt][nt]);
+                        acc[mt][nt] = mfma_i8(af[j & 1][mt], bf, acc[mt][nt]);
                     }
                 }
             }
@@ -231,29 +247,65 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     if (kb + 1 < KT) stage(kb + 1, std::integral_constant<int, 1>{});
 
     // ---- epilogue -----------------------------------------------------------
+    // The accumulators leave through LDS so that global stores are whole lines:
+    // each wavefront transposes one 32-row slab of its tile at a time in its own
+    // LDS region (row stride NT*32 + 8 dwords: the two half-waves of a write and
+    // the sixteen lanes of a 16-byte read each cover all banks once), then every
+    // lane owns four consecutive columns of one row, applies sx[m] * sw[n] in
+    // fp32, and sixteen lanes store one 128-byte line of fp16.
+    static_assert(NT % 2 == 0, "the epilogue reads 64-column blocks");
+    constexpr int ESTRIDE = (NT * 32 + 8) * 4;          // bytes per staged row
+    static_assert(3 * XSTAGE >= WAVES * 32 * ESTRIDE, "epilogue staging must fit the stage buffers");
+    uint8_t *stg = lds + wave * (32 * ESTRIDE);
+    const int ecol = (lane & 15) * 4;                   // first of this lane's 4 columns in a block
+    const int n_wave = bn0 + wn * NT * 32;
+    float swv[NT / 2][4];
+    bool cvalid[NT / 2];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        if (!wvalid[nt]) continue;
-        const int n = bn0 + (wn * NT + nt) * 32 + (lane & 31);
-        const float swn = GROUP ? 0.25f : h2f(a.scales[n]);
+    for (int cb = 0; cb < NT / 2; ++cb) {
+        const int n = n_wave + cb * 64 + ecol;
+        cvalid[cb] = n < N;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
+        for (int c = 0; c < 4; ++c) swv[cb][c] = GROUP ? 0.25f : h2f(a.scales[cvalid[cb] ? n + c : 0]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m_slab = bm0 + (wm * MT + mt) * 32;
+        if (m_slab >= M) break;                          // uniform: nothing below is stored
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int m = bm0 + (wm * MT + mt) * 32 + mfma_row(r, lane);
-                if (m < M) {
-                    const float sxm = h2f(a.sx[m]);
-                    if (GROUP) {
-                        a.y[(long)m * N + n] = f2h(facc[GROUP ? mt : 0][GROUP ? nt : 0][r] * swn * sxm);
-                    } else {
-                        const int q = acc[mt][nt][r] >> 2;
-                        if (a.acc_out) a.acc_out[(long)m * N + n] = q;
-                        a.y[(long)m * N + n] = f2h((float)q * (sxm * swn));
-                    }
-                }
+                const int v = GROUP ? __float_as_int(facc[GROUP ? mt : 0][GROUP ? nt : 0][r])
+                                    : (acc[mt][nt][r] >> 2);
+                *reinterpret_cast<int *>(stg + mfma_row(r, lane) * ESTRIDE +
+                                         (nt * 32 + (lane & 31)) * 4) = v;
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own region only: no barrier
+#pragma unroll
+        for (int i = 0; i < 4 * NT; ++i) {
+            const int row = (i % 8) * 4 + (lane >> 4);
+            const int cb = i / 8;                        // which 64-column block
+            const v4i q = *reinterpret_cast<const v4i *>(stg + row * ESTRIDE + (cb * 64 + ecol) * 4);
+            const int m = m_slab + row;
+            const int n = n_wave + cb * 64 + ecol;
+            if (m < M && cvalid[cb]) {
+                const float sxm = h2f(a.sx[m]);
+                uint16_t h[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    h[c] = GROUP ? f2h(__int_as_float(q[c]) * swv[cb][c] * sxm)
+                                 : f2h((float)q[c] * (sxm * swv[cb][c]));
+                uint2 out2;
+                out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
+                out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
+                *reinterpret_cast<uint2 *>(a.y + (long)m * N + n) = out2;
+                if (!GROUP && a.acc_out) *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n) = q;
             }
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next slab overwrites
     }
+#endif
 }
 
 template <int WM, int WN, int MT, int NT, bool GROUP, int WPE>
@@ -285,11 +337,10 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
     switch (cfg) {
     case 1: return launch_cfg<2, 2, 4, 4, false, 1>(a, st);   // 256x256, 4 waves, 1 wave/SIMD
     case 2: return launch_cfg<2, 4, 4, 2, false, 2>(a, st);   // 256x256, 8 waves (128x64 each)
-    case 3: return launch_cfg<4, 2, 2, 4, false, 2>(a, st);   // 256x256, 8 waves (64x128 each)
-    case 4: return launch_cfg<2, 2, 2, 4, false, 2>(a, st);   // 128x256, 4 waves, 2 workgroups/CU
     case 5: return launch_cfg<2, 2, 4, 2, false, 2>(a, st);   // 256x128, 4 waves, 2 workgroups/CU
     case 6: return launch_cfg<1, 4, 8, 2, false, 1>(a, st);   // 256x256, 4 waves side by side (256x64 each)
-    default: return launch_cfg<2, 4, 4, 2, false, 2>(a, st);
+    case 7: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);   // 128x256, 4 waves side by side, 2 workgroups/CU
+    default: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);
     }
 }
 

@@ -25,6 +25,11 @@ sys.path.insert(0, ROOT)
 METRIC = "W6A8/W6A6 GEMM TOPS (M>=1024) + decode GEMV HBM GB/s, LLaMA-2-70B linears"
 PEAK_I8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
+# Bytes fetched past L2 + written, per launch, averaged over the four layers: rocprofv3 FETCH_SIZE and
+# WRITE_SIZE runs of this script, scaled on a 1 GiB device copy (x2.000 and x1.000); the runs, the
+# raw readings and the per-layer table are in profiles/bench_llama2_70b_linears_hbm_traffic.md.
+TRAFFIC_GEMM_M4096 = 1478.6e6 + 172.0e6
+TRAFFIC_GEMV_M1 = 160.76e6 + 0.042e6
 SIGMA = 0.015
 LAYERS = [("qkv", 8192, 10240, 6), ("o", 8192, 8192, 6), ("gate_up", 8192, 57344, 6),
           ("down", 28672, 8192, 8)]          # name, K, N, activation bits
@@ -48,6 +53,9 @@ def main():
     ap.add_argument("--prefill-m", type=int, default=4096)
     ap.add_argument("--decode-m", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="only run a plain device copy of known size (for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); "
@@ -62,6 +70,16 @@ def main():
         sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.traffic_calibration:
+        nbytes = 1 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)          # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "5 copies", "bytes_read_per_copy": nbytes,
+                          "bytes_written_per_copy": nbytes}))
+        return
     fq.load()
 
     # ---- resident inputs: packed weights, fp16 activations -----------------
@@ -141,7 +159,8 @@ def main():
         "avg_launch_ms": round(gemm_s / 4 * 1e3, 4), "launches": launches,
         "per_layer_tops": {n: round(2.0 * Mp * L["N"] * L["K"] / (sum(per_layer[n]) / args.steps) / 1e12, 2)
                            for n, L in ((L["name"], L) for L in layers)},
-        "traffic": None,
+        "traffic": TRAFFIC_GEMM_M4096 if Mp == 4096 else None,
+        "algorithmic_bytes": sum(gemm_bytes(Mp, L["N"], L["K"]) for L in layers) / 4,
     }
 
     # ---- decode: weight-streaming GEMV ---------------------------------------
@@ -170,7 +189,8 @@ def main():
         "achieved": round(gbytes / gemv_s / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
         "frac": round(gbytes / gemv_s / 1e9 / PEAK_HBM_GBS, 4),
         "avg_launch_us": round(gemv_s / 4 * 1e6, 2), "launches": 4 * args.steps,
-        "bytes_per_step": int(gbytes), "traffic": None,
+        "bytes_per_step": int(gbytes), "algorithmic_bytes": gbytes / 4,
+        "traffic": TRAFFIC_GEMV_M1 if Md == 1 else None,
     }
 
     # ---- the CPU oracle on a bounded sample of the same workload --------------

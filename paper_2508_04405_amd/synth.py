@@ -48,8 +48,12 @@ def weight_rows_at(N, K, sigma, seed, rows):
     """The listed rows of W[N, K], regenerated block by block."""
     rows = np.asarray(rows, dtype=np.int64)
     out = np.empty((rows.size, K), dtype=np.float32)
+    blocks = {}
     for i, r in enumerate(rows):
-        out[i] = weight_rows(N, K, sigma, seed, int(r), int(r) + 1)[0]
+        b = int(r) // ROW_BLOCK
+        if b not in blocks:
+            blocks = {b: weight_rows(N, K, sigma, seed, b * ROW_BLOCK, min((b + 1) * ROW_BLOCK, N))}
+        out[i] = blocks[b][int(r) - b * ROW_BLOCK]
     return out
 
 

@@ -282,50 +282,105 @@ def test_repeatable():
 
 # ------------------------------------------- full-size shapes, sampled outputs
 
-FULL = [
-    # name, K, N, sigma, M list (LLaMA-2-70B linears; 7B fused gate+up for a ragged N)
-    ("70b_o", 8192, 8192, 0.015, [1, 16, 128, 1024]),
-    ("70b_down", 28672, 8192, 0.015, [1, 16, 4096]),
-    ("7b_gate_up", 4096, 22016, 0.02, [1, 8, 512]),
-]
-
-
-@pytest.mark.parametrize("name,K,N,sigma,Ms", FULL)
-def test_full_size_sampled(name, K, N, sigma, Ms):
-    seed = 4000 + K + N
-    say(f"full size {name}: generating W[{N},{K}]")
-    rng = np.random.default_rng(seed)
-    cols = np.unique(np.concatenate([[0, 31, 32, N - 1], rng.integers(0, N, 124)]))
-    # quantize + pack on the GPU in row blocks to bound host memory
+def build_packed(N, K, sigma, seed, group=0):
+    """Quantize + pack W[N,K] on the GPU in row blocks (bounds host memory)."""
     wq = torch.empty((N, K), dtype=torch.int8, device=DEV)
-    sw = torch.empty((N,), dtype=torch.float16, device=DEV)
+    sw = torch.empty((N,) if group == 0 else (N, K // 128), dtype=torch.float16, device=DEV)
     step = 4096
     for r0 in range(0, N, step):
         r1 = min(N, r0 + step)
-        q, s = fq.quant_w6(to_dev(synth.weight_rows(N, K, sigma, seed, r0, r1)))
+        q, s = fq.quant_w6(to_dev(synth.weight_rows(N, K, sigma, seed, r0, r1)), group)
         wq[r0:r1] = q
         sw[r0:r1] = s
-    packed = fq.pack_w6(wq, sw)
+    packed = fq.pack_w6(wq, sw, group)
     del wq
+    return packed
+
+
+def check_sampled(packed, N, K, sigma, seed, M, bits, group=0, prologue=False, n_rows=30, n_cols=124):
+    """Sampled rows x columns against the oracle with full-K dot products, plus
+    the size-independent property acc(-x) = -acc(x) on every output."""
+    rng = np.random.default_rng(seed + 17 * M + bits)
+    cols = np.unique(np.concatenate([[0, 31, 32, N - 1], rng.integers(0, N, n_cols)]))
+    rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, n_rows)]))
     w_cols = synth.weight_rows_at(N, K, sigma, seed, cols)
-    for M in Ms:
-        say(f"full size {name}: M={M}")
-        x = synth.activations(M, K, seed=seed + M, outlier_frac=0.01)
-        rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 30)]))
-        ref = oracle.linear(x[rows], w_cols, 8)
-        xq, sx = fq.quant_act(to_dev(x), 8)
+    x = synth.activations(M, K, seed=seed + M, outlier_frac=0.01)
+    ref = oracle.linear(x[rows], w_cols, bits, group)
+    ws = fq.make_workspace(M, N, K)
+    stream = M <= 128
+    fn = {(6, True): fq.gemv_w6a6, (8, True): fq.gemv_w6a8, (6, False): fq.gemm_w6a6,
+          (8, False): fq.gemm_w6a8}[(bits, stream)]
+    want_acc = group == 0
+    if prologue:
+        out = fn(packed, N, K, group, x_fp16=to_dev(x), want_acc=want_acc, workspace=ws)
+    else:
+        xq, sx = fq.quant_act(to_dev(x), bits)
         assert np.array_equal(xq.cpu().numpy()[rows], ref["xq"])
-        ws = fq.make_workspace(M, N, K)
-        fn = fq.gemv_w6a8 if M <= 128 else fq.gemm_w6a8
-        y, acc = fn(packed, N, K, 0, xq=xq, sx=sx, want_acc=True, workspace=ws)
-        torch.cuda.synchronize()
-        acc = acc.cpu().numpy()[np.ix_(rows, cols)]
-        y = y.cpu().numpy()[np.ix_(rows, cols)]
+        assert np.array_equal(sx.cpu().numpy().view(np.uint16)[rows], ref["sx"].view(np.uint16))
+        out = fn(packed, N, K, group, xq=xq, sx=sx, want_acc=want_acc, workspace=ws)
+    torch.cuda.synchronize()
+    y = (out[0] if want_acc else out).cpu().numpy()[np.ix_(rows, cols)]
+    if want_acc:
+        acc = out[1].cpu().numpy()[np.ix_(rows, cols)]
         assert np.array_equal(acc.astype(np.int64), ref["acc"])
         assert_y_close(y.view(np.float16), ref["y"])
-        # a property that holds at any size: negated activations negate every accumulator
-        neg = (-xq.to(torch.int16)).clamp(-128, 127).to(torch.int8)
-        _, acc2 = fn(packed, N, K, 0, xq=neg, sx=sx, want_acc=True, workspace=ws)
-        _, acc1 = fn(packed, N, K, 0, xq=xq, sx=sx, want_acc=True, workspace=ws)
-        torch.cuda.synchronize()
-        assert torch.equal(acc2, -acc1)
+        if not prologue:
+            neg = (-xq.to(torch.int16)).clamp(-128, 127).to(torch.int8)
+            _, acc2 = fn(packed, N, K, 0, xq=neg, sx=sx, want_acc=True, workspace=ws)
+            torch.cuda.synchronize()
+            assert torch.equal(acc2, -out[1])
+    else:
+        assert_y_close(y.view(np.float16), ref["y"], slack=group_slack(ref))
+
+
+FULL = [
+    # LLaMA-2-70B linears (the bench workload), then the 7B fused gate+up for a ragged N
+    ("70b_o", 8192, 8192, 0.015, [(1, 8), (16, 6), (128, 8), (1024, 6), (4096, 8)]),
+    ("70b_qkv", 8192, 10240, 0.015, [(1, 6), (16, 8), (4096, 6)]),
+    ("70b_gate_up", 8192, 57344, 0.015, [(1, 6), (4096, 6)]),
+    ("70b_down", 28672, 8192, 0.015, [(1, 8), (16, 8), (128, 6), (4096, 8)]),
+    ("7b_gate_up", 4096, 22016, 0.02, [(1, 8), (8, 8), (512, 6), (2048, 8)]),
+]
+
+
+@pytest.mark.parametrize("name,K,N,sigma,cases", FULL)
+def test_full_size_sampled(name, K, N, sigma, cases):
+    seed = 4000 + K + N
+    say(f"full size {name}: generating and packing W[{N},{K}]")
+    packed = build_packed(N, K, sigma, seed)
+    for M, bits in cases:
+        say(f"full size {name}: M={M} A{bits}")
+        check_sampled(packed, N, K, sigma, seed, M, bits)
+    M, bits = cases[-1]
+    say(f"full size {name}: M={M} A{bits} with the quantize prologue")
+    check_sampled(packed, N, K, sigma, seed, M, bits, prologue=True)
+
+
+@pytest.mark.parametrize("K,N", [(4096, 12288), (4096, 4096), (11008, 4096)])
+def test_7b_decode_all_outputs(K, N):
+    """LLaMA-2-7B decode shapes, M in {1, 8}: every output against the oracle."""
+    seed = 5000 + K + N
+    say(f"7B decode K={K} N={N}")
+    w = synth.weights(N, K, 0.02, seed)
+    packed, wq, _ = prepare(w)
+    for M in (1, 8):
+        x = synth.activations(M, K, seed=seed + M, outlier_frac=0.02)
+        ref = oracle.linear(x, w, 8)
+        if M == 1:
+            assert np.array_equal(wq.cpu().numpy(), ref["wq"])
+        xq, sx = fq.quant_act(to_dev(x), 8)
+        y, acc = run_linear(fq.gemv_w6a8, packed, N, K, 0, xq, sx, True)
+        assert np.array_equal(acc.astype(np.int64), ref["acc"])
+        assert_y_close(y.view(np.float16), ref["y"])
+
+
+@pytest.mark.parametrize("K,N", [(5120, 5120), (5120, 13824), (13824, 5120)])
+def test_13b_group128_sampled(K, N):
+    """LLaMA-2-13B linears with group-128 weight scales, batched decode M=32 and
+    prefill M=2048; outlier-heavy layers run W6A8, the others W6A6."""
+    seed = 6000 + K + N
+    say(f"13B group-128 K={K} N={N}: packing")
+    packed = build_packed(N, K, 0.02, seed, group=128)
+    for M, bits in ((32, 8), (32, 6), (2048, 6), (2048, 8)):
+        say(f"13B group-128 K={K} N={N} M={M} A{bits}")
+        check_sampled(packed, N, K, 0.02, seed, M, bits, group=128, n_rows=20, n_cols=60)

@@ -113,6 +113,11 @@ def main():
 
     def run_layer(layer, tag, events=None):
         b = layer[tag]
+        if tag == "decode":     # small batch: the GEMV call quantizes the fp16 activations itself
+            gemv = fq.gemv_w6a6 if layer["bits"] == 6 else fq.gemv_w6a8
+            gemv(layer["packed"], layer["N"], layer["K"], 0, x_fp16=b["x"], workspace=b["ws"],
+                 out=b["y"])
+            return
         fq.quant_act(b["x"], layer["bits"], out=(b["xq"], b["sx"]))
         gemm = fq.gemm_w6a6 if layer["bits"] == 6 else fq.gemm_w6a8
         if tag == "decode":
@@ -169,7 +174,8 @@ def main():
     dbytes = sum(algorithmic_bytes(Md, L["N"], L["K"]) for L in layers)
     # kernel-only rate: the same four GEMV launches back to back, no quantize pass, one event pair
     for layer in layers:
-        run_layer(layer, "decode")
+        b = layer["decode"]
+        fq.quant_act(b["x"], layer["bits"], out=(b["xq"], b["sx"]))
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()

@@ -109,7 +109,19 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
 
     hipStream_t st = (hipStream_t)stream;
     Workspace ws = carve(workspace, workspace_bytes, M, K);
-    if (x_fp16) {
+
+    const int forced = g_force_kernel.load();
+    bool stream_kernel = prefer_stream ? (M <= kSkinnyMaxM) : (M <= 64);
+    if (forced == 1) stream_kernel = true;
+    if (forced == 2) stream_kernel = false;
+
+    // Small decode batches: the streaming kernel quantizes the activations itself.
+    // (Each workgroup then scans the token's whole fp16 row, which pays off while a
+    // CU runs only a few workgroups: measured break-even near 1024 workgroups.)
+    const int ks0 = choose_split(M, N, K);
+    const bool fuse = x_fp16 && stream_kernel && (long)(N / 32) * ks0 <= 1024 &&
+                      flexq::skinny_can_fuse(M, K, ks0);
+    if (x_fp16 && !fuse) {
         if (flexq::launch_quant_act(x_fp16, M, K, act_bits, ws.xq, ws.sx, st) != hipSuccess)
             return FLEXQ_EHIP;
         xq = ws.xq;
@@ -124,11 +136,8 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     a.group = group;
     a.counters = ws.counters;
     a.partial = ws.partial;
-
-    const int forced = g_force_kernel.load();
-    bool stream_kernel = prefer_stream ? (M <= kSkinnyMaxM) : (M <= 64);
-    if (forced == 1) stream_kernel = true;
-    if (forced == 2) stream_kernel = false;
+    a.x_fp16 = fuse ? x_fp16 : nullptr;
+    a.qmax = act_bits == 6 ? 31.0f : 127.0f;
 
     if (!stream_kernel) {
         // the tiled kernel addresses both operands with 32-bit buffer offsets

@@ -19,6 +19,8 @@ struct LinearArgs {
     unsigned *counters;      // zero on entry, zero on exit
     void *partial;           // split-K partial sums
     int split_k;             // >= 1
+    const uint16_t *x_fp16;  // streaming kernel only: quantize these fp16 activations in the
+    float qmax;              // kernel (31 or 127) instead of reading xq / sx; else null
 };
 
 hipError_t launch_quant_w6(const float *w, int N, int K, int group, int8_t *wq, uint16_t *sw,
@@ -33,6 +35,8 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
 
 // Streaming kernel, M <= 128 per launch (the caller loops over row chunks).
 hipError_t launch_skinny(const LinearArgs &a, int waves, hipStream_t st);
+// True if the streaming kernel can quantize fp16 activations itself for this shape.
+bool skinny_can_fuse(int M, int K, int split_k);
 // Tiled MFMA kernel for large M.
 hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st);
 

@@ -57,12 +57,31 @@ __device__ __forceinline__ void load_stage(Stage<MT, XLDS> &s, const v4i *packed
     if (GROUP) s.gs = scales[tile_index * 32 + (lane & 31)];
 }
 
-template <int MT, bool GROUP, bool XLDS, int P, int W, int WPE>
+// Quantizer arithmetic of the fused prologue: the same operations, in the same
+// order, as the stand-alone activation quantizer (scale = fp16(absmax / qmax),
+// 1.0 if zero; code = clamp(rne(v / scale))), so both give identical codes.
+__device__ __forceinline__ void prologue_scale(float amax, float qmax, float &sf)
+{
+    const float s32 = amax / qmax;
+    sf = h2f(f2h(s32));
+    if (amax == 0.0f || sf == 0.0f) sf = 1.0f;
+}
+
+__device__ __forceinline__ unsigned prologue_code(uint16_t hbits, float sf, float qmin, float qmax)
+{
+    float q = __builtin_rintf(h2f(hbits) / sf);
+    q = fminf(fmaxf(q, qmin), qmax);
+    return (unsigned)((int)q & 0xff);
+}
+
+template <int MT, bool GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void skinny_kernel(flexq::LinearArgs a)
 {
+    static_assert(!FUSEQ || (XLDS && MT == 1), "the fused quantizer fills the LDS slice");
     __shared__ int red[W][4][64];
     __shared__ int s_last;
+    __shared__ float s_sx[32];      // FUSEQ: per-token scales made in this kernel
     extern __shared__ __attribute__((aligned(16))) uint8_t xlds[];  // XLDS: M rows of (span + 16) bytes
 
     constexpr int THREADS = 64 * W;
@@ -93,7 +112,7 @@ void skinny_kernel(flexq::LinearArgs a)
     const int xstride = span + 16;              // padded LDS row
 
     v4i xstage[XLDS ? 4 : 1];
-    if (XLDS) {
+    if (XLDS && !FUSEQ) {
         // issue the slice's global loads first so they complete ahead of the weight stream
         const int chunks_per_row = span >> 4;
         const int total = M * chunks_per_row;
@@ -108,6 +127,21 @@ void skinny_kernel(flexq::LinearArgs a)
         }
     }
 
+    // FUSEQ, small slices: this thread's share of the fp16 rows, loaded ahead of the
+    // weight stream so that the absmax does not queue behind it (loads return in order)
+    constexpr int XH = 8;
+    uint4 xh[FUSEQ ? XH : 1];
+    const int row_chunks = a.K >> 3;                     // 16-byte chunks of 8 fp16 per row
+    const bool xh_fits = FUSEQ && M * row_chunks <= XH * THREADS;
+    if (FUSEQ && xh_fits) {
+#pragma unroll
+        for (int i = 0; i < XH; ++i) {
+            const int idx = tid + i * THREADS;
+            if (idx < M * row_chunks)
+                xh[FUSEQ ? i : 0] = reinterpret_cast<const uint4 *>(a.x_fp16)[idx];
+        }
+    }
+
     Stage<MT, XLDS> st[P];
     const int tw = t0 + wave;
 #pragma unroll
@@ -117,7 +151,84 @@ void skinny_kernel(flexq::LinearArgs a)
             load_stage<MT, GROUP, XLDS>(st[p], packed, a.scales, xrow, xact, tile_base + t, t, lane);
     }
 
-    if (XLDS) {
+    if (FUSEQ) {
+        // The weight tiles above are already in flight; meanwhile quantize the
+        // activations here instead of in a separate launch.  Every workgroup
+        // scans the whole fp16 row (it is L2-resident) for the token's absmax,
+        // then quantizes only its own K range into the LDS slice.
+        const float qmax = a.qmax, qmin = -a.qmax - 1.0f;
+        auto scan = [](const uint4 &v, unsigned best) {
+            const unsigned w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                best = max(best, w4[i] & 0x7fffu);     // fp16 magnitudes order like their bits
+                best = max(best, (w4[i] >> 16) & 0x7fffu);
+            }
+            return best;
+        };
+        auto emit = [&](const uint4 &v, int m, int c) {    // chunk c of the K range of token m
+            const float sf = s_sx[m];
+            const unsigned w4[4] = {v.x, v.y, v.z, v.w};
+            unsigned out[2] = {0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned lo = prologue_code((uint16_t)(w4[i] & 0xffffu), sf, qmin, qmax);
+                const unsigned hi = prologue_code((uint16_t)(w4[i] >> 16), sf, qmin, qmax);
+                out[i >> 1] |= (lo | (hi << 8)) << (16 * (i & 1));
+            }
+            *reinterpret_cast<uint2 *>(xlds + m * xstride + 8 * c) = make_uint2(out[0], out[1]);
+        };
+        // LDS-only barrier: __syncthreads() would also wait for the weight tiles
+        auto lds_sync = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+        for (int m = 0; m < M; ++m) {
+            unsigned best = 0;
+            if (xh_fits) {
+#pragma unroll
+                for (int i = 0; i < XH; ++i) {
+                    const int idx = tid + i * THREADS;
+                    if (idx >= m * row_chunks && idx < (m + 1) * row_chunks)
+                        best = scan(xh[FUSEQ ? i : 0], best);
+                }
+            } else {
+                const uint4 *src = reinterpret_cast<const uint4 *>(a.x_fp16 + (long)m * a.K);
+                for (int c = tid; c < row_chunks; c += THREADS) best = scan(src[c], best);
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1)
+                best = max(best, (unsigned)__shfl_xor((int)best, off, 64));
+            if (lane == 0) red[wave][0][m & 3] = (int)best;
+            if ((m & 3) == 3 || m == M - 1) {
+                lds_sync();
+                if (tid <= (m & 3)) {
+                    const int mm = (m & ~3) + tid;
+                    unsigned b = 0;
+                    for (int w = 0; w < W; ++w) b = max(b, (unsigned)red[w][0][tid]);
+                    float sf;
+                    prologue_scale(h2f((uint16_t)b), qmax, sf);
+                    s_sx[mm] = sf;
+                }
+                lds_sync();
+            }
+        }
+        const int c0 = t0 * 16, c1 = t1 * 16;            // this K range in 8-element chunks
+        if (xh_fits) {
+#pragma unroll
+            for (int i = 0; i < XH; ++i) {
+                const int idx = tid + i * THREADS;
+                if (idx < M * row_chunks) {
+                    const int m = idx / row_chunks, c = idx - m * row_chunks;
+                    if (c >= c0 && c < c1) emit(xh[FUSEQ ? i : 0], m, c - c0);
+                }
+            }
+        } else {
+            const int span_chunks = c1 - c0;
+            for (int idx = tid; idx < M * span_chunks; idx += THREADS) {
+                const int m = idx / span_chunks, c = idx - m * span_chunks;
+                emit(*reinterpret_cast<const uint4 *>(a.x_fp16 + (long)m * a.K + 8L * (c0 + c)), m, c);
+            }
+        }
+        lds_sync();
+    } else if (XLDS) {
         const int chunks_per_row = span >> 4;
         const int total = M * chunks_per_row;
 #pragma unroll
@@ -220,11 +331,12 @@ void skinny_kernel(flexq::LinearArgs a)
                     }
                     if (KS == 1) {
                         if (GROUP) {
-                            a.y[(long)m * N + n] = f2h(__int_as_float(v) * 0.25f * h2f(a.sx[m]));
+                            a.y[(long)m * N + n] = f2h(__int_as_float(v) * 0.25f * (FUSEQ ? s_sx[m] : h2f(a.sx[m])));
                         } else {
                             const int qv = v >> 2;
                             if (a.acc_out) a.acc_out[(long)m * N + n] = qv;
-                            a.y[(long)m * N + n] = f2h((float)qv * (h2f(a.sx[m]) * h2f(a.scales[n])));
+                            a.y[(long)m * N + n] =
+                                f2h((float)qv * ((FUSEQ ? s_sx[m] : h2f(a.sx[m])) * h2f(a.scales[n])));
                         }
                     } else {
                         // device-coherent write-through store: nothing stays dirty in
@@ -264,7 +376,7 @@ void skinny_kernel(flexq::LinearArgs a)
             for (int k = 0; k < KS; ++k)
                 f += __int_as_float(__hip_atomic_load(&partial_i[((long)k * M + m) * N + n],
                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            a.y[(long)m * N + n] = f2h(f * 0.25f * h2f(a.sx[m]));
+            a.y[(long)m * N + n] = f2h(f * 0.25f * (FUSEQ ? s_sx[m] : h2f(a.sx[m])));
         } else {
             int v = 0;
             for (int k = 0; k < KS; ++k)
@@ -272,16 +384,16 @@ void skinny_kernel(flexq::LinearArgs a)
                                        __HIP_MEMORY_SCOPE_AGENT);
             const int q = v >> 2;
             if (a.acc_out) a.acc_out[(long)m * N + n] = q;
-            a.y[(long)m * N + n] = f2h((float)q * (h2f(a.sx[m]) * h2f(a.scales[n])));
+            a.y[(long)m * N + n] = f2h((float)q * ((FUSEQ ? s_sx[m] : h2f(a.sx[m])) * h2f(a.scales[n])));
         }
     }
 }
 
-template <int MT, bool GROUP, bool XLDS, int P, int W, int WPE>
+template <int MT, bool GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE>
 hipError_t launch_one(const flexq::LinearArgs &a, hipStream_t st)
 {
     const unsigned blocks = (unsigned)(a.N / 32) * (unsigned)a.split_k;
-    auto kern = skinny_kernel<MT, GROUP, XLDS, P, W, WPE>;
+    auto kern = skinny_kernel<MT, GROUP, XLDS, FUSEQ, P, W, WPE>;
     size_t dyn = 0;
     if (XLDS) {
         const int KT = a.K / 128;
@@ -306,27 +418,40 @@ hipError_t pick(const flexq::LinearArgs &a, int waves, hipStream_t st)
     const int KT = a.K / 128;
     const int max_tiles = (KT + a.split_k - 1) / a.split_k;
     const bool xlds = a.M <= 32 && (long)a.M * max_tiles * 128 <= kXldsBytes;
+    if (a.x_fp16) {  // fused quantize prologue: the caller checked skinny_can_fuse()
+        if (!xlds) return hipErrorInvalidValue;
+        if (waves == 16) return launch_one<1, GROUP, true, true, 4, 16, 4>(a, st);
+        if (waves == 8) return launch_one<1, GROUP, true, true, 4, 8, 4>(a, st);
+        return launch_one<1, GROUP, true, true, 4, 4, 4>(a, st);
+    }
     if (a.M <= 32) {
         if (xlds) {
-            if (waves == 16) return launch_one<1, GROUP, true, 4, 16, 4>(a, st);
-            if (waves == 8) return launch_one<1, GROUP, true, 4, 8, 4>(a, st);
-            return launch_one<1, GROUP, true, 4, 4, 4>(a, st);
+            if (waves == 16) return launch_one<1, GROUP, true, false, 4, 16, 4>(a, st);
+            if (waves == 8) return launch_one<1, GROUP, true, false, 4, 8, 4>(a, st);
+            return launch_one<1, GROUP, true, false, 4, 4, 4>(a, st);
         }
-        if (waves == 16) return launch_one<1, GROUP, false, 2, 16, 4>(a, st);
-        if (waves == 8) return launch_one<1, GROUP, false, 2, 8, 4>(a, st);
-        return launch_one<1, GROUP, false, 2, 4, 4>(a, st);
+        if (waves == 16) return launch_one<1, GROUP, false, false, 2, 16, 4>(a, st);
+        if (waves == 8) return launch_one<1, GROUP, false, false, 2, 8, 4>(a, st);
+        return launch_one<1, GROUP, false, false, 2, 4, 4>(a, st);
     }
     if (a.M <= 64) {
-        if (waves >= 8) return launch_one<2, GROUP, false, 2, 8, 2>(a, st);
-        return launch_one<2, GROUP, false, 2, 4, 2>(a, st);
+        if (waves >= 8) return launch_one<2, GROUP, false, false, 2, 8, 2>(a, st);
+        return launch_one<2, GROUP, false, false, 2, 4, 2>(a, st);
     }
-    if (waves >= 8) return launch_one<4, GROUP, false, 1, 8, 2>(a, st);
-    return launch_one<4, GROUP, false, 1, 4, 2>(a, st);
+    if (waves >= 8) return launch_one<4, GROUP, false, false, 1, 8, 2>(a, st);
+    return launch_one<4, GROUP, false, false, 1, 4, 2>(a, st);
 }
 
 }  // namespace
 
 namespace flexq {
+
+bool skinny_can_fuse(int M, int K, int split_k)
+{
+    const int KT = K / 128;
+    const int max_tiles = (KT + split_k - 1) / split_k;
+    return M <= 8 && (long)M * max_tiles * 128 <= kXldsBytes;
+}
 
 hipError_t launch_skinny(const LinearArgs &a, int waves, hipStream_t st)
 {

@@ -248,7 +248,7 @@ def test_linear_group128(M, K, N, kernel):
 
 
 @pytest.mark.parametrize("bits", [6, 8])
-@pytest.mark.parametrize("M", [1, 16, 200])
+@pytest.mark.parametrize("M", [1, 3, 8, 16, 200])
 def test_quantize_prologue(bits, M):
     say(f"prologue A{bits} M={M}")
     K, N = 1024, 256
@@ -256,11 +256,19 @@ def test_quantize_prologue(bits, M):
     x = synth.activations(M, K, seed=12, outlier_frac=0.01)
     ref = oracle.linear(x, w, bits)
     packed, _, _ = prepare(w)
+    if M > 1:
+        x[M - 1, :] = 0                          # a token of zeros: scale 1.0, zero output
+    ref = oracle.linear(x, w, bits)
     fn = {6: fq.gemm_w6a6, 8: fq.gemm_w6a8}[bits]
-    y, acc = fn(packed, N, K, 0, x_fp16=to_dev(x), want_acc=True)
-    torch.cuda.synchronize()
-    assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
-    assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
+    for split in (0, 2):                         # M <= 8: quantized inside the streaming kernel
+        fq.set_dispatch(0, split, 0, 0)
+        try:
+            y, acc = fn(packed, N, K, 0, x_fp16=to_dev(x), want_acc=True)
+            torch.cuda.synchronize()
+        finally:
+            fq.set_dispatch(0, 0, 0, 0)
+        assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
+        assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
     # the two activation widths really differ
     other = oracle.linear(x, w, 14 - bits)
     assert not np.array_equal(other["acc"], ref["acc"])

@@ -252,22 +252,21 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     // LDS region (row stride NT*32 + 8 dwords: the two half-waves of a write and
     // the sixteen lanes of a 16-byte read each cover all banks once), then every
     // lane owns four consecutive columns of one row, applies sx[m] * sw[n] in
-    // fp32, and sixteen lanes store one 128-byte line of fp16.
-    static_assert(NT % 2 == 0, "the epilogue reads 64-column blocks");
+    // fp32, and the lanes of a row store whole 64- or 128-byte runs of fp16.
     constexpr int ESTRIDE = (NT * 32 + 8) * 4;          // bytes per staged row
     static_assert(3 * XSTAGE >= WAVES * 32 * ESTRIDE, "epilogue staging must fit the stage buffers");
+    constexpr int LPR = NT * 8;                          // lanes per staged row (4 columns each)
+    constexpr int RPI = 64 / LPR;                        // rows per read instruction
+    static_assert(64 % LPR == 0, "a read instruction covers whole rows");
     uint8_t *stg = lds + wave * (32 * ESTRIDE);
-    const int ecol = (lane & 15) * 4;                   // first of this lane's 4 columns in a block
+    const int ecol = (lane % LPR) * 4;                  // first of this lane's 4 columns
+    const int erow = lane / LPR;
     const int n_wave = bn0 + wn * NT * 32;
-    float swv[NT / 2][4];
-    bool cvalid[NT / 2];
+    const int n_lane = n_wave + ecol;
+    const bool cvalid = n_lane < N;
+    float swv[4];
 #pragma unroll
-    for (int cb = 0; cb < NT / 2; ++cb) {
-        const int n = n_wave + cb * 64 + ecol;
-        cvalid[cb] = n < N;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) swv[cb][c] = GROUP ? 0.25f : h2f(a.scales[cvalid[cb] ? n + c : 0]);
-    }
+    for (int c = 0; c < 4; ++c) swv[c] = GROUP ? 0.25f : h2f(a.scales[cvalid ? n_lane + c : 0]);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m_slab = bm0 + (wm * MT + mt) * 32;
@@ -283,24 +282,22 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own region only: no barrier
 #pragma unroll
-        for (int i = 0; i < 4 * NT; ++i) {
-            const int row = (i % 8) * 4 + (lane >> 4);
-            const int cb = i / 8;                        // which 64-column block
-            const v4i q = *reinterpret_cast<const v4i *>(stg + row * ESTRIDE + (cb * 64 + ecol) * 4);
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = i * RPI + erow;
+            const v4i q = *reinterpret_cast<const v4i *>(stg + row * ESTRIDE + ecol * 4);
             const int m = m_slab + row;
-            const int n = n_wave + cb * 64 + ecol;
-            if (m < M && cvalid[cb]) {
+            if (m < M && cvalid) {
                 const float sxm = h2f(a.sx[m]);
                 uint16_t h[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    h[c] = GROUP ? f2h(__int_as_float(q[c]) * swv[cb][c] * sxm)
-                                 : f2h((float)q[c] * (sxm * swv[cb][c]));
+                    h[c] = GROUP ? f2h(__int_as_float(q[c]) * swv[c] * sxm)
+                                 : f2h((float)q[c] * (sxm * swv[c]));
                 uint2 out2;
                 out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
                 out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
-                *reinterpret_cast<uint2 *>(a.y + (long)m * N + n) = out2;
-                if (!GROUP && a.acc_out) *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n) = q;
+                *reinterpret_cast<uint2 *>(a.y + (long)m * N + n_lane) = out2;
+                if (!GROUP && a.acc_out) *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n_lane) = q;
             }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next slab overwrites
@@ -334,12 +331,22 @@ namespace flexq {
 hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
 {
     if (a.group != 0) return launch_cfg<2, 2, 2, 2, true, 1>(a, st);
+    if (cfg == 0) {
+        // 128x256 tiles (two workgroups per CU) are the most efficient once the chip
+        // is full of them; while twice as many 128x128 tiles still fit at once (three
+        // per CU, 768 in all) those fill it better.  Measured on MI355X for the N, K
+        // of LLaMA-2 linears.
+        const long tiles_big = (long)((a.M + 127) / 128) * ((a.N + 255) / 256);
+        cfg = tiles_big <= 384 ? 8 : 7;
+    }
     switch (cfg) {
     case 1: return launch_cfg<2, 2, 4, 4, false, 1>(a, st);   // 256x256, 4 waves, 1 wave/SIMD
     case 2: return launch_cfg<2, 4, 4, 2, false, 2>(a, st);   // 256x256, 8 waves (128x64 each)
     case 5: return launch_cfg<2, 2, 4, 2, false, 2>(a, st);   // 256x128, 4 waves, 2 workgroups/CU
     case 6: return launch_cfg<1, 4, 8, 2, false, 1>(a, st);   // 256x256, 4 waves side by side (256x64 each)
     case 7: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);   // 128x256, 4 waves side by side, 2 workgroups/CU
+    case 8: return launch_cfg<1, 4, 4, 1, false, 3>(a, st);   // 128x128, 4 waves side by side, 3 workgroups/CU
+    case 9: return launch_cfg<1, 2, 4, 2, false, 2>(a, st);   // 128x128, 2 waves side by side
     default: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);
     }
 }

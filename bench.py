@@ -199,6 +199,39 @@ def main():
         "traffic": TRAFFIC_GEMV_M1 if Md == 1 else None,
     }
 
+    # ---- measured ceilings on this machine (context for the fractions above) ------
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    for layer in layers:                                   # warm-up
+        fq.probe_hbm_read(layer["packed"], sink)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        for layer in layers:                               # 642 MB per pass: cold, like the GEMV
+            fq.probe_hbm_read(layer["packed"], sink)
+    e1.record()
+    torch.cuda.synchronize()
+    read_gbs = sum(L["packed"].numel() for L in layers) * args.steps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    a_ops, b_ops = layers[0]["prefill"]["xq"], layers[0]["packed"]
+    fq.probe_mfma_i8(a_ops, b_ops, 50, 512, sink)
+    torch.cuda.synchronize()
+    iters = 4000                                           # ~1 ms, like one GEMM launch
+    e0.record()
+    fq.probe_mfma_i8(a_ops, b_ops, iters, 512, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_tops = 2.0 * 32768 * 16 * iters * 4 * 512 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    roofline["measured_ceiling"] = {
+        "value": round(mfma_tops, 1), "unit": "TOP/s",
+        "what": "v_mfma_i32_32x32x32_i8 only, operands = this workload's activation codes and "
+                "weight bytes held in registers (the clock drops with switching activity)",
+        "frac_of_ceiling": round(gemm_tops / mfma_tops, 4)}
+    roofline_decode["measured_ceiling"] = {
+        "value": round(read_gbs, 1), "unit": "GB/s",
+        "what": "read-only kernel over the same four packed weight buffers",
+        "frac_of_ceiling": round(roofline_decode["achieved"] / read_gbs, 4)}
+
     # ---- the CPU oracle on a bounded sample of the same workload --------------
     cpu = None
     if not args.no_cpu_baseline:

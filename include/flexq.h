@@ -173,6 +173,29 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq,
  */
 flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg);
 
+/*
+ * Measurement helpers (no arithmetic of the method): the ceilings a roofline
+ * fraction can be read against on the machine at hand.
+ *
+ * flexq_probe_hbm_read: a kernel that only reads `bytes` bytes at `src` (dev,
+ * 16-byte aligned) with 16-byte loads, 12 KiB in flight per wavefront.  bytes /
+ * its duration is the read bandwidth a streaming kernel can reach at that size.
+ *
+ * flexq_probe_mfma_i8: `workgroups` workgroups of four wavefronts each issue
+ * iters * 16 independent v_mfma_i32_32x32x32_i8 on operands held in registers,
+ * taken from the first 16 KiB at a_operands (int8 activation codes) and
+ * b_operands (packed weight bytes, low two bits cleared as the kernels do).
+ * 2 * 32768 * 16 * iters * 4 * workgroups / its duration is the int8 rate the
+ * matrix pipe sustains on such data.
+ *
+ * `sink` (dev, 4 bytes) is never written in practice; it keeps the work alive.
+ */
+flexq_status flexq_probe_hbm_read(const void *src, size_t bytes, void *sink,
+                                  void *stream);
+flexq_status flexq_probe_mfma_i8(const void *a_operands, const void *b_operands,
+                                 int iters, int workgroups, void *sink,
+                                 void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -51,6 +51,10 @@ def load():
         fn = getattr(lib, name)
         fn.restype = c_int
         fn.argtypes = [vp, c_int, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp, c_size, vp]
+    lib.flexq_probe_hbm_read.restype = c_int
+    lib.flexq_probe_hbm_read.argtypes = [vp, c_size, vp, vp]
+    lib.flexq_probe_mfma_i8.restype = c_int
+    lib.flexq_probe_mfma_i8.argtypes = [vp, vp, c_int, c_int, vp, vp]
     lib.flexq_set_dispatch.restype = c_int
     lib.flexq_set_dispatch.argtypes = [c_int, c_int, c_int, c_int]
     _lib = lib
@@ -85,6 +89,20 @@ def packed_bytes(N, K, group=0):
 
 def set_dispatch(which=0, split_k=0, waves=0, gemm_cfg=0):
     _check(load().flexq_set_dispatch(which, split_k, waves, gemm_cfg))
+
+
+def probe_hbm_read(buf, sink):
+    """Enqueue the read-only streaming kernel over `buf` (any dtype, contiguous)."""
+    _check(load().flexq_probe_hbm_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink),
+                                       _stream()))
+
+
+def probe_mfma_i8(a_operands, b_operands, iters, workgroups, sink):
+    """Enqueue the MFMA-only kernel; operands are read from the first 16 KiB of each buffer."""
+    assert a_operands.numel() * a_operands.element_size() >= 16384
+    assert b_operands.numel() * b_operands.element_size() >= 16384
+    _check(load().flexq_probe_mfma_i8(_ptr(a_operands), _ptr(b_operands), iters, workgroups,
+                                      _ptr(sink), _stream()))
 
 
 def quant_w6(w, group=0):

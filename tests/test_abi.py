@@ -87,6 +87,9 @@ def test_other_entry_points_argument_errors():
     assert lib.flexq_unpack_w6(P16, 96, 300, 0, P16, P16, None) == -2
     assert lib.flexq_workspace_init(None, 1 << 20, None) == -1
     assert lib.flexq_workspace_init(P16, 16, None) == -5
+    assert lib.flexq_probe_hbm_read(None, 4096, P16, None) == -1
+    assert lib.flexq_probe_hbm_read(ODD, 4096, P16, None) == -3
+    assert lib.flexq_probe_mfma_i8(P16, P16, 0, 1, P16, None) == -1
     assert lib.flexq_set_dispatch(3, 0, 0, 0) == -1
     assert lib.flexq_set_dispatch(0, 0, 5, 0) == -1
     assert lib.flexq_set_dispatch(0, 0, 0, 0) == 0

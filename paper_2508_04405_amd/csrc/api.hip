@@ -54,6 +54,30 @@ int choose_split(int M, int N, int K)
     return ks;
 }
 
+// K splits of the tiled kernel for mid-size M: with fewer than one 128x128 output
+// tile per CU the blocks are long latency chains on a mostly idle chip, so K is
+// split until there is about one block per CU (measured optimum on MI355X: 4 splits
+// at M = 128, 2 at M = 256), keeping at least four 128-k stages per block and the
+// partial-sum traffic (8 bytes per split and output) under the weight bytes.
+int choose_gemm_split(int M, int N, int K)
+{
+    const int kt = K / 128;
+    int ks;
+    if (g_force_split.load() > 0) {
+        ks = g_force_split.load();
+    } else {
+        const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+        if (tiles >= 256) return 1;
+        ks = (int)(256 / tiles);
+        if (ks > kt / 4) ks = kt / 4;
+        const int by_traffic = K / (11 * M);
+        if (ks > by_traffic) ks = by_traffic;
+        if (ks > 16) ks = 16;
+    }
+    if (ks > kt) ks = kt;
+    return ks < 1 ? 1 : ks;
+}
+
 // Wavefronts per workgroup of the streaming kernel.
 int choose_waves(int M, int N, int K, int ks)
 {
@@ -111,7 +135,9 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     Workspace ws = carve(workspace, workspace_bytes, M, K);
 
     const int forced = g_force_kernel.load();
-    bool stream_kernel = prefer_stream ? (M <= kSkinnyMaxM) : (M <= 64);
+    // measured cross-over between the streaming kernel and the tiled kernel with K splits
+    (void)prefer_stream;
+    bool stream_kernel = M <= 64;
     if (forced == 1) stream_kernel = true;
     if (forced == 2) stream_kernel = false;
 
@@ -147,7 +173,12 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
         a.M = M;
         a.y = y;
         a.acc_out = acc_out;
-        a.split_k = 1;
+        a.split_k = choose_gemm_split(M, N, K);
+        const size_t per_split = (size_t)M * N * 4;
+        if ((size_t)a.split_k * per_split > ws.partial_capacity)
+            a.split_k = (int)(ws.partial_capacity / per_split);
+        if ((size_t)a.split_k * per_split >= ((size_t)1 << 32)) a.split_k = 1;   // 32-bit buffer offsets
+        if (a.split_k < 2) a.split_k = 1;
         return flexq::launch_gemm(a, g_force_gemm_cfg.load(), st) == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
     }
     for (int m0 = 0; m0 < M; m0 += kSkinnyMaxM) {
@@ -249,6 +280,11 @@ size_t flexq_workspace_bytes(int M, int N, int K)
     const int top = M < kSkinnyMaxM ? M : kSkinnyMaxM;
     for (int m = 1; m <= top; ++m) {
         const size_t b = (size_t)choose_split(m, N, K) * m * N * 4;
+        if (b > partial) partial = b;
+    }
+    {
+        const int gs = choose_gemm_split(M, N, K);
+        const size_t b = gs > 1 ? (size_t)gs * M * N * 4 : 0;
         if (b > partial) partial = b;
     }
     return fixed_bytes(M, K) + round_up(partial, 256);

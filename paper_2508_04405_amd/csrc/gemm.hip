@@ -71,8 +71,14 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     const int KT = K / FLEXQ_TILE_K;
 
     // ---- XCD-aware tile choice: blocks 8 apart share an XCD ---------------
+    // K splits of one output tile are adjacent block ids
+    const int KS = a.split_k;
+    const int ksplit = blockIdx.x % KS;
+    const int kb0 = (int)((long)ksplit * KT / KS);              // first 128-k stage of this block
+    const int KN = (int)((long)(ksplit + 1) * KT / KS) - kb0;   // and how many
     const int nblk = tiles_m * tiles_n;
-    int bid = blockIdx.x;
+    int bid = blockIdx.x / KS;
+    const int tile_id = bid;
     {
         const int per = nblk / 8, rem = nblk % 8;
         const int xcd = bid % 8, slot = bid / 8;
@@ -111,7 +117,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             uint8_t *dst = lds + buf * XSTAGE + (wave * XDMA + i) * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 xrsrc, (void __attribute__((address_space(3))) *)dst, 16, xoff[i],
-                kb * FLEXQ_TILE_K, 0, 0);
+                (kb0 + kb) * FLEXQ_TILE_K, 0, 0);
         }
     };
 
@@ -153,18 +159,18 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
         constexpr int B = decltype(buf_tag)::value;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const unsigned soff = (unsigned)(wnb[nt] * KT + kb) * FLEXQ_TILE_BYTES;
+            const unsigned soff = (unsigned)(wnb[nt] * KT + kb0 + kb) * FLEXQ_TILE_BYTES;
             wreg[B][nt].q0 = (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, soff, 0);
             wreg[B][nt].q1 = (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, soff + 1024, 0);
             wreg[B][nt].q2 = (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, soff + 2048, 0);
-            if (GROUP) gsreg[B][nt] = a.scales[((long)wnb[nt] * KT + kb) * 32 + (lane & 31)];
+            if (GROUP) gsreg[B][nt] = a.scales[((long)wnb[nt] * KT + kb0 + kb) * 32 + (lane & 31)];
         }
     };
 
     // prologue: stages 0 and 1 in flight, stage 0 landed
     dma_x(0, 0);
     load_w(0, std::integral_constant<int, 0>{});
-    if (KT > 1) {
+    if (KN > 1) {
         dma_x(1, 1);
         load_w(1, std::integral_constant<int, 1>{});
     }
@@ -178,7 +184,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     auto stage = [&](int kb, auto cur_tag) {
         constexpr int CUR = decltype(cur_tag)::value;
         constexpr int NXT2 = (CUR + 2) % 3;
-        const bool more2 = kb + 2 < KT;
+        const bool more2 = kb + 2 < KN;
         if (more2) {  // two stages ahead: that buffer was last read in stage kb - 1
             dma_x(kb + 2, NXT2);
             load_w(kb + 2, std::integral_constant<int, NXT2>{});
@@ -238,13 +244,13 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     };
 
     int kb = 0;
-    for (; kb + 2 < KT; kb += 3) {
+    for (; kb + 2 < KN; kb += 3) {
         stage(kb, std::integral_constant<int, 0>{});
         stage(kb + 1, std::integral_constant<int, 1>{});
         stage(kb + 2, std::integral_constant<int, 2>{});
     }
-    if (kb < KT) stage(kb, std::integral_constant<int, 0>{});
-    if (kb + 1 < KT) stage(kb + 1, std::integral_constant<int, 1>{});
+    if (kb < KN) stage(kb, std::integral_constant<int, 0>{});
+    if (kb + 1 < KN) stage(kb + 1, std::integral_constant<int, 1>{});
 
     // ---- epilogue -----------------------------------------------------------
     // The accumulators leave through LDS so that global stores are whole lines:
@@ -267,6 +273,24 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     float swv[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) swv[c] = GROUP ? 0.25f : h2f(a.scales[cvalid ? n_lane + c : 0]);
+    // scale and store four columns of row m (q: exact int32 sums, or fp32 group sums)
+    auto finish = [&](const v4i &q, int m) {
+        const float sxm = h2f(a.sx[m]);
+        uint16_t h[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            h[c] = GROUP ? f2h(__int_as_float(q[c]) * swv[c] * sxm) : f2h((float)q[c] * (sxm * swv[c]));
+        uint2 out2;
+        out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
+        out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
+        *reinterpret_cast<uint2 *>(a.y + (long)m * N + n_lane) = out2;
+        if (!GROUP && a.acc_out) *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n_lane) = q;
+    };
+    // split-K partial sums [split][M][N] int32, addressed as a buffer; cache policy
+    // bit 4 = sc1 = device scope: the access goes to memory all XCDs share
+    constexpr int kScopeAgent = 16;
+    const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
+        a.partial, 0, (unsigned)((long)KS * M * N * 4), 0x00020000);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m_slab = bm0 + (wm * MT + mt) * 32;
@@ -287,20 +311,73 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             const v4i q = *reinterpret_cast<const v4i *>(stg + row * ESTRIDE + ecol * 4);
             const int m = m_slab + row;
             if (m < M && cvalid) {
-                const float sxm = h2f(a.sx[m]);
-                uint16_t h[4];
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    h[c] = GROUP ? f2h(__int_as_float(q[c]) * swv[c] * sxm)
-                                 : f2h((float)q[c] * (sxm * swv[c]));
-                uint2 out2;
-                out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
-                out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
-                *reinterpret_cast<uint2 *>(a.y + (long)m * N + n_lane) = out2;
-                if (!GROUP && a.acc_out) *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n_lane) = q;
+                if (KS == 1) {
+                    finish(q, m);
+                } else {
+                    // device-scope (sc1) 16-byte store: see the hand-off below
+                    const unsigned off = (unsigned)((((long)ksplit * M + m) * N + n_lane) * 4);
+                    __builtin_amdgcn_raw_buffer_store_b128((v4u)q, prsrc, off, 0, kScopeAgent);
+                }
             }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next slab overwrites
+    }
+    if (KS == 1) return;
+
+    // ---- K splits meet: the last block of this tile to arrive adds the partial
+    // sums in split order and stores the tile.  Partial sums were written with
+    // device-scope stores; once they are acknowledged (vmcnt 0) the barrier plus
+    // one relaxed device-scope counter increment publishes them, and the reader
+    // uses device-scope loads -- no L2 write-back / invalidate is needed.
+    __shared__ int s_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
+    if (tid == 0) {
+        const unsigned prev = __hip_atomic_fetch_add(&a.counters[tile_id], 1u, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (prev == (unsigned)(KS - 1));
+        if (s_last) __hip_atomic_store(&a.counters[tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    lds_barrier();
+    if (!s_last) return;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m_slab = bm0 + (wm * MT + mt) * 32;
+        if (m_slab >= M) break;
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int m = m_slab + i * RPI + erow;
+            if (m < M && cvalid) {
+                v4i q = {0, 0, 0, 0};
+                float f[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                for (int k0 = 0; k0 < KS; k0 += 4) {       // four independent loads in flight
+                    v4i v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int k = k0 + u < KS ? k0 + u : KS - 1;
+                        const unsigned off = (unsigned)((((long)k * M + m) * N + n_lane) * 4);
+                        v[u] = (v4i)__builtin_amdgcn_raw_buffer_load_b128(prsrc, off, 0, kScopeAgent);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        if (k0 + u < KS) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                if (GROUP)
+                                    f[c] += __int_as_float(v[u][c]);
+                                else
+                                    q[c] += v[u][c];
+                            }
+                        }
+                    }
+                }
+                if (GROUP) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) q[c] = __float_as_int(f[c]);
+                }
+                finish(q, m);
+            }
+        }
     }
 #endif
 }
@@ -319,8 +396,9 @@ hipError_t launch_cfg(const flexq::LinearArgs &a, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WN), lds_bytes, st, a,
-                       tiles_m, tiles_n);
+    if (a.split_k > 1 && tiles_m * tiles_n > 4096) return hipErrorInvalidValue;  // one counter per tile
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n * a.split_k)), dim3(64 * WM * WN),
+                       lds_bytes, st, a, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
@@ -330,7 +408,11 @@ namespace flexq {
 
 hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
 {
+    // Group-128 scales cost two vector operations per accumulator and group (int -> float,
+    // multiply-add): the vector unit, not the tile shape, bounds that mode (measured: every
+    // tile shape within 3 %).
     if (a.group != 0) return launch_cfg<2, 2, 2, 2, true, 1>(a, st);
+    if (a.split_k > 1 && cfg == 0) cfg = 8;   // K splits are chosen for 128x128 tiles
     if (cfg == 0) {
         // 128x256 tiles (two workgroups per CU) are the most efficient once the chip
         // is full of them; while twice as many 128x128 tiles still fit at once (three
@@ -347,6 +429,7 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
     case 7: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);   // 128x256, 4 waves side by side, 2 workgroups/CU
     case 8: return launch_cfg<1, 4, 4, 1, false, 3>(a, st);   // 128x128, 4 waves side by side, 3 workgroups/CU
     case 9: return launch_cfg<1, 2, 4, 2, false, 2>(a, st);   // 128x128, 2 waves side by side
+    case 10: return launch_cfg<1, 8, 8, 1, false, 2>(a, st);  // 256x256, 8 waves side by side (256x32 each)
     default: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);
     }
 }

@@ -198,6 +198,32 @@ def test_stream_kernel_k_splits(split, M, waves):
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
+@pytest.mark.parametrize("split", [2, 3, 7])
+@pytest.mark.parametrize("M", [5, 100, 260])
+@pytest.mark.parametrize("group", [0, 128])
+def test_tiled_kernel_k_splits(split, M, group):
+    say(f"tiled kernel split={split} M={M} group={group}")
+    K, N = 1408, 320                            # 11 stages: uneven splits; ragged tiles in M and N
+    w = synth.weights(N, K, 0.02, seed=17)
+    x = synth.activations(M, K, seed=18, outlier_frac=0.02)
+    ref = oracle.linear(x, w, 8, group)
+    packed, _, _ = prepare(w, group)
+    xq, sx = fq.quant_act(to_dev(x), 8)
+    ws = fq.make_workspace(M, N, K, extra=split * M * N * 4)
+    fq.set_dispatch(2, split, 0, 0)
+    try:
+        for _ in range(2):                      # counters must return to zero each call
+            y, acc = run_linear(fq.gemm_w6a8, packed, N, K, group, xq, sx, group == 0, ws)
+            if group == 0:
+                assert np.array_equal(acc.astype(np.int64), ref["acc"])
+                assert_y_close(y.view(np.float16), ref["y"])
+            else:
+                assert_y_close(y.view(np.float16), ref["y"], slack=group_slack(ref))
+    finally:
+        fq.set_dispatch(0, 0, 0, 0)
+    assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
+
+
 @pytest.mark.parametrize("kernel", ["stream", "tiled"])
 def test_extreme_codes_exact(kernel):
     say(f"extreme codes kernel={kernel}")

@@ -29,10 +29,11 @@ flexq_status check_shape(int N, int K, int group)
 size_t scale_count(int N, int K, int group) { return group == 0 ? (size_t)N : (size_t)N * (K / 128); }
 
 // K splits of the streaming kernel.  Measured on MI355X: one workgroup of
-// eight wavefronts per 32-row block streams fastest as soon as there is at least
-// one such workgroup per CU; splitting K further only adds the cross-workgroup
-// hand-off.  So split just enough to give each of the 256 CUs a workgroup, keep
-// at least two tiles per wavefront, and keep the partial-sum traffic (8 bytes
+// eight wavefronts per 32-row block streams fastest as soon as there are enough
+// of them for half the CUs (at N = 4096, 128 blocks unsplit beat 256 split ones:
+// the cross-workgroup hand-off costs more than the idle CUs); splitting K
+// further only adds hand-offs.  So split just enough to reach 128 workgroups,
+// keep at least two tiles per wavefront, and keep the partial-sum traffic (8 bytes
 // per split, token and column) under a ninth of the weight stream.
 int choose_split(int M, int N, int K)
 {
@@ -43,7 +44,7 @@ int choose_split(int M, int N, int K)
         ks = forced;
     } else {
         const int row_blocks = N / 32;
-        ks = (256 + row_blocks - 1) / row_blocks;
+        ks = (128 + row_blocks - 1) / row_blocks;
         const int by_traffic = (int)((long)K / (96L * M));
         if (ks > by_traffic) ks = by_traffic;
         if (ks > kt / 16) ks = kt / 16;

@@ -314,6 +314,45 @@ def test_repeatable():
     assert torch.equal(a, b)
 
 
+def test_graph_replay_matches_eager():
+    """The calls only enqueue kernels (no allocation, no memset), so they can be
+    captured in a HIP graph; replays with fresh inputs must equal eager runs."""
+    say("graph capture / replay")
+    K, N = 2048, 1024                            # 32 row blocks: the streaming kernel splits K
+    w = synth.weights(N, K, 0.02, seed=31)
+    packed, _, _ = prepare(w)
+    cases = []
+    for M in (1, 300):
+        x = to_dev(synth.activations(M, K, seed=32 + M))
+        cases.append({"M": M, "x": x, "y": torch.empty((M, N), dtype=torch.float16, device=DEV),
+                      "ws": fq.make_workspace(M, N, K)})
+
+    def enqueue():
+        for c in cases:
+            fq.gemm_w6a8(packed, N, K, 0, x_fp16=c["x"], workspace=c["ws"], out=c["y"])
+
+    enqueue()
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            enqueue()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for c in cases:
+            c["x"].copy_(to_dev(synth.activations(c["M"], K, seed=100 * rep + c["M"])))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [c["y"].clone() for c in cases]
+        enqueue()                                # eager work between the replays
+        torch.cuda.synchronize()
+        for c, g in zip(cases, got):
+            assert torch.equal(c["y"], g), (rep, c["M"])
+        ref = oracle.linear(cases[0]["x"].cpu().numpy(), w, 8)
+        assert_y_close(got[0].cpu().numpy().view(np.float16), ref["y"])
+
+
 # ------------------------------------------- full-size shapes, sampled outputs
 
 def build_packed(N, K, sigma, seed, group=0):

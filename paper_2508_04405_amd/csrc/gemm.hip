@@ -3,19 +3,26 @@
 // Large M makes the layer a dense contraction, so the matrix pipe is the
 // roofline (the paper measures no batch above 8; Section 4.3.6 describes its
 // pipeline, which this kernel re-creates for CDNA4 in its own way):
-//   - activations (int8) go global -> registers -> LDS, double buffered, one
-//     128-k stage ahead, in an XOR-swizzled row layout so that both the 16-byte
-//     writes and the 16-byte MFMA-operand reads are bank-conflict free;
+//   - activations (int8) go global -> LDS by DMA (buffer loads with the lds
+//     bit: no registers in between), three stage buffers of 128 k, two stages
+//     ahead, in an XOR-swizzled row layout so that the 16-byte MFMA-operand
+//     reads are bank-conflict free;
 //   - packed weights never touch LDS: each wavefront loads the 3 KiB tiles of
-//     its own columns straight into registers one stage ahead and expands them
+//     its own columns straight into registers two stages ahead and expands them
 //     to int8 (nine VALU operations per 16 weights) in the shadow of the MFMAs;
 //     an expanded operand is reused by MT MFMAs, which is what keeps the VALU
 //     work hidden;
-//   - the epilogue shifts the 4x accumulators back, applies sx[m]*sw[n] in
-//     fp32 and stores fp16 (Section 4.3.4, fused dequantization).
-// Workgroup ids are remapped so that the workgroups an XCD runs at one time
-// form a compact block of output tiles and share operand panels in that XCD's
-// L2.
+//   - stages are handed over with counted s_waitcnt vmcnt and a raw s_barrier;
+//   - the epilogue shifts the 4x accumulators back, transposes them through
+//     LDS, applies sx[m]*sw[n] in fp32 and stores whole lines of fp16 (Section
+//     4.3.4, fused dequantization; Section 4.3.2, coalesced write-back);
+//   - for mid-size M, K can be split over several workgroups per output tile;
+//     the last one to finish adds the partial sums (exact for int32).
+// The default shape is a 128x256 tile per workgroup of four wavefronts, two
+// workgroups per CU: what one workgroup loses at its barrier, prologue and
+// epilogue the other fills with MFMAs.  Workgroup ids are remapped so that the
+// workgroups an XCD runs at one time form a compact block of output tiles and
+// share operand panels in that XCD's L2.
 #include "flexq_device.h"
 #include "flexq_kernels.h"
 #include <type_traits>

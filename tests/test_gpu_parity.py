@@ -314,6 +314,39 @@ def test_repeatable():
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("kernel", ["stream", "tiled"])
+@pytest.mark.parametrize("M,K,N", [(1, 128, 32), (2, 128, 64), (1, 65536, 32), (130, 65536, 32)])
+def test_smallest_and_longest_shapes(kernel, M, K, N):
+    """The smallest legal shape (one tile) and the longest legal reduction
+    (K = 65536), the latter with the extreme codes that maximize |acc|."""
+    say(f"edge shapes M={M} K={K} N={N} kernel={kernel}")
+    rng = np.random.default_rng(K + N + M)
+    if K == 65536:
+        wq = np.full((N, K), -32, dtype=np.int8)
+        wq[1] = 31
+        wq[2] = rng.integers(-32, 32, K)
+        xq = np.full((M, K), -128, dtype=np.int8)
+        if M > 1:
+            xq[1] = rng.integers(-128, 128, K)
+    else:
+        wq = rng.integers(-32, 32, (N, K)).astype(np.int8)
+        xq = rng.integers(-128, 128, (M, K)).astype(np.int8)
+    sw = rng.uniform(1e-4, 1e-3, N).astype(np.float16)
+    sx = rng.uniform(1e-3, 1e-2, M).astype(np.float16)
+    packed = fq.pack_w6(to_dev(wq), to_dev(sw))
+    acc_ref = oracle.matmul(xq, wq)
+    y_ref = oracle.dequant(acc_ref, sx, sw)
+    fq.set_dispatch(1 if kernel == "stream" else 2, 0, 0, 0)
+    try:
+        y, acc = run_linear(fq.gemm_w6a8, packed, N, K, 0, to_dev(xq), to_dev(sx), True)
+    finally:
+        fq.set_dispatch(0, 0, 0, 0)
+    if K == 65536:
+        assert acc[0, 0] == 32 * 128 * K          # 2^28: the 4x internal sum is 2^30
+    assert np.array_equal(acc.astype(np.int64), acc_ref)
+    assert_y_close(y.view(np.float16), y_ref)
+
+
 def test_graph_replay_matches_eager():
     """The calls only enqueue kernels (no allocation, no memset), so they can be
     captured in a HIP graph; replays with fresh inputs must equal eager runs."""

@@ -44,6 +44,10 @@ def _load():
         lib.flexq_oracle_pack6_dense.argtypes = [vp, i64, vp]
         lib.flexq_oracle_unpack6_dense.restype = None
         lib.flexq_oracle_unpack6_dense.argtypes = [vp, i64, vp]
+        lib.flexq_oracle_rmsnorm.restype = None
+        lib.flexq_oracle_rmsnorm.argtypes = [vp, vp, i64, i64, ctypes.c_double, vp]
+        lib.flexq_oracle_swiglu.restype = None
+        lib.flexq_oracle_swiglu.argtypes = [vp, i64, i64, vp]
         lib.flexq_oracle_num_threads.restype = ctypes.c_int
         lib.flexq_oracle_num_threads.argtypes = []
         _lib = lib
@@ -165,6 +169,29 @@ def linear(x_fp16, w_fp32, act_bits, group=0):
     y = dequant(acc, sx, sw)
     total = acc if group == 0 else acc.sum(axis=2)
     return {"wq": wq, "sw": sw, "xq": xq, "sx": sx, "acc": total, "acc_g": acc, "y": y}
+
+
+def rmsnorm(x_fp16, gamma_fp16, eps):
+    """fp16( x / sqrt(mean(x^2) + eps) * gamma ) per row, evaluated in fp64."""
+    lib = _load()
+    x = np.ascontiguousarray(x_fp16, dtype=np.float16)
+    g = np.ascontiguousarray(gamma_fp16, dtype=np.float16)
+    M, K = x.shape
+    assert g.shape == (K,)
+    h = np.empty((M, K), dtype=np.uint16)
+    lib.flexq_oracle_rmsnorm(_p(x), _p(g), M, K, float(eps), _p(h))
+    return h.view(np.float16)
+
+
+def swiglu(gate_up_fp16):
+    """fp16( silu(gate) * up ) for the fused [M, 2F] gate|up layout, evaluated in fp64."""
+    lib = _load()
+    gu = np.ascontiguousarray(gate_up_fp16, dtype=np.float16)
+    M, F2 = gu.shape
+    assert F2 % 2 == 0
+    h = np.empty((M, F2 // 2), dtype=np.uint16)
+    lib.flexq_oracle_swiglu(_p(gu), M, F2 // 2, _p(h))
+    return h.view(np.float16)
 
 
 def pack6_dense(wq):

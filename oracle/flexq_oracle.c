@@ -286,6 +286,52 @@ void flexq_oracle_unpack6_dense(const uint8_t *in, int64_t count, int8_t *wq)
     }
 }
 
+/* --------------------------------------- producers of the activations */
+
+/*
+ * The paper fuses the activation quantizer into the kernel that produces the
+ * activations: the normalization before the QKV and gate/up projections, and the
+ * activation function before the down projection (Section 4.1.3, "FlexQ System
+ * Runtime").  These two functions state what those producers output BEFORE the
+ * quantizer, as fp16 (what the unfused pipeline would hand to the quantizer):
+ *
+ *   RMS normalization (LLaMA's):  h[m][k] = fp16( x[m][k] / sqrt(mean_k x^2 + eps) * gamma[k] )
+ *   gated SiLU ("SwiGLU"):        h[m][f] = fp16( g / (1 + exp(-g)) * u ),
+ *                                  g = gu[m][f], u = gu[m][F + f]   (fused gate|up layout)
+ *
+ * both evaluated in fp64 with one final rounding.  The paper does not specify
+ * either formula beyond naming the layers; they are the public definitions of
+ * the LLaMA architecture it evaluates.
+ */
+void flexq_oracle_rmsnorm(const uint16_t *x, const uint16_t *gamma, int64_t M,
+                          int64_t K, double eps, uint16_t *h)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double v = flexq_oracle_f16_to_f64(x[m * K + k]);
+            ss += v * v;
+        }
+        double inv = 1.0 / sqrt(ss / (double)K + eps);
+        for (int64_t k = 0; k < K; ++k)
+            h[m * K + k] = flexq_oracle_f64_to_f16(flexq_oracle_f16_to_f64(x[m * K + k]) * inv *
+                                                   flexq_oracle_f16_to_f64(gamma[k]));
+    }
+}
+
+void flexq_oracle_swiglu(const uint16_t *gu, int64_t M, int64_t F, uint16_t *h)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t f = 0; f < F; ++f) {
+            double g = flexq_oracle_f16_to_f64(gu[m * 2 * F + f]);
+            double u = flexq_oracle_f16_to_f64(gu[m * 2 * F + F + f]);
+            h[m * F + f] = flexq_oracle_f64_to_f16(g / (1.0 + exp(-g)) * u);
+        }
+    }
+}
+
 int flexq_oracle_num_threads(void)
 {
     int n = 1;

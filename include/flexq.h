@@ -104,6 +104,38 @@ flexq_status flexq_quant_act(const uint16_t *x, int M, int K, int act_bits,
                              int8_t *xq, uint16_t *sx, void *stream);
 
 /*
+ * Activation producers with the quantizer fused in (Section 4.1.3: the
+ * quantization of an activation happens inside the operator that produces it,
+ * so no fp16 copy travels through HBM in between).  Both compute the producer
+ * in fp32, round its output h to fp16, and quantize that fp16 h per token
+ * exactly as flexq_quant_act would: the codes and scales are bit-identical to
+ * flexq_quant_act applied to h.
+ *
+ * flexq_rmsnorm_quant:  h[m][k] = (x[m][k] / sqrt(mean_k x[m][k]^2 + eps)) * gamma[k]
+ *   x      dev, fp16 [M,K] row-major, 16-byte aligned
+ *   gamma  dev, fp16 [K], 16-byte aligned
+ *   eps    > 0 (an all-zero token then gives h = 0)
+ * flexq_swiglu_quant:   h[m][f] = silu(gate_up[m][f]) * gate_up[m][F + f],
+ *                       silu(g) = g / (1 + exp(-g))
+ *   gate_up  dev, fp16 [M, 2F] row-major (the output of a fused gate|up
+ *            linear), 16-byte aligned
+ * Common:
+ *   xq     dev, int8 [M,K] (or [M,F]), out, 16-byte aligned
+ *   sx     dev, fp16 [M], out
+ *   h_out  dev, fp16 [M,K] (or [M,F]), out, 16-byte aligned, or NULL when the
+ *          fp16 values are not needed (the fused case)
+ * K and F must be multiples of 128 and at most FLEXQ_MAX_K.  Inputs must be
+ * finite.  Nothing is allocated; the caller owns every buffer.
+ */
+flexq_status flexq_rmsnorm_quant(const uint16_t *x, const uint16_t *gamma,
+                                 float eps, int M, int K, int act_bits,
+                                 int8_t *xq, uint16_t *sx, uint16_t *h_out,
+                                 void *stream);
+flexq_status flexq_swiglu_quant(const uint16_t *gate_up, int M, int F,
+                                int act_bits, int8_t *xq, uint16_t *sx,
+                                uint16_t *h_out, void *stream);
+
+/*
  * Bytes of workspace the GEMM / GEMV entry points need for (M,N,K): room for
  * split-K partial sums and their arrival counters, and for the quantized
  * activations when the quantize prologue is requested.  Never 0 for a valid

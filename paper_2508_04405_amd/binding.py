@@ -43,6 +43,10 @@ def load():
     lib.flexq_unpack_w6.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
     lib.flexq_quant_act.restype = c_int
     lib.flexq_quant_act.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
+    lib.flexq_rmsnorm_quant.restype = c_int
+    lib.flexq_rmsnorm_quant.argtypes = [vp, vp, ctypes.c_float, c_int, c_int, c_int, vp, vp, vp, vp]
+    lib.flexq_swiglu_quant.restype = c_int
+    lib.flexq_swiglu_quant.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp, vp]
     lib.flexq_workspace_bytes.restype = c_size
     lib.flexq_workspace_bytes.argtypes = [c_int, c_int, c_int]
     lib.flexq_workspace_init.restype = c_int
@@ -153,6 +157,45 @@ def quant_act(x, act_bits, out=None):
         sx = torch.empty((M,), dtype=torch.float16, device=x.device)
     _check(lib.flexq_quant_act(_ptr(x), M, K, act_bits, _ptr(xq), _ptr(sx), _stream()))
     return xq, sx
+
+
+def _producer_out(M, L, device, want_h, out):
+    if out is not None:
+        xq, sx = _dev(out[0], torch.int8), _dev(out[1], torch.float16)
+        assert xq.shape == (M, L) and sx.shape == (M,)
+    else:
+        xq = torch.empty((M, L), dtype=torch.int8, device=device)
+        sx = torch.empty((M,), dtype=torch.float16, device=device)
+    h = torch.empty((M, L), dtype=torch.float16, device=device) if want_h else None
+    return xq, sx, h
+
+
+def rmsnorm_quant(x, gamma, eps, act_bits, want_h=False, out=None):
+    """RMS norm of fp16 X[M,K] with fp16 gamma[K], quantized per token in the same
+    kernel -> (xq, sx) or (xq, sx, h) with the fp16 normed values when want_h."""
+    lib = load()
+    _dev(x, torch.float16)
+    _dev(gamma, torch.float16)
+    M, K = x.shape
+    assert gamma.shape == (K,)
+    xq, sx, h = _producer_out(M, K, x.device, want_h, out)
+    _check(lib.flexq_rmsnorm_quant(_ptr(x), _ptr(gamma), float(eps), M, K, act_bits, _ptr(xq),
+                                   _ptr(sx), _ptr(h) if want_h else None, _stream()))
+    return (xq, sx, h) if want_h else (xq, sx)
+
+
+def swiglu_quant(gate_up, act_bits, want_h=False, out=None):
+    """silu(gate) * up of fp16 [M, 2F] (gate columns first), quantized per token in the
+    same kernel -> (xq, sx) or (xq, sx, h)."""
+    lib = load()
+    _dev(gate_up, torch.float16)
+    M, F2 = gate_up.shape
+    assert F2 % 2 == 0
+    F = F2 // 2
+    xq, sx, h = _producer_out(M, F, gate_up.device, want_h, out)
+    _check(lib.flexq_swiglu_quant(_ptr(gate_up), M, F, act_bits, _ptr(xq), _ptr(sx),
+                                  _ptr(h) if want_h else None, _stream()))
+    return (xq, sx, h) if want_h else (xq, sx)
 
 
 def workspace_bytes(M, N, K):

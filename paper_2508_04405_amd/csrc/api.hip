@@ -274,6 +274,35 @@ flexq_status flexq_quant_act(const uint16_t *x, int M, int K, int act_bits, int8
                : FLEXQ_EHIP;
 }
 
+flexq_status flexq_rmsnorm_quant(const uint16_t *x, const uint16_t *gamma, float eps, int M, int K,
+                                 int act_bits, int8_t *xq, uint16_t *sx, uint16_t *h_out,
+                                 void *stream)
+{
+    if (!x || !gamma || !xq || !sx || M < 1 || K < 1) return FLEXQ_EINVAL;
+    if (act_bits != 6 && act_bits != 8) return FLEXQ_EINVAL;
+    if (!(eps > 0.0f)) return FLEXQ_EINVAL;
+    if (K % 128 != 0 || K > FLEXQ_MAX_K) return FLEXQ_ESHAPE;
+    if (!aligned16(x) || !aligned16(gamma) || !aligned16(xq) || (h_out && !aligned16(h_out)))
+        return FLEXQ_EALIGN;
+    return flexq::launch_rmsnorm_quant(x, gamma, eps, M, K, act_bits, xq, sx, h_out,
+                                       (hipStream_t)stream) == hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
+flexq_status flexq_swiglu_quant(const uint16_t *gate_up, int M, int F, int act_bits, int8_t *xq,
+                                uint16_t *sx, uint16_t *h_out, void *stream)
+{
+    if (!gate_up || !xq || !sx || M < 1 || F < 1) return FLEXQ_EINVAL;
+    if (act_bits != 6 && act_bits != 8) return FLEXQ_EINVAL;
+    if (F % 128 != 0 || F > FLEXQ_MAX_K) return FLEXQ_ESHAPE;
+    if (!aligned16(gate_up) || !aligned16(xq) || (h_out && !aligned16(h_out))) return FLEXQ_EALIGN;
+    return flexq::launch_swiglu_quant(gate_up, M, F, act_bits, xq, sx, h_out,
+                                      (hipStream_t)stream) == hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
 size_t flexq_workspace_bytes(int M, int N, int K)
 {
     if (M < 1 || check_shape(N, K, 0) != FLEXQ_OK) return 0;

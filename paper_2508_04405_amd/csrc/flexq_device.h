@@ -96,3 +96,35 @@ __device__ __forceinline__ uint16_t f2h(float f)
     __builtin_memcpy(&bits, &h, 2);
     return bits;
 }
+
+// The IEEE fp32 quotient v / s for many v and one s, without a division per
+// element: r must be the correctly rounded 1 / s.  q = v * r is within an ulp;
+// the fused remainder v - q * s is exact, and adding remainder * r rounds to
+// the correctly rounded quotient (Markstein's correction; it needs the
+// significand of s not to be all ones, and s is an fp16 value here).  Checked
+// over every pair of finite fp16 values v and s > 0 by tests/check_exact_division.c.
+__device__ __forceinline__ float div_by(float v, float s, float r)
+{
+    const float q = v * r;
+    const float rem = __builtin_fmaf(-q, s, v);
+    return __builtin_fmaf(rem, r, q);
+}
+
+// Eight fp16 values -> eight int8 codes clamp(rne(v / s), qmin, qmax).  The
+// code is biased by 128 into a byte (v_cvt_pk_u8_f32 on an exact integer) and
+// the bias is taken off four codes at a time by flipping the top bits.
+__device__ __forceinline__ uint2 quant8(const uint4 &v, float s, float r, float qmin, float qmax)
+{
+    const unsigned w4[4] = {v.x, v.y, v.z, v.w};
+    unsigned out[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float lo = __builtin_rintf(div_by(h2f((uint16_t)(w4[i] & 0xffffu)), s, r));
+        float hi = __builtin_rintf(div_by(h2f((uint16_t)(w4[i] >> 16)), s, r));
+        lo = __builtin_amdgcn_fmed3f(lo, qmin, qmax) + 128.0f;
+        hi = __builtin_amdgcn_fmed3f(hi, qmin, qmax) + 128.0f;
+        out[i >> 1] = __builtin_amdgcn_cvt_pk_u8_f32(lo, 2 * (i & 1), out[i >> 1]);
+        out[i >> 1] = __builtin_amdgcn_cvt_pk_u8_f32(hi, 2 * (i & 1) + 1, out[i >> 1]);
+    }
+    return make_uint2(out[0] ^ 0x80808080u, out[1] ^ 0x80808080u);
+}

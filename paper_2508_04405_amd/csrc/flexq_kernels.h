@@ -33,6 +33,14 @@ hipError_t launch_unpack_w6(const void *packed, int N, int K, int group, int8_t 
                             hipStream_t st);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
 
+// Producers fused with the per-token quantizer; h_out (fp16 copy of the
+// producer's output) may be null.
+hipError_t launch_rmsnorm_quant(const uint16_t *x, const uint16_t *gamma, float eps, int M, int K,
+                                int act_bits, int8_t *xq, uint16_t *sx, uint16_t *h_out,
+                                hipStream_t st);
+hipError_t launch_swiglu_quant(const uint16_t *gate_up, int M, int F, int act_bits, int8_t *xq,
+                               uint16_t *sx, uint16_t *h_out, hipStream_t st);
+
 // Streaming kernel, M <= 128 per launch (the caller loops over row chunks).
 hipError_t launch_skinny(const LinearArgs &a, int waves, hipStream_t st);
 // True if the streaming kernel can quantize fp16 activations itself for this shape.

@@ -1,0 +1,234 @@
+// Activation producers fused with the per-token quantizer (gfx950).
+//
+// Section 4.1.3 of the paper quantizes activations on the fly inside the
+// operator that produces them, so the fp16 tensor never makes a round trip
+// through HBM between the producer and the quantized GEMM.  Two producers are
+// built here, the two that feed quantized linears in a LLaMA block:
+//
+//   MODE 0  RMS norm:    h = fp16( (x * rsqrt(mean(x^2) + eps)) * gamma )
+//   MODE 1  gated SiLU:  h = fp16( (g / (1 + exp(-g))) * u ),  [g | u] fused
+//   MODE 2  identity:    h = x, the stand-alone per-token quantizer
+//
+// followed by the quantizer of Section 2.1 on h: s = fp16(absmax(h) / qmax),
+// code = clamp(rne(h / s)).  h is rounded to fp16 BEFORE it is quantized, so
+// the codes are those the stand-alone quantizer gives for the stored fp16 h.
+//
+// One workgroup of T lanes owns a token.  The token's h values stay in
+// registers (CH chunks of eight per lane) between the absmax pass and the
+// emit pass, so HBM sees each input element once and each output byte once.
+// Short rows take T = 256; long rows take T = 1024 so that a lane holds few
+// chunks and the compute unit stays fully occupied (rows are at most 65536
+// long, eight chunks per lane).
+#include "flexq_device.h"
+#include "flexq_kernels.h"
+
+namespace {
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Wave results meet in LDS and are combined in a fixed order.
+template <bool SUM, int WAVES>
+__device__ __forceinline__ float block_reduce(float v, float *red)
+{
+    v = SUM ? wave_sum(v) : wave_max(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = red[0];
+#pragma unroll
+    for (int i = 1; i < WAVES; ++i) r = SUM ? r + red[i] : fmaxf(r, red[i]);
+    __syncthreads();
+    return r;
+}
+
+__device__ __forceinline__ unsigned pack_h2(float lo, float hi)
+{
+    return (unsigned)f2h(lo) | ((unsigned)f2h(hi) << 16);
+}
+
+// g / (1 + e^-g) through v_exp_f32 and v_rcp_f32: each is good to an ulp of
+// fp32 and the product g * log2(e) to |g| * 2^-24 in the exponent, orders of
+// magnitude inside the half ulp of the fp16 result.  e^-g overflowing to
+// infinity gives g * 0 = -0, the correctly rounded value there.
+__device__ __forceinline__ float silu(float g)
+{
+    return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.44269504088896341f));
+}
+
+template <int MODE, int CH, int T>
+__global__ __launch_bounds__(T) void producer_kernel(const uint16_t *__restrict__ in,
+                                                       const uint16_t *__restrict__ gamma,
+                                                       float eps, int L, float qmax,
+                                                       int8_t *__restrict__ xq,
+                                                       uint16_t *__restrict__ sx,
+                                                       uint16_t *__restrict__ h_out)
+{
+    __shared__ float red[T / 64];
+    const long row = blockIdx.x;
+    const int chunks = L / 8;
+    const uint4 *src = reinterpret_cast<const uint4 *>(in + row * (long)(MODE == 1 ? 2 * L : L));
+    const uint4 *up = src + chunks;                                  // MODE 1 only
+    const uint4 *gam = reinterpret_cast<const uint4 *>(gamma);       // MODE 0 only
+    uint4 held[CH], other[CH];            // other: gamma (MODE 0) or the up half (MODE 1)
+
+    float inv = 0.0f;
+    if (MODE == 0) {
+        float ss = 0.0f;
+        auto squares = [&](const uint4 &v) {
+            unsigned w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float a = h2f((uint16_t)(w4[i] & 0xffffu)), b = h2f((uint16_t)(w4[i] >> 16));
+                ss += a * a;
+                ss += b * b;
+            }
+        };
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = threadIdx.x + T * i;
+            if (c < chunks) held[i] = src[c];
+        }
+        // gamma does not wait for the norm: fetch it ahead of the reduction
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = threadIdx.x + T * i;
+            if (c < chunks) other[i] = gam[c];
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+            if (threadIdx.x + T * i < chunks) squares(held[i]);
+        ss = block_reduce<true, T / 64>(ss, red);
+        inv = 1.0f / sqrtf(ss / (float)L + eps);
+    }
+
+    // eight h values of a chunk from its first operand (x, or the gate half) and its second
+    auto make_h = [&](const uint4 &a, const uint4 &b) -> uint4 {
+        if (MODE == 2) return a;
+        unsigned a4[4] = {a.x, a.y, a.z, a.w}, b4[4] = {b.x, b.y, b.z, b.w}, o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float alo = h2f((uint16_t)(a4[i] & 0xffffu)), ahi = h2f((uint16_t)(a4[i] >> 16));
+            const float blo = h2f((uint16_t)(b4[i] & 0xffffu)), bhi = h2f((uint16_t)(b4[i] >> 16));
+            if (MODE == 0)
+                o[i] = pack_h2((alo * inv) * blo, (ahi * inv) * bhi);
+            else
+                o[i] = pack_h2(silu(alo) * blo, silu(ahi) * bhi);
+        }
+        return make_uint4(o[0], o[1], o[2], o[3]);
+    };
+
+    // fp16 magnitudes of finite values order like their bit patterns
+    unsigned best = 0;
+    auto scan = [&](const uint4 &v) {
+        unsigned w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            best = max(best, w4[i] & 0x7fffu);
+            best = max(best, (w4[i] >> 16) & 0x7fffu);
+        }
+    };
+    if (MODE != 0) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = threadIdx.x + T * i;
+            if (c < chunks) {
+                held[i] = src[c];
+                if (MODE == 1) other[i] = up[c];
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        if (threadIdx.x + T * i < chunks) {
+            held[i] = make_h(held[i], other[i]);
+            scan(held[i]);
+        }
+    }
+    const float amax = block_reduce<false, T / 64>(h2f((uint16_t)best), red);
+
+    float s32 = amax / qmax;
+    uint16_t bits = f2h(s32);
+    float sf = h2f(bits);
+    if (amax == 0.0f || sf == 0.0f) {
+        bits = 0x3c00;
+        sf = 1.0f;
+    }
+    if (threadIdx.x == 0) sx[row] = bits;
+    const float qmin = -qmax - 1.0f;
+
+    uint2 *dst = reinterpret_cast<uint2 *>(xq + row * (long)L);
+    uint4 *hdst = h_out ? reinterpret_cast<uint4 *>(h_out + row * (long)L) : nullptr;
+    const float rf = 1.0f / sf;
+    auto emit = [&](const uint4 &v, int c) {
+        dst[c] = quant8(v, sf, rf, qmin, qmax);
+        if (hdst) hdst[c] = v;
+    };
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        const int c = threadIdx.x + T * i;
+        if (c < chunks) emit(held[i], c);
+    }
+}
+
+template <int MODE>
+hipError_t launch(const uint16_t *in, const uint16_t *gamma, float eps, int M, int L, int act_bits,
+                  int8_t *xq, uint16_t *sx, uint16_t *h_out, hipStream_t st)
+{
+    const float qmax = act_bits == 6 ? 31.0f : 127.0f;
+    const int chunks = L / 8;
+#define FLEXQ_PRODUCER(CH, T)                                                                   \
+    hipLaunchKernelGGL((producer_kernel<MODE, CH, T>), dim3(M), dim3(T), 0, st, in, gamma, eps, \
+                       L, qmax, xq, sx, h_out)
+    if (chunks <= 256)
+        FLEXQ_PRODUCER(1, 256);
+    else if (chunks <= 512)
+        FLEXQ_PRODUCER(2, 256);
+    else if (chunks <= 1024)
+        FLEXQ_PRODUCER(4, 256);
+    else if (chunks <= 2048)
+        FLEXQ_PRODUCER(4, 512);
+    else if (chunks <= 4096)
+        FLEXQ_PRODUCER(8, 512);
+    else if (chunks <= 8192)
+        FLEXQ_PRODUCER(8, 1024);
+    else
+        return hipErrorInvalidValue;            // rows longer than 65536: refused by the caller
+#undef FLEXQ_PRODUCER
+    return hipGetLastError();
+}
+
+}  // namespace
+
+namespace flexq {
+
+hipError_t launch_rmsnorm_quant(const uint16_t *x, const uint16_t *gamma, float eps, int M, int K,
+                                int act_bits, int8_t *xq, uint16_t *sx, uint16_t *h_out,
+                                hipStream_t st)
+{
+    return launch<0>(x, gamma, eps, M, K, act_bits, xq, sx, h_out, st);
+}
+
+hipError_t launch_swiglu_quant(const uint16_t *gate_up, int M, int F, int act_bits, int8_t *xq,
+                               uint16_t *sx, uint16_t *h_out, hipStream_t st)
+{
+    return launch<1>(gate_up, nullptr, 0.0f, M, F, act_bits, xq, sx, h_out, st);
+}
+
+hipError_t launch_quant_act(const uint16_t *x, int M, int K, int act_bits, int8_t *xq, uint16_t *sx,
+                            hipStream_t st)
+{
+    return launch<2>(x, nullptr, 0.0f, M, K, act_bits, xq, sx, nullptr, st);
+}
+
+}  // namespace flexq

@@ -1,4 +1,5 @@
-// Quantizers and the 6-bit packer (gfx950).
+// Weight quantizer and the 6-bit packer (gfx950); the activation quantizer
+// lives with the activation producers.
 //
 // Quantization is the symmetric, zero-point-free scheme of the paper's Section
 // 2.1 with one scale per group of consecutive elements (Section 4.1.1); a whole
@@ -64,71 +65,6 @@ __global__ void quant_w6_kernel(const float *__restrict__ w, int K, int G, int8_
     if (threadIdx.x == 0) sw[unit] = bits;
     for (int i = threadIdx.x; i < G; i += blockDim.x)
         dst[i] = (int8_t)quant_code(src[i], sf, -32.0f, 31.0f);
-}
-
-// One block per token: fp16 in (8 values = 16 bytes per load), int8 out.  The row
-// stays in registers between the absmax pass and the quantize pass when it fits
-// (K <= 8 * 256 * CH), so HBM sees it once: 2 bytes in, 1 byte out per element.
-template <int CH>
-__global__ __launch_bounds__(256) void quant_act_kernel(const uint16_t *__restrict__ x, int K,
-                                                        float qmax, int8_t *__restrict__ xq,
-                                                        uint16_t *__restrict__ sx)
-{
-    __shared__ float red[16];
-    const long row = blockIdx.x;
-    const uint4 *src = reinterpret_cast<const uint4 *>(x + row * K);
-    uint2 *dst = reinterpret_cast<uint2 *>(xq + row * K);
-    const int chunks = K / 8;
-    uint4 held[CH > 0 ? CH : 1];
-    // fp16 magnitudes of finite values order like their bit patterns
-    unsigned best = 0;
-    auto scan = [&](const uint4 &v) {
-        unsigned w4[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            best = max(best, w4[i] & 0x7fffu);
-            best = max(best, (w4[i] >> 16) & 0x7fffu);
-        }
-    };
-    if (CH > 0) {
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int c = threadIdx.x + 256 * i;
-            if (c < chunks) held[i] = src[c];
-        }
-#pragma unroll
-        for (int i = 0; i < CH; ++i)
-            if (threadIdx.x + 256 * i < chunks) scan(held[i]);
-    } else {
-        for (int c = threadIdx.x; c < chunks; c += 256) scan(src[c]);
-    }
-    float amax = block_max(h2f((uint16_t)best), red);
-    uint16_t bits;
-    float sf;
-    make_scale(amax, qmax, bits, sf);
-    if (threadIdx.x == 0) sx[row] = bits;
-    const float qmin = -qmax - 1.0f;
-    auto emit = [&](const uint4 &v, int c) {
-        unsigned w4[4] = {v.x, v.y, v.z, v.w};
-        unsigned out[2] = {0u, 0u};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int lo = quant_code(h2f((uint16_t)(w4[i] & 0xffffu)), sf, qmin, qmax);
-            int hi = quant_code(h2f((uint16_t)(w4[i] >> 16)), sf, qmin, qmax);
-            unsigned pair = (unsigned)(lo & 0xff) | ((unsigned)(hi & 0xff) << 8);
-            out[i >> 1] |= pair << (16 * (i & 1));
-        }
-        dst[c] = make_uint2(out[0], out[1]);
-    };
-    if (CH > 0) {
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int c = threadIdx.x + 256 * i;
-            if (c < chunks) emit(held[i], c);
-        }
-    } else {
-        for (int c = threadIdx.x; c < chunks; c += 256) emit(src[c], c);
-    }
 }
 
 // One thread per (tile, lane): 64 codes in, 48 packed bytes out.
@@ -230,20 +166,6 @@ hipError_t launch_quant_w6(const float *w, int N, int K, int group, int8_t *wq, 
     const long units = (long)N * (K / G);
     const int threads = G >= 1024 ? 256 : 64;
     hipLaunchKernelGGL(quant_w6_kernel, dim3((unsigned)units), dim3(threads), 0, st, w, K, G, wq, sw);
-    return hipGetLastError();
-}
-
-hipError_t launch_quant_act(const uint16_t *x, int M, int K, int act_bits, int8_t *xq, uint16_t *sx,
-                            hipStream_t st)
-{
-    const float qmax = act_bits == 6 ? 31.0f : 127.0f;
-    const int chunks_per_thread = (K / 8 + 255) / 256;
-    if (chunks_per_thread <= 4)
-        hipLaunchKernelGGL(quant_act_kernel<4>, dim3(M), dim3(256), 0, st, x, K, qmax, xq, sx);
-    else if (chunks_per_thread <= 16)
-        hipLaunchKernelGGL(quant_act_kernel<16>, dim3(M), dim3(256), 0, st, x, K, qmax, xq, sx);
-    else
-        hipLaunchKernelGGL(quant_act_kernel<0>, dim3(M), dim3(256), 0, st, x, K, qmax, xq, sx);
     return hipGetLastError();
 }
 

@@ -66,3 +66,23 @@ def activations(M, K, seed, outlier_frac=0.01, outlier_scale=20.0):
         ch = np.random.default_rng([seed, 11]).choice(K, size=n_out, replace=False)
         x[:, ch] *= np.float32(outlier_scale)
     return x.astype(np.float16)
+
+
+def norm_gain(K, seed):
+    """fp16 gamma[K] of an RMS-norm layer: 1 + 0.1 N(0, 1), a few channels amplified the way
+    trained norms amplify outlier channels."""
+    rng = np.random.default_rng([seed, 13])
+    g = 1.0 + 0.1 * rng.standard_normal(K, dtype=np.float32)
+    ch = rng.choice(K, size=max(1, K // 256), replace=False)
+    g[ch] *= np.float32(4.0)
+    return g.astype(np.float16)
+
+
+def gate_up(M, F, seed):
+    """fp16 [M, 2F]: the output of a fused gate|up projection, N(0, 1.5) with sparse large
+    entries (the massive activations ahead of a down projection)."""
+    rng = np.random.default_rng([seed, 17])
+    gu = np.float32(1.5) * rng.standard_normal((M, 2 * F), dtype=np.float32)
+    hits = rng.random((M, 2 * F), dtype=np.float32) < np.float32(5e-4)
+    gu[hits] *= np.float32(12.0)
+    return gu.astype(np.float16)

@@ -79,6 +79,19 @@ def test_other_entry_points_argument_errors():
     assert lib.flexq_quant_act(P16, 1, 128, 7, P16, P16, None) == -1
     assert lib.flexq_quant_act(P16, 1, 100, 8, P16, P16, None) == -2
     assert lib.flexq_quant_act(ODD, 1, 128, 8, P16, P16, None) == -3
+    rn, sg = lib.flexq_rmsnorm_quant, lib.flexq_swiglu_quant
+    rn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_int, ctypes.c_int,
+                   ctypes.c_int] + [ctypes.c_void_p] * 4
+    sg.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 3 + [ctypes.c_void_p] * 4
+    assert rn(P16, None, 1e-5, 1, 128, 8, P16, P16, None, None) == -1
+    assert rn(P16, P16, 0.0, 1, 128, 8, P16, P16, None, None) == -1
+    assert rn(P16, P16, 1e-5, 1, 128, 5, P16, P16, None, None) == -1
+    assert rn(P16, P16, 1e-5, 1, 192, 8, P16, P16, None, None) == -2
+    assert rn(P16, P16, 1e-5, 1, 128, 8, P16, P16, ODD, None) == -3
+    assert sg(None, 1, 128, 8, P16, P16, None, None) == -1
+    assert sg(P16, 0, 128, 8, P16, P16, None, None) == -1
+    assert sg(P16, 1, 65536 + 128, 8, P16, P16, None, None) == -2
+    assert sg(ODD, 1, 128, 8, P16, P16, None, None) == -3
     assert lib.flexq_pack_w6(P16, P16, 96, 256, 0, None, None) == -1
     assert lib.flexq_pack_w6(P16, P16, 100, 256, 0, P16, None) == -2
     assert lib.flexq_pack_w6(P16, P16, 96, 256, 0, ODD, None) == -3

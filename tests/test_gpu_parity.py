@@ -90,6 +90,23 @@ def test_quant_act_bit_exact(bits):
     assert np.array_equal(xq.cpu().numpy(), rq)
 
 
+@pytest.mark.parametrize("bits", [6, 8])
+def test_quant_act_every_fp16_value(bits):
+    """Each row holds every finite fp16 value up to a cap of its own, so 256 different
+    scales (subnormal ones included) each divide the whole fp16 range below them."""
+    say(f"quant_act every fp16 value, bits={bits}")
+    pos = np.arange(0x7c00, dtype=np.uint16)
+    vals = np.concatenate([pos, pos | 0x8000]).view(np.float16)          # 63488 = 496 * 128
+    caps = np.linspace(1, 0x7bff, 256).astype(np.uint16)
+    x = np.tile(vals, (256, 1))
+    mag = x.view(np.uint16) & 0x7fff
+    x[mag > caps[:, None]] = 0
+    xq, sx = fq.quant_act(to_dev(x), bits)
+    rq, rs = oracle.quantize(x.astype(np.float32), bits, 0)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint16), rs.view(np.uint16))
+    assert np.array_equal(xq.cpu().numpy(), rq)
+
+
 def test_quant_act_large_rows():
     say("quant_act K=28672 M=5")
     x = synth.activations(5, 28672, seed=10, outlier_frac=0.01)

@@ -365,7 +365,7 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq, co
 
 flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg)
 {
-    if (gemm_cfg < 0 || gemm_cfg > 16) return FLEXQ_EINVAL;
+    if (gemm_cfg < 0 || gemm_cfg > 32) return FLEXQ_EINVAL;
     g_force_gemm_cfg.store(gemm_cfg);
     if (which < 0 || which > 2 || split_k < 0 || split_k > 64) return FLEXQ_EINVAL;
     if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return FLEXQ_EINVAL;

@@ -150,8 +150,17 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0;
+    static_assert(!GROUP || MT * NT >= 2, "group mode scales up to two blocks behind");
     v16f facc[GROUP ? MT : 1][GROUP ? NT : 1];
+    v16i gpart[3];             // group mode: int32 sums of the block in flight and the two before
+    float gs_prev[NT];         // scales of the stage before, for the blocks it leaves unscaled
     if (GROUP) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) gs_prev[nt] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gpart[i][r] = 0;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -197,48 +206,88 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             load_w(kb + 2, std::integral_constant<int, NXT2>{});
         }
         const uint8_t *xs = lds + CUR * XSTAGE;
-        v16i part[GROUP ? MT : 1][GROUP ? NT : 1];
-        // activation operands are read from LDS one k-step ahead of their MFMAs
-        v4i af[2][MT];
+        if constexpr (GROUP) {
+            // Group-128 scales: the int32 sum of one 128-k stage is exact, and is
+            // folded into the fp32 accumulator as facc += float(sum) * sw[n][g]
+            // (Eq. 7 with the factor 2^(s+t) restored).  That is two vector
+            // operations per accumulator and stage, as many cycles as the MFMAs
+            // themselves, so they are issued in the MFMAs' shadow.  A block's four
+            // MFMAs (one per k-step, chained through the same registers) are
+            // slots 4b .. 4b+3; quarter q of block c is scaled in slot 4c + q + 5,
+            // one block and one slot later, when its last MFMA has surely
+            // finished.  Three block buffers rotate so that the block two back,
+            // whose last quarter is still being read, is not the one overwritten.
+            v4i af[MT][4];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-            af[0][mt] = *reinterpret_cast<const v4i *>(xs + lds_off(arow + 32 * mt, ahalf));
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (j < 3) {
+                for (int j = 0; j < 4; ++j)
+                    af[mt][j] = *reinterpret_cast<const v4i *>(
+                        xs + lds_off(arow + 32 * mt, 2 * j + ahalf));
+            float gsv[NT];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
-                        xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
-            }
+            for (int nt = 0; nt < NT; ++nt) gsv[nt] = h2f(gsreg[CUR][nt]);
+            const v16i vzero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            constexpr int NB = MT * NT;          // blocks per stage, b = nt * MT + mt
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const v4i bf = unpack_kstep(wreg[CUR][nt], j);
+                v4i bf[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bf[j] = unpack_kstep(wreg[CUR][nt], j);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    if (GROUP) {
-                        if (j == 0) {
+                    const int b = nt * MT + mt;
+                    const int buf = (CUR * NB + b) % 3;
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) part[GROUP ? mt : 0][GROUP ? nt : 0][r] = 0;
-                        }
-                        part[GROUP ? mt : 0][GROUP ? nt : 0] =
-                            mfma_i8(af[j & 1][mt], bf, part[GROUP ? mt : 0][GROUP ? nt : 0]);
-                    } else {
-                        acc[mt][nt] = mfma_i8(af[j & 1][mt], bf, acc[mt][nt]);
+                    for (int j = 0; j < 4; ++j) {
+                        gpart[buf] = mfma_i8(af[mt][j], bf[j], j == 0 ? vzero : gpart[buf]);
+                        // the quarter that is due: block b - 1 (quarter j - 1), or the last
+                        // quarter of block b - 2; blocks before this stage's first belong to
+                        // the previous stage and carry its scale
+                        const int c = j == 0 ? b - 2 : b - 1;
+                        const int q = j == 0 ? 3 : j - 1;
+                        const int cw = (c + NB) % NB;                   // block within its stage
+                        const int cmt = cw % MT, cnt = cw / MT;
+                        const int cbuf = (CUR * NB + b + (c - b) + 3) % 3;
+                        const float cgs = c >= 0 ? gsv[cnt] : gs_prev[cnt];
+                        float t[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            t[r] = __builtin_fmaf((float)gpart[cbuf][4 * q + r], cgs,
+                                                  facc[cmt][cnt][4 * q + r]);
+                        // an empty volatile statement that "uses" the four results: code
+                        // motion cannot sink the scaling out of the MFMAs' shadow
+                        asm volatile("" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) facc[cmt][cnt][4 * q + r] = t[r];
+                        // keep this order: the scheduler would otherwise gather the
+                        // MFMAs and leave the vector work with nothing to hide behind
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
-        }
-        if (GROUP) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const float gs = h2f(gsreg[CUR][nt]);
+            for (int nt = 0; nt < NT; ++nt) gs_prev[nt] = gsv[nt];
+        } else {
+            // activation operands are read from LDS one k-step ahead of their MFMAs
+            v4i af[2][MT];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
+                af[0][mt] = *reinterpret_cast<const v4i *>(xs + lds_off(arow + 32 * mt, ahalf));
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        facc[GROUP ? mt : 0][GROUP ? nt : 0][r] +=
-                            (float)part[GROUP ? mt : 0][GROUP ? nt : 0][r] * gs;
+            for (int j = 0; j < 4; ++j) {
+                if (j < 3) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
+                            xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
+                }
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const v4i bf = unpack_kstep(wreg[CUR][nt], j);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma_i8(af[j & 1][mt], bf, acc[mt][nt]);
+                }
             }
         }
         // stage kb + 1 must have landed in LDS (every wavefront's share) before
@@ -258,6 +307,25 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     }
     if (kb < KN) stage(kb, std::integral_constant<int, 0>{});
     if (kb + 1 < KN) stage(kb + 1, std::integral_constant<int, 1>{});
+    if constexpr (GROUP) {
+        // still unscaled: the last block of the last stage, and the last quarter of
+        // the block before it
+        constexpr int NB = MT * NT;
+        const int last = (KN * NB - 1) % 3, before = (KN * NB - 2) % 3;
+        auto fold = [&](int buf, int c, int r0) {
+            const int cmt = c % MT, cnt = c / MT;
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+                if (i == buf) {
+#pragma unroll
+                    for (int r = r0; r < 16; ++r)
+                        facc[cmt][cnt][r] =
+                            __builtin_fmaf((float)gpart[i][r], gs_prev[cnt], facc[cmt][cnt][r]);
+                }
+        };
+        fold(before, NB - 2, 12);
+        fold(last, NB - 1, 0);
+    }
 
     // ---- epilogue -----------------------------------------------------------
     // The accumulators leave through LDS so that global stores are whole lines:
@@ -416,9 +484,13 @@ namespace flexq {
 hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
 {
     // Group-128 scales cost two vector operations per accumulator and group (int -> float,
-    // multiply-add): the vector unit, not the tile shape, bounds that mode (measured: every
-    // tile shape within 3 %).
-    if (a.group != 0) return launch_cfg<2, 2, 2, 2, true, 1>(a, st);
+    // multiply-add), as many cycles as the MFMAs: that mode is bound by the vector unit.
+    // 128x128 tiles with two workgroups per CU keep the int32 sums out of the AGPR half
+    // of the register file (which vector instructions cannot read directly).
+    if (a.group != 0) {
+        if (cfg == 21) return launch_cfg<1, 4, 4, 2, true, 1>(a, st);   // 128x256, 1 wave/SIMD
+        return launch_cfg<1, 4, 4, 1, true, 2>(a, st);
+    }
     if (a.split_k > 1 && cfg == 0) cfg = 8;   // K splits are chosen for 128x128 tiles
     if (cfg == 0) {
         // 128x256 tiles (two workgroups per CU) are the most efficient once the chip

@@ -282,6 +282,9 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
                         af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
                             xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
                 }
+                // the reads stay here, a k-step ahead of their MFMAs: left alone, the
+                // scheduler sinks them next to their first use and exposes the LDS latency
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
                     const v4i bf = unpack_kstep(wreg[CUR][nt], j);

@@ -69,6 +69,18 @@ __device__ __forceinline__ v4i unpack_kstep(const PackedTile &t, int j)
     return ((t.q0 & low2) << 6) | ((t.q1 & low2) << 4) | ((t.q2 & low2) << 2);
 }
 
+// One dword (four weights) of the same operand, for callers that spread the
+// expansion between other instructions.
+__device__ __forceinline__ int unpack_kstep_dword(const PackedTile &t, int j, int d)
+{
+    const int top6 = (int)0xFCFCFCFC;
+    const int low2 = 0x03030303;
+    if (j == 0) return t.q0[d] & top6;
+    if (j == 1) return t.q1[d] & top6;
+    if (j == 2) return t.q2[d] & top6;
+    return ((t.q0[d] & low2) << 6) | ((t.q1[d] & low2) << 4) | ((t.q2[d] & low2) << 2);
+}
+
 // D[32x32] += A[32 x 32k] * B[32k x 32], int8 in, int32 out.  Lane l supplies
 // row (l & 31) of A and column (l & 31) of B, 16 consecutive k each, k-half
 // (l >> 5).  Register r of D at lane l is D[8*(r/4) + 4*(l>>5) + r%4][l & 31].

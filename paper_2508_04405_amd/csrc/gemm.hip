@@ -191,6 +191,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
         load_w(1, std::integral_constant<int, 1>{});
     }
     wait_vmcnt<0>();
+    v4i bf_first = unpack_kstep(wreg[0][0], 0);   // weight operand of a stage's first step
     lds_barrier();
 
     const int arow = (wm * MT) * 32 + (lane & 31);
@@ -269,28 +270,37 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) gs_prev[nt] = gsv[nt];
         } else {
-            // activation operands are read from LDS one k-step ahead of their MFMAs
+            // One flat software pipeline over the stage's 4 * NT (k-step, column tile)
+            // steps.  Activation operands are read from LDS a k-step ahead of their
+            // MFMAs, and the weight operand of step s + 1 is expanded one dword per
+            // MFMA of step s, i.e. in the shadow of the MFMA just issued.  The
+            // scheduling barriers keep that order (left alone, the scheduler sinks the
+            // LDS reads next to their first use and gathers the MFMAs).
+            static_assert(MT >= 4, "one dword of the next operand per MFMA");
             v4i af[2][MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
                 af[0][mt] = *reinterpret_cast<const v4i *>(xs + lds_off(arow + 32 * mt, ahalf));
+            v4i bfc = bf_first;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (j < 3) {
+            for (int s = 0; s < 4 * NT; ++s) {
+                const int j = s / NT, nt = s % NT;
+                if (nt == 0 && j < 3) {
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
                         af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
                             xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                // the reads stay here, a k-step ahead of their MFMAs: left alone, the
-                // scheduler sinks them next to their first use and exposes the LDS latency
-                __builtin_amdgcn_sched_barrier(0);
+                v4i bfn = bfc;
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const v4i bf = unpack_kstep(wreg[CUR][nt], j);
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma_i8(af[j & 1][mt], bf, acc[mt][nt]);
+                for (int mt = 0; mt < MT; ++mt) {
+                    acc[mt][nt] = mfma_i8(af[j & 1][mt], bfc, acc[mt][nt]);
+                    if (mt < 4 && s + 1 < 4 * NT)
+                        bfn[mt] = unpack_kstep_dword(wreg[CUR][(s + 1) % NT], (s + 1) / NT, mt);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                bfc = bfn;
             }
         }
         // stage kb + 1 must have landed in LDS (every wavefront's share) before
@@ -299,6 +309,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             wait_vmcnt<XDMA + WLOADS + (GROUP ? NT : 0)>();
         else
             wait_vmcnt<0>();
+        if constexpr (!GROUP) bf_first = unpack_kstep(wreg[(CUR + 1) % 3][0], 0);   // has landed
         lds_barrier();
     };
 

@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
 # Bytes fetched past L2 + written, per launch, averaged over the four layers: rocprofv3 FETCH_SIZE and
 # WRITE_SIZE runs of this script, scaled on a 1 GiB device copy (x2.000 and x1.000); the runs, the
 # raw readings and the per-layer table are in profiles/bench_llama2_70b_linears_hbm_traffic.md.
-TRAFFIC_GEMM_M4096 = 1478.6e6 + 172.0e6
+TRAFFIC_GEMM_M4096 = 1474.6e6 + 172.0e6
 TRAFFIC_GEMV_M1 = 160.76e6 + 0.042e6
 SIGMA = 0.015
 LAYERS = [("qkv", 8192, 10240, 6), ("o", 8192, 8192, 6), ("gate_up", 8192, 57344, 6),
@@ -45,6 +45,54 @@ def gemm_bytes(M, N, K):
     return 0.75 * N * K + 2 * N + M * K + 2 * M + 2 * M * N
 
 
+def sweep(args, torch, fq, synth, dev):
+    """Per-layer time of the linear-layer call (pre-quantized activations) for each token
+    count, the four layers cycled so that every launch streams its weights from HBM."""
+    gen = torch.Generator(device=dev)
+    packed = []
+    for i, (name, K, N, bits) in enumerate(LAYERS):
+        gen.manual_seed(3000 + 10 * i)
+        wq = torch.empty((N, K), dtype=torch.int8, device=dev)
+        sw = torch.empty((N,), dtype=torch.float16, device=dev)
+        for r0 in range(0, N, 8192):
+            r1 = min(N, r0 + 8192)
+            w = torch.randn((r1 - r0, K), generator=gen, device=dev, dtype=torch.float32) * SIGMA
+            wq[r0:r1], sw[r0:r1] = fq.quant_w6(w)
+            del w
+        packed.append(fq.pack_w6(wq, sw))
+        del wq, sw
+    print("| M | " + " | ".join("%s us (TOP/s, GB/s)" % L[0] for L in LAYERS) + " |")
+    print("|---|" + "---|" * len(LAYERS))
+    for M in (1, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096):
+        bufs = []
+        for i, (name, K, N, bits) in enumerate(LAYERS):
+            x = torch.from_numpy(synth.activations(M, K, seed=3000 + 10 * i + 1,
+                                                   outlier_frac=0.01)).to(dev)
+            xq, sx = fq.quant_act(x, bits)
+            bufs.append((xq, sx, torch.empty((M, N), dtype=torch.float16, device=dev),
+                         fq.make_workspace(M, N, K, dev)))
+        times = [[] for _ in LAYERS]
+        for rep in range(args.warmup + args.steps):
+            for i, (name, K, N, bits) in enumerate(LAYERS):
+                xq, sx, y, ws = bufs[i]
+                fn = fq.gemm_w6a6 if bits == 6 else fq.gemm_w6a8
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn(packed[i], N, K, 0, xq=xq, sx=sx, workspace=ws, out=y)
+                e1.record()
+                if rep >= args.warmup:
+                    times[i].append((e0, e1))
+        torch.cuda.synchronize()
+        cells = []
+        for i, (name, K, N, bits) in enumerate(LAYERS):
+            us = sorted(a.elapsed_time(b) * 1e3 for a, b in times[i])[len(times[i]) // 2]
+            cells.append("%.1f (%.0f, %.0f)" % (us, 2.0 * M * N * K / us / 1e6,
+                                                gemm_bytes(M, N, K) / us / 1e3))
+        print("| %d | " % M + " | ".join(cells) + " |", flush=True)
+        del bufs
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,6 +104,9 @@ def main():
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="only run a plain device copy of known size (for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line, print a table of per-layer GEMM / GEMV "
+                         "times over token counts M = 1 .. 4096 (library's own dispatch)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); "
@@ -81,6 +132,9 @@ def main():
                           "bytes_written_per_copy": nbytes}))
         return
     fq.load()
+
+    if args.sweep:
+        return sweep(args, torch, fq, synth, dev)
 
     # ---- resident inputs: packed weights, fp16 activations -----------------
     gen = torch.Generator(device=dev)

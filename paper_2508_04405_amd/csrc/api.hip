@@ -68,8 +68,12 @@ int choose_gemm_split(int M, int N, int K)
         ks = g_force_split.load();
     } else {
         const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
-        if (tiles >= 256) return 1;
-        ks = (int)(256 / tiles);
+        // about one block per CU; two per CU once there are several row tiles and K is
+        // long enough for the partial sums to stay a small share of the traffic
+        // (measured: 28672-deep down projection at 256 and 512 tokens)
+        const long target = (K >= 16384 && tiles >= 128) ? 512 : 256;
+        if (tiles >= target) return 1;
+        ks = (int)(target / tiles);
         if (ks > kt / 4) ks = kt / 4;
         const int by_traffic = K / (11 * M);
         if (ks > by_traffic) ks = by_traffic;
@@ -136,9 +140,13 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     Workspace ws = carve(workspace, workspace_bytes, M, K);
 
     const int forced = g_force_kernel.load();
-    // measured cross-over between the streaming kernel and the tiled kernel with K splits
+    // Measured cross-over between the streaming kernel and the tiled kernel with K splits:
+    // past 32 tokens the streaming kernel needs a second MFMA row tile and re-reads the
+    // activations once per 32 output channels, while the tiled kernel's time stays flat
+    // up to 128 tokens; only small layers (N*K <= 2^26) keep streaming up to 64.
     (void)prefer_stream;
-    bool stream_kernel = M <= 64;
+    const bool tiled_ok = (long)(M + 256) * K < (1L << 32) && (long)N * K / 4 * 3 < (1L << 32);
+    bool stream_kernel = M <= 32 || (M <= 64 && ((long)N * K <= (1L << 26) || !tiled_ok));
     if (forced == 1) stream_kernel = true;
     if (forced == 2) stream_kernel = false;
 

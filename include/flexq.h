@@ -198,6 +198,36 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq,
                              void *stream);
 
 /*
+ * The paper's full scheme (Section 4.1.1, Eq. 7): BOTH operands carry one fp16
+ * scale per group of 128 along K,
+ *   y[m,n] = fp16( sum_g sxg[g][m] * sw[n][g] * acc_g[m,n] ),
+ * acc_g the exact int32 product over group g; fp32 arithmetic, one rounding.
+ *
+ * flexq_quant_act_g128: per token and group, scale = fp16(absmax / qmax)
+ * (1.0 if zero), codes = clamp(round_half_even(x / scale)), as flexq_quant_act.
+ *   x           dev, fp16 [M,K] row-major, 16-byte aligned
+ *   xq          dev, int8 [M,K], out, 16-byte aligned
+ *   sxg         dev, fp16 [K/128][sxg_stride], out: GROUP-major (the scales of
+ *               one group for all tokens are contiguous), sxg_stride >= M;
+ *               elements m >= M of a row are not written
+ * flexq_linear_g128: the linear layer on such activations.
+ *   packed      dev, from flexq_pack_w6 with group = 128
+ *   xq, sxg     dev, as written by flexq_quant_act_g128 (A6 or A8 codes alike)
+ *   y           dev, fp16 [M,N], out, 16-byte aligned
+ *   workspace   as for flexq_gemm_*, flexq_workspace_bytes(M,N,K) bytes
+ * Same shape and alignment rules and status codes as the calls above; any
+ * M >= 1.  (Runs the streaming kernel 128 tokens at a time: built for decode
+ * batches; prefill-size M works but is not tuned.)
+ */
+flexq_status flexq_quant_act_g128(const uint16_t *x, int M, int K, int act_bits,
+                                  int8_t *xq, uint16_t *sxg, int sxg_stride,
+                                  void *stream);
+flexq_status flexq_linear_g128(const void *packed, const int8_t *xq,
+                               const uint16_t *sxg, int sxg_stride, int M,
+                               int N, int K, uint16_t *y, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
+/*
  * Tuning hook for experiments and tests: force the kernel the next calls use.
  * which: 0 = automatic, 1 = streaming (skinny) kernel, 2 = tiled GEMM kernel.
  * split_k: 0 = automatic, else the number of K splits of the streaming kernel.

@@ -43,6 +43,10 @@ def load():
     lib.flexq_unpack_w6.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
     lib.flexq_quant_act.restype = c_int
     lib.flexq_quant_act.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
+    lib.flexq_quant_act_g128.restype = c_int
+    lib.flexq_quant_act_g128.argtypes = [vp, c_int, c_int, c_int, vp, vp, c_int, vp]
+    lib.flexq_linear_g128.restype = c_int
+    lib.flexq_linear_g128.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_int, vp, vp, ctypes.c_size_t, vp]
     lib.flexq_rmsnorm_quant.restype = c_int
     lib.flexq_rmsnorm_quant.argtypes = [vp, vp, ctypes.c_float, c_int, c_int, c_int, vp, vp, vp, vp]
     lib.flexq_swiglu_quant.restype = c_int
@@ -196,6 +200,35 @@ def swiglu_quant(gate_up, act_bits, want_h=False, out=None):
     _check(lib.flexq_swiglu_quant(_ptr(gate_up), M, F, act_bits, _ptr(xq), _ptr(sx),
                                   _ptr(h) if want_h else None, _stream()))
     return (xq, sx, h) if want_h else (xq, sx)
+
+
+def quant_act_g128(x, act_bits):
+    """fp16 X[M,K] -> (int8 codes [M,K], fp16 scales [K/128, M]) with one scale per token and
+    group of 128 along K; the scales are group-major."""
+    lib = load()
+    _dev(x, torch.float16)
+    M, K = x.shape
+    xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    sxg = torch.empty((K // 128, M), dtype=torch.float16, device=x.device)
+    _check(lib.flexq_quant_act_g128(_ptr(x), M, K, act_bits, _ptr(xq), _ptr(sxg), M, _stream()))
+    return xq, sxg
+
+
+def linear_g128(packed, N, K, xq, sxg, workspace=None, out=None):
+    """Y[M,N] for group-128 scales on both operands (packed made with group = 128)."""
+    lib = load()
+    _dev(packed, torch.uint8)
+    _dev(xq, torch.int8)
+    _dev(sxg, torch.float16)
+    M = xq.shape[0]
+    assert xq.shape == (M, K) and sxg.shape[0] == K // 128 and sxg.shape[1] >= M
+    dev = xq.device
+    if workspace is None:
+        workspace = make_workspace(M, N, K, dev)
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=dev)
+    _check(lib.flexq_linear_g128(_ptr(packed), _ptr(xq), _ptr(sxg), sxg.shape[1], M, N, K, _ptr(y),
+                                 _ptr(workspace), workspace.numel(), _stream()))
+    return y
 
 
 def workspace_bytes(M, N, K):

@@ -123,10 +123,15 @@ Workspace carve(void *ws, size_t bytes, int M, int K)
 
 flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int group, const int8_t *xq,
                     const uint16_t *sx, const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
-                    int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
+                    int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream,
+                    const uint16_t *sxg = nullptr, int sxg_stride = 0)
 {
     if (!packed || !y || M < 1) return FLEXQ_EINVAL;
-    if (!x_fp16 && (!xq || !sx)) return FLEXQ_EINVAL;
+    if (sxg) {   // scales per token and group: pre-quantized activations, group-128 weights
+        if (!xq || x_fp16 || acc_out || group != 128 || sxg_stride < M) return FLEXQ_EINVAL;
+    } else if (!x_fp16 && (!xq || !sx)) {
+        return FLEXQ_EINVAL;
+    }
     flexq_status s = check_shape(N, K, group);
     if (s != FLEXQ_OK) return s;
     if (group != 0 && acc_out) return FLEXQ_EINVAL;
@@ -147,6 +152,7 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     (void)prefer_stream;
     const bool tiled_ok = (long)(M + 256) * K < (1L << 32) && (long)N * K / 4 * 3 < (1L << 32);
     bool stream_kernel = M <= 32 || (M <= 64 && ((long)N * K <= (1L << 26) || !tiled_ok));
+    if (sxg) stream_kernel = true;   // group-wise activation scales: streaming kernel, 128 rows a launch
     if (forced == 1) stream_kernel = true;
     if (forced == 2) stream_kernel = false;
 
@@ -173,6 +179,8 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     a.partial = ws.partial;
     a.x_fp16 = fuse ? x_fp16 : nullptr;
     a.qmax = act_bits == 6 ? 31.0f : 127.0f;
+    a.sxg = nullptr;
+    a.sxg_stride = sxg_stride;
 
     if (!stream_kernel) {
         // the tiled kernel addresses both operands with 32-bit buffer offsets
@@ -193,7 +201,8 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     for (int m0 = 0; m0 < M; m0 += kSkinnyMaxM) {
         const int rows = M - m0 < kSkinnyMaxM ? M - m0 : kSkinnyMaxM;
         a.xq = xq + (size_t)m0 * K;
-        a.sx = sx + m0;
+        a.sx = sx ? sx + m0 : nullptr;
+        a.sxg = sxg ? sxg + m0 : nullptr;
         a.M = rows;
         a.y = y + (size_t)m0 * N;
         a.acc_out = acc_out ? acc_out + (size_t)m0 * N : nullptr;
@@ -309,6 +318,28 @@ flexq_status flexq_swiglu_quant(const uint16_t *gate_up, int M, int F, int act_b
                                       (hipStream_t)stream) == hipSuccess
                ? FLEXQ_OK
                : FLEXQ_EHIP;
+}
+
+flexq_status flexq_quant_act_g128(const uint16_t *x, int M, int K, int act_bits, int8_t *xq,
+                                  uint16_t *sxg, int sxg_stride, void *stream)
+{
+    if (!x || !xq || !sxg || M < 1 || K < 1 || sxg_stride < M) return FLEXQ_EINVAL;
+    if (act_bits != 6 && act_bits != 8) return FLEXQ_EINVAL;
+    if (K % 128 != 0 || K > FLEXQ_MAX_K) return FLEXQ_ESHAPE;
+    if (!aligned16(x) || !aligned16(xq)) return FLEXQ_EALIGN;
+    return flexq::launch_quant_act_g128(x, M, K, act_bits, xq, sxg, sxg_stride,
+                                        (hipStream_t)stream) == hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
+flexq_status flexq_linear_g128(const void *packed, const int8_t *xq, const uint16_t *sxg,
+                               int sxg_stride, int M, int N, int K, uint16_t *y, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    if (!sxg) return FLEXQ_EINVAL;
+    return linear(8, true, packed, 128, xq, nullptr, nullptr, M, N, K, y, nullptr, workspace,
+                  workspace_bytes, stream, sxg, sxg_stride);
 }
 
 size_t flexq_workspace_bytes(int M, int N, int K)

@@ -21,12 +21,17 @@ struct LinearArgs {
     int split_k;             // >= 1
     const uint16_t *x_fp16;  // streaming kernel only: quantize these fp16 activations in the
     float qmax;              // kernel (31 or 127) instead of reading xq / sx; else null
+    const uint16_t *sxg;     // group-wise activation scales [K/128][sxg_stride] (group-major),
+    int sxg_stride;          // or null: one scale per token in sx (sxg needs group == 128)
 };
 
 hipError_t launch_quant_w6(const float *w, int N, int K, int group, int8_t *wq, uint16_t *sw,
                            hipStream_t st);
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int act_bits, int8_t *xq,
                             uint16_t *sx, hipStream_t st);
+// Group-wise (128 along K) activation quantizer; sxg is [K/128][stride], group-major.
+hipError_t launch_quant_act_g128(const uint16_t *x, int M, int K, int act_bits, int8_t *xq,
+                                 uint16_t *sxg, int stride, hipStream_t st);
 hipError_t launch_pack_w6(const int8_t *wq, const uint16_t *sw, int N, int K, int group,
                           void *packed, hipStream_t st);
 hipError_t launch_unpack_w6(const void *packed, int N, int K, int group, int8_t *wq, uint16_t *sw,

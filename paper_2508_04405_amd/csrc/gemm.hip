@@ -520,7 +520,6 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
     case 6: return launch_cfg<1, 4, 8, 2, false, 1>(a, st);   // 256x256, 4 waves side by side (256x64 each)
     case 7: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);   // 128x256, 4 waves side by side, 2 workgroups/CU
     case 8: return launch_cfg<1, 4, 4, 1, false, 3>(a, st);   // 128x128, 4 waves side by side, 3 workgroups/CU
-    case 10: return launch_cfg<1, 8, 8, 1, false, 2>(a, st);  // 256x256, 8 waves side by side (256x32 each)
     default: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);
     }
 }

@@ -181,6 +181,43 @@ __global__ __launch_bounds__(T) void producer_kernel(const uint16_t *__restrict_
     }
 }
 
+// Group-wise activation quantizer (Section 4.1.1: the activations are cut into the same
+// groups of 128 along K as the weights).  Sixteen lanes own one (token, group): eight values
+// each, the absmax meets by four shuffles, nothing crosses a wavefront.  Scales are written
+// group-major, sxg[g][m], the order in which the linear-layer kernels consume them.
+__global__ __launch_bounds__(256) void quant_act_g128_kernel(const uint16_t *__restrict__ x, int M,
+                                                             int K, float qmax,
+                                                             int8_t *__restrict__ xq,
+                                                             uint16_t *__restrict__ sxg, int stride)
+{
+    const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+    const int G = K / 128;
+    const long unit = gid >> 4;
+    if (unit >= (long)M * G) return;           // the sixteen lanes of a unit leave together
+    const long m = unit / G;
+    const int g = (int)(unit - m * G), c = (int)(gid & 15);
+    const long at = m * K + 128L * g + 8 * c;
+    const uint4 v = *reinterpret_cast<const uint4 *>(x + at);
+    const unsigned w4[4] = {v.x, v.y, v.z, v.w};
+    unsigned best = 0;                         // fp16 magnitudes order like their bit patterns
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        best = max(best, w4[i] & 0x7fffu);
+        best = max(best, (w4[i] >> 16) & 0x7fffu);
+    }
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) best = max(best, (unsigned)__shfl_xor((int)best, off, 64));
+    const float amax = h2f((uint16_t)best);
+    uint16_t bits = f2h(amax / qmax);
+    float sf = h2f(bits);
+    if (amax == 0.0f || sf == 0.0f) {
+        bits = 0x3c00;
+        sf = 1.0f;
+    }
+    if (c == 0) sxg[(long)g * stride + m] = bits;
+    *reinterpret_cast<uint2 *>(xq + at) = quant8(v, sf, 1.0f / sf, -qmax - 1.0f, qmax);
+}
+
 template <int MODE>
 hipError_t launch(const uint16_t *in, const uint16_t *gamma, float eps, int M, int L, int act_bits,
                   int8_t *xq, uint16_t *sx, uint16_t *h_out, hipStream_t st)
@@ -229,6 +266,16 @@ hipError_t launch_quant_act(const uint16_t *x, int M, int K, int act_bits, int8_
                             hipStream_t st)
 {
     return launch<2>(x, nullptr, 0.0f, M, K, act_bits, xq, sx, nullptr, st);
+}
+
+hipError_t launch_quant_act_g128(const uint16_t *x, int M, int K, int act_bits, int8_t *xq,
+                                 uint16_t *sxg, int stride, hipStream_t st)
+{
+    const float qmax = act_bits == 6 ? 31.0f : 127.0f;
+    const long lanes = (long)M * (K / 128) * 16;
+    hipLaunchKernelGGL(quant_act_g128_kernel, dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, st,
+                       x, M, K, qmax, xq, sxg, stride);
+    return hipGetLastError();
 }
 
 }  // namespace flexq

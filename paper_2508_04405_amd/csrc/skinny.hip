@@ -34,13 +34,17 @@ template <int MT, bool XLDS>
 struct Stage {
     PackedTile w;
     v4i a[XLDS ? 1 : MT][XLDS ? 1 : 4];
-    uint16_t gs;  // group scale of this lane's column (group mode)
+    uint16_t gs;      // group scale of this lane's column (group modes)
+    uint16_t xs[MT];  // group mode 2: this tile's scale of token 32 mt + (lane & 31)
 };
 
-template <int MT, bool GROUP, bool XLDS>
+// GROUP: 0 = one scale per output channel and per token; 1 = weight scales per 128-k
+// group (Section 4.1.1), one scale per token; 2 = both operands scaled per group (Eq. 7).
+template <int MT, int GROUP, bool XLDS>
 __device__ __forceinline__ void load_stage(Stage<MT, XLDS> &s, const v4i *packed,
                                            const uint16_t *scales, const int8_t *const (&xrow)[MT],
-                                           const bool (&xact)[MT], long tile_index, int t, int lane)
+                                           const bool (&xact)[MT], long tile_index, int t, int lane,
+                                           const uint16_t *sxg, int sxg_stride)
 {
     s.w = load_packed_tile(packed + tile_index * (FLEXQ_TILE_BYTES / 16), lane);
     if (!XLDS) {
@@ -55,6 +59,11 @@ __device__ __forceinline__ void load_stage(Stage<MT, XLDS> &s, const v4i *packed
         }
     }
     if (GROUP) s.gs = scales[tile_index * 32 + (lane & 31)];
+    if (GROUP == 2) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            s.xs[mt] = xact[mt] ? sxg[(long)t * sxg_stride + 32 * mt + (lane & 31)] : (uint16_t)0;
+    }
 }
 
 // Quantizer arithmetic of the fused prologue: the same operations, in the same
@@ -74,11 +83,12 @@ __device__ __forceinline__ unsigned prologue_code(uint16_t hbits, float sf, floa
     return (unsigned)((int)q & 0xff);
 }
 
-template <int MT, bool GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE>
+template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void skinny_kernel(flexq::LinearArgs a)
 {
     static_assert(!FUSEQ || (XLDS && MT == 1), "the fused quantizer fills the LDS slice");
+    static_assert(!FUSEQ || GROUP != 2, "the fused quantizer makes one scale per token");
     __shared__ int red[W][4][64];
     __shared__ int s_last;
     __shared__ float s_sx[32];      // FUSEQ: per-token scales made in this kernel
@@ -148,7 +158,8 @@ void skinny_kernel(flexq::LinearArgs a)
     for (int p = 0; p < P; ++p) {
         const int t = tw + W * p;
         if (t < t1)
-            load_stage<MT, GROUP, XLDS>(st[p], packed, a.scales, xrow, xact, tile_base + t, t, lane);
+            load_stage<MT, GROUP, XLDS>(st[p], packed, a.scales, xrow, xact, tile_base + t, t, lane,
+                                        a.sxg, a.sxg_stride);
     }
 
     if (FUSEQ) {
@@ -286,8 +297,20 @@ void skinny_kernel(flexq::LinearArgs a)
 #pragma unroll
                         for (int j = 0; j < 4; ++j) part = mfma_i8(af[mt][j], b[j], part);
                         const float gs = h2f(st[p].gs);
+                        if (GROUP == 2) {
+                            // register r holds token 8 (r / 4) + 4 (lane / 32) + r % 4, whose
+                            // scale for this tile sits in the lane of that number
+                            const int mine = st[p].xs[mt];
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) facc[mt][r] += (float)part[r] * gs;
+                            for (int r = 0; r < 16; ++r) {
+                                const int src = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                                const float xs = h2f((uint16_t)__builtin_amdgcn_ds_bpermute(4 * src, mine));
+                                facc[mt][r] = __builtin_fmaf((float)part[r] * gs, xs, facc[mt][r]);
+                            }
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) facc[mt][r] += (float)part[r] * gs;
+                        }
                     } else {
 #pragma unroll
                         for (int j = 0; j < 4; ++j) acc[mt] = mfma_i8(af[mt][j], b[j], acc[mt]);
@@ -296,7 +319,7 @@ void skinny_kernel(flexq::LinearArgs a)
                 const int tn = t + W * P;
                 if (tn < t1)
                     load_stage<MT, GROUP, XLDS>(st[p], packed, a.scales, xrow, xact, tile_base + tn,
-                                                tn, lane);
+                                                tn, lane, a.sxg, a.sxg_stride);
                 t += W;
             }
         }
@@ -331,7 +354,8 @@ void skinny_kernel(flexq::LinearArgs a)
                     }
                     if (KS == 1) {
                         if (GROUP) {
-                            a.y[(long)m * N + n] = f2h(__int_as_float(v) * 0.25f * (FUSEQ ? s_sx[m] : h2f(a.sx[m])));
+                            a.y[(long)m * N + n] = f2h(__int_as_float(v) * 0.25f *
+                                                       (GROUP == 2 ? 1.0f : FUSEQ ? s_sx[m] : h2f(a.sx[m])));
                         } else {
                             const int qv = v >> 2;
                             if (a.acc_out) a.acc_out[(long)m * N + n] = qv;
@@ -376,7 +400,7 @@ void skinny_kernel(flexq::LinearArgs a)
             for (int k = 0; k < KS; ++k)
                 f += __int_as_float(__hip_atomic_load(&partial_i[((long)k * M + m) * N + n],
                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            a.y[(long)m * N + n] = f2h(f * 0.25f * (FUSEQ ? s_sx[m] : h2f(a.sx[m])));
+            a.y[(long)m * N + n] = f2h(f * 0.25f * (GROUP == 2 ? 1.0f : FUSEQ ? s_sx[m] : h2f(a.sx[m])));
         } else {
             int v = 0;
             for (int k = 0; k < KS; ++k)
@@ -389,7 +413,7 @@ void skinny_kernel(flexq::LinearArgs a)
     }
 }
 
-template <int MT, bool GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE>
+template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE>
 hipError_t launch_one(const flexq::LinearArgs &a, hipStream_t st)
 {
     const unsigned blocks = (unsigned)(a.N / 32) * (unsigned)a.split_k;
@@ -412,17 +436,18 @@ hipError_t launch_one(const flexq::LinearArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-template <bool GROUP>
+template <int GROUP>
 hipError_t pick(const flexq::LinearArgs &a, int waves, hipStream_t st)
 {
     const int KT = a.K / 128;
     const int max_tiles = (KT + a.split_k - 1) / a.split_k;
     const bool xlds = a.M <= 32 && (long)a.M * max_tiles * 128 <= kXldsBytes;
     if (a.x_fp16) {  // fused quantize prologue: the caller checked skinny_can_fuse()
-        if (!xlds) return hipErrorInvalidValue;
-        if (waves == 16) return launch_one<1, GROUP, true, true, 4, 16, 4>(a, st);
-        if (waves == 8) return launch_one<1, GROUP, true, true, 4, 8, 4>(a, st);
-        return launch_one<1, GROUP, true, true, 4, 4, 4>(a, st);
+        if (!xlds || GROUP == 2) return hipErrorInvalidValue;
+        constexpr int G = GROUP == 2 ? 1 : GROUP;     // never instantiated for mode 2
+        if (waves == 16) return launch_one<1, G, true, true, 4, 16, 4>(a, st);
+        if (waves == 8) return launch_one<1, G, true, true, 4, 8, 4>(a, st);
+        return launch_one<1, G, true, true, 4, 4, 4>(a, st);
     }
     if (a.M <= 32) {
         if (xlds) {
@@ -455,7 +480,8 @@ bool skinny_can_fuse(int M, int K, int split_k)
 
 hipError_t launch_skinny(const LinearArgs &a, int waves, hipStream_t st)
 {
-    return a.group != 0 ? pick<true>(a, waves, st) : pick<false>(a, waves, st);
+    if (a.sxg) return a.group == 128 ? pick<2>(a, waves, st) : hipErrorInvalidValue;
+    return a.group != 0 ? pick<1>(a, waves, st) : pick<0>(a, waves, st);
 }
 
 }  // namespace flexq

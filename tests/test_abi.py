@@ -79,6 +79,19 @@ def test_other_entry_points_argument_errors():
     assert lib.flexq_quant_act(P16, 1, 128, 7, P16, P16, None) == -1
     assert lib.flexq_quant_act(P16, 1, 100, 8, P16, P16, None) == -2
     assert lib.flexq_quant_act(ODD, 1, 128, 8, P16, P16, None) == -3
+    qg, lg = lib.flexq_quant_act_g128, lib.flexq_linear_g128
+    assert qg(None, 1, 128, 8, P16, P16, 1, None) == -1
+    assert qg(P16, 4, 128, 8, P16, P16, 3, None) == -1          # stride shorter than M
+    assert qg(P16, 1, 128, 7, P16, P16, 1, None) == -1
+    assert qg(P16, 1, 192, 8, P16, P16, 1, None) == -2
+    assert qg(ODD, 1, 128, 8, P16, P16, 1, None) == -3
+    big = 1 << 26
+    assert lg(P16, P16, None, 4, 4, 128, 256, P16, P16, big, None) == -1
+    assert lg(P16, None, P16, 4, 4, 128, 256, P16, P16, big, None) == -1
+    assert lg(P16, P16, P16, 3, 4, 128, 256, P16, P16, big, None) == -1   # stride shorter than M
+    assert lg(P16, P16, P16, 4, 4, 100, 256, P16, P16, big, None) == -2
+    assert lg(P16, P16, P16, 4, 4, 128, 256, ODD, P16, big, None) == -3
+    assert lg(P16, P16, P16, 4, 4, 128, 256, P16, None, big, None) == -5
     rn, sg = lib.flexq_rmsnorm_quant, lib.flexq_swiglu_quant
     rn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_int, ctypes.c_int,
                    ctypes.c_int] + [ctypes.c_void_p] * 4

@@ -1,0 +1,128 @@
+"""GPU parity of the scheme with group-128 scales on BOTH operands (Section 4.1.1, Eq. 7)
+against the CPU oracle: codes and scales bit-exact, outputs within one fp16 ulp plus the
+bound of an fp32 sum of K/128 terms taken in the kernel's own order."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2508_04405_amd as fq
+from paper_2508_04405_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def ordered(h):
+    b = h.view(np.uint16).astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7fff), b)
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("M,K", [(1, 128), (37, 1152), (130, 8192), (3, 65536)])
+def test_quant_act_g128_bit_exact(M, K, bits):
+    say(f"quant_act_g128 M={M} K={K} bits={bits}")
+    qmax = 31 if bits == 6 else 127
+    x = synth.activations(M, K, seed=50 + K, outlier_frac=0.02).astype(np.float32)
+    x[0, :128] = 0.0                                     # an all-zero group
+    if K >= 256:
+        ks = np.arange(128) % (2 * qmax) - qmax
+        x[0, 128:256] = (ks + 0.5) * 0.5                 # every quotient a tie
+        x[0, 128] = qmax * 0.5
+    if M > 1:
+        x[1, :128] = 0.0
+        x[1, 5] = 6e-8                                   # fp16 subnormal input
+    x16 = x.astype(np.float16)
+    xq, sxg = fq.quant_act_g128(to_dev(x16), bits)
+    rq, rs = oracle.quantize(x16.astype(np.float32), bits, 128)      # rs is [M, K/128]
+    assert np.array_equal(sxg.cpu().numpy().view(np.uint16), rs.view(np.uint16).T)
+    assert np.array_equal(xq.cpu().numpy(), rq)
+
+
+def reference(x16, w, bits):
+    wq, sw = oracle.quantize(w, 6, 128)
+    xq, sxg = oracle.quantize(x16.astype(np.float32), bits, 128)
+    acc_g = oracle.matmul(xq, wq, 128)                               # [M, N, G]
+    y = oracle.dequant_xgroup(acc_g, sxg, sw)
+    terms = np.abs(acc_g.astype(np.float64) * sw.astype(np.float64)[None, :, :] *
+                   sxg.astype(np.float64)[:, None, :])
+    G = terms.shape[2]
+    # fp32: each term is rounded twice before it is added, the sum G times
+    slack = terms.sum(2) * (G + 2) * 2.0**-23
+    return xq, sxg, y, slack
+
+
+def assert_close(got, want, slack):
+    d = np.abs(ordered(got) - ordered(want))
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    ulp = np.abs(want.astype(np.float64)) * 2.0**-10 + 2.0**-24
+    bad = (d > 1) & (err > ulp + slack)
+    assert not bad.any(), (int(bad.sum()), got[bad][:5], want[bad][:5])
+
+
+CASES = [(1, 256, 128), (4, 1280, 160), (8, 4096, 64), (32, 1024, 320), (33, 640, 96),
+         (64, 2048, 128), (100, 1024, 64), (200, 512, 128)]
+
+
+@pytest.mark.parametrize("bits", [6, 8])
+@pytest.mark.parametrize("M,K,N", CASES)
+def test_linear_g128(M, K, N, bits):
+    say(f"linear_g128 M={M} K={K} N={N} A{bits}")
+    w = synth.weights(N, K, 0.02, seed=200 + N)
+    x = synth.activations(M, K, seed=300 + M, outlier_frac=0.02)
+    rq, rsg, ry, slack = reference(x, w, bits)
+    packed = fq.pack_w6(*fq.quant_w6(to_dev(w), 128), 128)
+    xq, sxg = fq.quant_act_g128(to_dev(x), bits)
+    assert np.array_equal(xq.cpu().numpy(), rq)
+    assert np.array_equal(sxg.cpu().numpy().view(np.uint16), rsg.view(np.uint16).T)
+    y = fq.linear_g128(packed, N, K, xq, sxg)
+    assert_close(y.cpu().numpy(), ry, slack)
+    # scales that are constant along K must reproduce the per-token entry point
+    sx = sxg[0].contiguous()
+    flat = sx[None, :].expand(K // 128, M).contiguous()
+    y_tok = fq.gemv_w6a8(packed, N, K, 128, xq=xq, sx=sx)
+    y_grp = fq.linear_g128(packed, N, K, xq, flat)
+    d = np.abs(ordered(y_tok.cpu().numpy()) - ordered(y_grp.cpu().numpy()))
+    assert d.max() <= 1
+
+
+@pytest.mark.parametrize("split,waves", [(2, 4), (3, 8), (5, 16)])
+def test_linear_g128_k_splits(split, waves):
+    say(f"linear_g128 split={split} waves={waves}")
+    M, K, N = 9, 2560, 96
+    w = synth.weights(N, K, 0.02, seed=7)
+    x = synth.activations(M, K, seed=8, outlier_frac=0.02)
+    _, _, ry, slack = reference(x, w, 8)
+    packed = fq.pack_w6(*fq.quant_w6(to_dev(w), 128), 128)
+    xq, sxg = fq.quant_act_g128(to_dev(x), 8)
+    fq.set_dispatch(1, split, waves, 0)
+    try:
+        y = fq.linear_g128(packed, N, K, xq, sxg,
+                           workspace=fq.make_workspace(M, N, K, DEV, extra=split * M * N * 4))
+        torch.cuda.synchronize()
+    finally:
+        fq.set_dispatch(0, 0, 0, 0)
+    assert_close(y.cpu().numpy(), ry, slack)
+
+
+def test_linear_g128_decode_shape_sampled():
+    """LLaMA-2-13B attention projection (5120 x 5120), batched decode M = 32."""
+    say("linear_g128 13B 5120x5120 M=32")
+    M, K, N = 32, 5120, 5120
+    w = synth.weights(N, K, 0.02, seed=21)
+    x = synth.activations(M, K, seed=22, outlier_frac=0.01, outlier_scale=50.0)
+    cols = np.unique(np.concatenate([[0, 31, 32, N - 1],
+                                     np.random.default_rng(5).integers(0, N, 150)]))
+    _, _, ry, slack = reference(x, w[cols], 6)
+    packed = fq.pack_w6(*fq.quant_w6(to_dev(w), 128), 128)
+    xq, sxg = fq.quant_act_g128(to_dev(x), 6)
+    y = fq.linear_g128(packed, N, K, xq, sxg).cpu().numpy()[:, cols]
+    assert_close(y, ry, slack)

@@ -216,8 +216,9 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq,
  *   y           dev, fp16 [M,N], out, 16-byte aligned
  *   workspace   as for flexq_gemm_*, flexq_workspace_bytes(M,N,K) bytes
  * Same shape and alignment rules and status codes as the calls above; any
- * M >= 1.  (Runs the streaming kernel 128 tokens at a time: built for decode
- * batches; prefill-size M works but is not tuned.)
+ * M >= 1.  The tiled kernel (larger M) fetches the scales four bytes at a time
+ * and needs an even sxg_stride; with an odd one the call still works, on the
+ * streaming kernel, 128 tokens at a time.
  */
 flexq_status flexq_quant_act_g128(const uint16_t *x, int M, int K, int act_bits,
                                   int8_t *xq, uint16_t *sxg, int sxg_stride,

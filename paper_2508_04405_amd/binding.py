@@ -203,14 +203,15 @@ def swiglu_quant(gate_up, act_bits, want_h=False, out=None):
 
 
 def quant_act_g128(x, act_bits):
-    """fp16 X[M,K] -> (int8 codes [M,K], fp16 scales [K/128, M]) with one scale per token and
-    group of 128 along K; the scales are group-major."""
+    """fp16 X[M,K] -> (int8 codes [M,K], fp16 scales [K/128, stride >= M]) with one scale per
+    token and group of 128 along K; the scales are group-major, rows padded to a multiple of 64."""
     lib = load()
     _dev(x, torch.float16)
     M, K = x.shape
     xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
-    sxg = torch.empty((K // 128, M), dtype=torch.float16, device=x.device)
-    _check(lib.flexq_quant_act_g128(_ptr(x), M, K, act_bits, _ptr(xq), _ptr(sxg), M, _stream()))
+    stride = (M + 63) // 64 * 64         # even, as the tiled kernel wants; padding stays unwritten
+    sxg = torch.zeros((K // 128, stride), dtype=torch.float16, device=x.device)
+    _check(lib.flexq_quant_act_g128(_ptr(x), M, K, act_bits, _ptr(xq), _ptr(sxg), stride, _stream()))
     return xq, sxg
 
 

@@ -152,7 +152,8 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     (void)prefer_stream;
     const bool tiled_ok = (long)(M + 256) * K < (1L << 32) && (long)N * K / 4 * 3 < (1L << 32);
     bool stream_kernel = M <= 32 || (M <= 64 && ((long)N * K <= (1L << 26) || !tiled_ok));
-    if (sxg) stream_kernel = true;   // group-wise activation scales: streaming kernel, 128 rows a launch
+    // group-wise activation scales reach the tiled kernel by 4-byte DMA loads: even stride
+    if (sxg && (sxg_stride % 2 != 0 || !tiled_ok)) stream_kernel = true;
     if (forced == 1) stream_kernel = true;
     if (forced == 2) stream_kernel = false;
 
@@ -187,6 +188,7 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
         if ((long)(M + 256) * K >= (1L << 32) || (long)N * K / 4 * 3 >= (1L << 32)) return FLEXQ_ESHAPE;
         a.xq = xq;
         a.sx = sx;
+        a.sxg = sxg;
         a.M = M;
         a.y = y;
         a.acc_out = acc_out;

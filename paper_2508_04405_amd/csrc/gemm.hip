@@ -56,7 +56,7 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <int WM, int WN, int MT, int NT, bool GROUP, int WPE>
+template <int WM, int WN, int MT, int NT, int GROUP, int WPE>
 __global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
 {
@@ -143,6 +143,33 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     }
     const unsigned wlane = (unsigned)lane * 16u;
 
+    // ---- GROUP == 2: the tile's token scales of one group, 2 bytes each, follow the
+    // activations into LDS (one 4-byte DMA load per lane covers the 128 rows).  A ring of
+    // four slots: a stage's scales are still read at the start of the next stage (the
+    // scaling runs one block behind the MFMAs), so its slot is reused three stages later,
+    // with a stage barrier in between.  Every wavefront issues the same load (the bytes
+    // land identically), which keeps the per-wavefront load count uniform.
+    static_assert(GROUP != 2 || (BM == 128 && WM == 1), "one 4-byte DMA load per lane covers the tile's rows");
+    constexpr int XSRING = 3 * XSTAGE;          // byte offset of the ring in LDS
+    constexpr int XSSLOT = BM * 2;
+    const __amdgpu_buffer_rsrc_t xsrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(GROUP == 2 ? a.sxg : a.scales), 0,
+        GROUP == 2 ? (unsigned)((long)KT * a.sxg_stride * 2) : 0u, 0x00020000);
+    // lanes whose two rows lie beyond M fetch nothing (an offset past the buffer reads as zero)
+    const unsigned xsoff = bm0 + 2 * lane < M ? (unsigned)(bm0 + 2 * lane) * 2u : 0x80000000u;
+    auto dma_xs = [&](int kb) {
+        if constexpr (GROUP == 2) {
+            uint8_t *dst = lds + XSRING + (kb & 3) * XSSLOT;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                xsrsrc, (void __attribute__((address_space(3))) *)dst, 4, xsoff,
+                (unsigned)(kb0 + kb) * (unsigned)a.sxg_stride * 2u, 0, 0);
+        }
+    };
+    const int xslane = 8 * (lane >> 5);         // register r of a block: row 8 (r / 4) + 4 (lane / 32) + r % 4
+    auto xs_ptr = [&](int kb, int mt, int q) {  // the four scales of quarter q of row block mt, stage kb
+        return reinterpret_cast<const uint2 *>(lds + XSRING + (kb & 3) * XSSLOT + 64 * mt + 16 * q + xslane);
+    };
+
     v16i acc[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -154,6 +181,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     v16f facc[GROUP ? MT : 1][GROUP ? NT : 1];
     v16i gpart[3];             // group mode: int32 sums of the block in flight and the two before
     float gs_prev[NT];         // scales of the stage before, for the blocks it leaves unscaled
+    uint2 xsq = make_uint2(0u, 0u);   // GROUP == 2: the four token scales of the quarter due next
     if (GROUP) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) gs_prev[nt] = 0.0f;
@@ -186,10 +214,14 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     // prologue: stages 0 and 1 in flight, stage 0 landed
     dma_x(0, 0);
     load_w(0, std::integral_constant<int, 0>{});
+    dma_xs(0);
     if (KN > 1) {
         dma_x(1, 1);
         load_w(1, std::integral_constant<int, 1>{});
+        dma_xs(1);
     }
+    if constexpr (GROUP == 2)   // "the stage before the first": its scales are read (times zero sums)
+        *reinterpret_cast<unsigned *>(lds + XSRING + 3 * XSSLOT + 4 * lane) = 0u;
     wait_vmcnt<0>();
     v4i bf_first = unpack_kstep(wreg[0][0], 0);   // weight operand of a stage's first step
     lds_barrier();
@@ -205,6 +237,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
         if (more2) {  // two stages ahead: that buffer was last read in stage kb - 1
             dma_x(kb + 2, NXT2);
             load_w(kb + 2, std::integral_constant<int, NXT2>{});
+            dma_xs(kb + 2);
         }
         const uint8_t *xs = lds + CUR * XSTAGE;
         if constexpr (GROUP) {
@@ -218,9 +251,13 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             // one block and one slot later, when its last MFMA has surely
             // finished.  Three block buffers rotate so that the block two back,
             // whose last quarter is still being read, is not the one overwritten.
-            v4i af[MT][4];
+            // Activation operands: all of the stage's up front, or (mode 2, which has
+            // no registers to spare) one row block ahead of its MFMAs.
+            constexpr bool AF_AHEAD = GROUP == 2;
+            static_assert(!AF_AHEAD || (MT * NT) % 2 == 0, "two operand sets alternate by block");
+            v4i af[AF_AHEAD ? 2 : MT][4];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < (AF_AHEAD ? 1 : MT); ++mt)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     af[mt][j] = *reinterpret_cast<const v4i *>(
@@ -241,7 +278,13 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
                     const int buf = (CUR * NB + b) % 3;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        gpart[buf] = mfma_i8(af[mt][j], bf[j], j == 0 ? vzero : gpart[buf]);
+                        gpart[buf] = mfma_i8(af[AF_AHEAD ? (b & 1) : mt][j], bf[j],
+                                             j == 0 ? vzero : gpart[buf]);
+                        if constexpr (AF_AHEAD) {
+                            if (b + 1 < NB)
+                                af[(b + 1) & 1][j] = *reinterpret_cast<const v4i *>(
+                                    xs + lds_off(arow + 32 * ((b + 1) % MT), 2 * j + ahalf));
+                        }
                         // the quarter that is due: block b - 1 (quarter j - 1), or the last
                         // quarter of block b - 2; blocks before this stage's first belong to
                         // the previous stage and carry its scale
@@ -252,10 +295,32 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
                         const int cbuf = (CUR * NB + b + (c - b) + 3) % 3;
                         const float cgs = c >= 0 ? gsv[cnt] : gs_prev[cnt];
                         float t[4];
+                        if constexpr (GROUP == 2) {
+                            // token scales of this quarter were fetched during the slot
+                            // before; fetch the next slot's now
+                            const uint2 mine = xsq;
+                            {
+                                const int b2 = j < 3 ? b : b + 1, j2 = j < 3 ? j + 1 : 0;
+                                const int c2 = j2 == 0 ? b2 - 2 : b2 - 1, q2 = j2 == 0 ? 3 : j2 - 1;
+                                // past this stage's last slot: the next stage's first unit,
+                                // which is this stage's block NB - 2
+                                const int kb2 = b2 == NB ? kb : (c2 >= 0 ? kb : kb - 1);
+                                const int cw2 = b2 == NB ? NB - 2 : (c2 + NB) % NB;
+                                xsq = *xs_ptr(kb2, cw2 % MT, q2);
+                            }
+                            const unsigned sh[2] = {mine.x, mine.y};
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            t[r] = __builtin_fmaf((float)gpart[cbuf][4 * q + r], cgs,
-                                                  facc[cmt][cnt][4 * q + r]);
+                            for (int r = 0; r < 4; ++r) {
+                                const float xs = h2f((uint16_t)(sh[r >> 1] >> (16 * (r & 1))));
+                                t[r] = __builtin_fmaf((float)gpart[cbuf][4 * q + r] * cgs, xs,
+                                                      facc[cmt][cnt][4 * q + r]);
+                            }
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                t[r] = __builtin_fmaf((float)gpart[cbuf][4 * q + r], cgs,
+                                                      facc[cmt][cnt][4 * q + r]);
+                        }
                         // an empty volatile statement that "uses" the four results: code
                         // motion cannot sink the scaling out of the MFMAs' shadow
                         asm volatile("" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));
@@ -306,7 +371,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
         // stage kb + 1 must have landed in LDS (every wavefront's share) before
         // anyone reads it; the loads of stage kb + 2 may stay in flight
         if (more2)
-            wait_vmcnt<XDMA + WLOADS + (GROUP ? NT : 0)>();
+            wait_vmcnt<XDMA + WLOADS + (GROUP ? NT : 0) + (GROUP == 2 ? 1 : 0)>();
         else
             wait_vmcnt<0>();
         if constexpr (!GROUP) bf_first = unpack_kstep(wreg[(CUR + 1) % 3][0], 0);   // has landed
@@ -332,9 +397,18 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             for (int i = 0; i < 3; ++i)
                 if (i == buf) {
 #pragma unroll
-                    for (int r = r0; r < 16; ++r)
-                        facc[cmt][cnt][r] =
-                            __builtin_fmaf((float)gpart[i][r], gs_prev[cnt], facc[cmt][cnt][r]);
+                    for (int r = r0; r < 16; ++r) {
+                        if constexpr (GROUP == 2) {
+                            const uint2 four = *xs_ptr(KN - 1, cmt, r >> 2);
+                            const unsigned half = (r & 2) ? four.y : four.x;
+                            const float xs = h2f((uint16_t)(half >> (16 * (r & 1))));
+                            facc[cmt][cnt][r] = __builtin_fmaf((float)gpart[i][r] * gs_prev[cnt], xs,
+                                                               facc[cmt][cnt][r]);
+                        } else {
+                            facc[cmt][cnt][r] = __builtin_fmaf((float)gpart[i][r], gs_prev[cnt],
+                                                               facc[cmt][cnt][r]);
+                        }
+                    }
                 }
         };
         fold(before, NB - 2, 12);
@@ -364,7 +438,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     for (int c = 0; c < 4; ++c) swv[c] = GROUP ? 0.25f : h2f(a.scales[cvalid ? n_lane + c : 0]);
     // scale and store four columns of row m (q: exact int32 sums, or fp32 group sums)
     auto finish = [&](const v4i &q, int m) {
-        const float sxm = h2f(a.sx[m]);
+        const float sxm = GROUP == 2 ? 1.0f : h2f(a.sx[m]);   // mode 2 scaled per group already
         uint16_t h[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c)
@@ -471,12 +545,12 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
 #endif
 }
 
-template <int WM, int WN, int MT, int NT, bool GROUP, int WPE>
+template <int WM, int WN, int MT, int NT, int GROUP, int WPE>
 hipError_t launch_cfg(const flexq::LinearArgs &a, hipStream_t st)
 {
     constexpr int BM = WM * MT * 32, BN = WN * NT * 32;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    const size_t lds_bytes = 3 * BM * 128;
+    const size_t lds_bytes = 3 * BM * 128 + (GROUP == 2 ? 4 * BM * 2 : 0);
     auto kern = gemm_kernel<WM, WN, MT, NT, GROUP, WPE>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -502,8 +576,9 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
     // 128x128 tiles with two workgroups per CU keep the int32 sums out of the AGPR half
     // of the register file (which vector instructions cannot read directly).
     if (a.group != 0) {
-        if (cfg == 21) return launch_cfg<1, 4, 4, 2, true, 1>(a, st);   // 128x256, 1 wave/SIMD
-        return launch_cfg<1, 4, 4, 1, true, 2>(a, st);
+        if (a.sxg) return launch_cfg<1, 4, 4, 1, 2, 2>(a, st);          // scales per group on both operands
+        if (cfg == 21) return launch_cfg<1, 4, 4, 2, 1, 1>(a, st);      // 128x256, 1 wave/SIMD
+        return launch_cfg<1, 4, 4, 1, 1, 2>(a, st);
     }
     if (a.split_k > 1 && cfg == 0) cfg = 8;   // K splits are chosen for 128x128 tiles
     if (cfg == 0) {
@@ -515,12 +590,12 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
         cfg = tiles_big <= 384 ? 8 : 7;
     }
     switch (cfg) {
-    case 1: return launch_cfg<2, 2, 4, 4, false, 1>(a, st);   // 256x256, 4 waves, 1 wave/SIMD
-    case 2: return launch_cfg<2, 4, 4, 2, false, 2>(a, st);   // 256x256, 8 waves (128x64 each)
-    case 6: return launch_cfg<1, 4, 8, 2, false, 1>(a, st);   // 256x256, 4 waves side by side (256x64 each)
-    case 7: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);   // 128x256, 4 waves side by side, 2 workgroups/CU
-    case 8: return launch_cfg<1, 4, 4, 1, false, 3>(a, st);   // 128x128, 4 waves side by side, 3 workgroups/CU
-    default: return launch_cfg<1, 4, 4, 2, false, 2>(a, st);
+    case 1: return launch_cfg<2, 2, 4, 4, 0, 1>(a, st);   // 256x256, 4 waves, 1 wave/SIMD
+    case 2: return launch_cfg<2, 4, 4, 2, 0, 2>(a, st);   // 256x256, 8 waves (128x64 each)
+    case 6: return launch_cfg<1, 4, 8, 2, 0, 1>(a, st);   // 256x256, 4 waves side by side (256x64 each)
+    case 7: return launch_cfg<1, 4, 4, 2, 0, 2>(a, st);   // 128x256, 4 waves side by side, 2 workgroups/CU
+    case 8: return launch_cfg<1, 4, 4, 1, 0, 3>(a, st);   // 128x128, 4 waves side by side, 3 workgroups/CU
+    default: return launch_cfg<1, 4, 4, 2, 0, 2>(a, st);
     }
 }
 

@@ -297,19 +297,28 @@ void skinny_kernel(flexq::LinearArgs a)
 #pragma unroll
                         for (int j = 0; j < 4; ++j) part = mfma_i8(af[mt][j], b[j], part);
                         const float gs = h2f(st[p].gs);
-                        if (GROUP == 2) {
-                            // register r holds token 8 (r / 4) + 4 (lane / 32) + r % 4, whose
-                            // scale for this tile sits in the lane of that number
-                            const int mine = st[p].xs[mt];
+                        // registers 4q .. 4q+3 hold token rows 8q .. 8q+7 of this row block:
+                        // quarters wholly beyond M are padding and are skipped (uniform)
+                        const int live = (M - 32 * mt + 7) >> 3;
+                        const int mine = GROUP == 2 ? st[p].xs[mt] : 0;
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const int src = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                                const float xs = h2f((uint16_t)__builtin_amdgcn_ds_bpermute(4 * src, mine));
-                                facc[mt][r] = __builtin_fmaf((float)part[r] * gs, xs, facc[mt][r]);
+                        for (int q = 0; q < 4; ++q) {
+                            if (q < live) {
+#pragma unroll
+                                for (int r = 4 * q; r < 4 * q + 4; ++r) {
+                                    if (GROUP == 2) {
+                                        // the scale of token 8q + 4 (lane / 32) + r % 4 for this
+                                        // tile sits in the lane of that number
+                                        const int src = 8 * q + 4 * (lane >> 5) + (r & 3);
+                                        const float xs = h2f(
+                                            (uint16_t)__builtin_amdgcn_ds_bpermute(4 * src, mine));
+                                        facc[mt][r] =
+                                            __builtin_fmaf((float)part[r] * gs, xs, facc[mt][r]);
+                                    } else {
+                                        facc[mt][r] = __builtin_fmaf((float)part[r], gs, facc[mt][r]);
+                                    }
+                                }
                             }
-                        } else {
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) facc[mt][r] += (float)part[r] * gs;
                         }
                     } else {
 #pragma unroll

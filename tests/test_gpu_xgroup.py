@@ -43,7 +43,7 @@ def test_quant_act_g128_bit_exact(M, K, bits):
     x16 = x.astype(np.float16)
     xq, sxg = fq.quant_act_g128(to_dev(x16), bits)
     rq, rs = oracle.quantize(x16.astype(np.float32), bits, 128)      # rs is [M, K/128]
-    assert np.array_equal(sxg.cpu().numpy().view(np.uint16), rs.view(np.uint16).T)
+    assert np.array_equal(sxg.cpu().numpy().view(np.uint16)[:, :M], rs.view(np.uint16).T)
     assert np.array_equal(xq.cpu().numpy(), rq)
 
 
@@ -69,29 +69,42 @@ def assert_close(got, want, slack):
 
 
 CASES = [(1, 256, 128), (4, 1280, 160), (8, 4096, 64), (32, 1024, 320), (33, 640, 96),
-         (64, 2048, 128), (100, 1024, 64), (200, 512, 128)]
+         (64, 2048, 128), (100, 1024, 64), (200, 512, 128), (129, 128, 32), (300, 1408, 288)]
 
 
+@pytest.mark.parametrize("kernel", ["auto", "stream", "tiled"])
 @pytest.mark.parametrize("bits", [6, 8])
 @pytest.mark.parametrize("M,K,N", CASES)
-def test_linear_g128(M, K, N, bits):
-    say(f"linear_g128 M={M} K={K} N={N} A{bits}")
+def test_linear_g128(M, K, N, bits, kernel):
+    say(f"linear_g128 M={M} K={K} N={N} A{bits} {kernel}")
+    fq.set_dispatch({"auto": 0, "stream": 1, "tiled": 2}[kernel], 0, 0, 0)
+    try:
+        run_linear_g128(M, K, N, bits)
+        torch.cuda.synchronize()
+    finally:
+        fq.set_dispatch(0, 0, 0, 0)
+
+
+def run_linear_g128(M, K, N, bits):
     w = synth.weights(N, K, 0.02, seed=200 + N)
     x = synth.activations(M, K, seed=300 + M, outlier_frac=0.02)
     rq, rsg, ry, slack = reference(x, w, bits)
     packed = fq.pack_w6(*fq.quant_w6(to_dev(w), 128), 128)
     xq, sxg = fq.quant_act_g128(to_dev(x), bits)
     assert np.array_equal(xq.cpu().numpy(), rq)
-    assert np.array_equal(sxg.cpu().numpy().view(np.uint16), rsg.view(np.uint16).T)
+    assert np.array_equal(sxg.cpu().numpy().view(np.uint16)[:, :M], rsg.view(np.uint16).T)
     y = fq.linear_g128(packed, N, K, xq, sxg)
     assert_close(y.cpu().numpy(), ry, slack)
     # scales that are constant along K must reproduce the per-token entry point
-    sx = sxg[0].contiguous()
-    flat = sx[None, :].expand(K // 128, M).contiguous()
+    sx = sxg[0, :M].contiguous()
+    flat = sxg[0][None, :].expand(K // 128, sxg.shape[1]).contiguous()
     y_tok = fq.gemv_w6a8(packed, N, K, 128, xq=xq, sx=sx)
     y_grp = fq.linear_g128(packed, N, K, xq, flat)
-    d = np.abs(ordered(y_tok.cpu().numpy()) - ordered(y_grp.cpu().numpy()))
-    assert d.max() <= 1
+    # (fp32 sums in different orders: the same bound as against the oracle)
+    ref_flat = oracle.dequant_xgroup(oracle.matmul(rq, oracle.quantize(w, 6, 128)[0], 128),
+                                     np.repeat(rsg[:, :1], K // 128, 1), oracle.quantize(w, 6, 128)[1])
+    assert_close(y_grp.cpu().numpy(), ref_flat, slack * 4 + np.abs(ref_flat.astype(np.float64)) * 2.0**-9)
+    assert_close(y_tok.cpu().numpy(), ref_flat, slack * 4 + np.abs(ref_flat.astype(np.float64)) * 2.0**-9)
 
 
 @pytest.mark.parametrize("split,waves", [(2, 4), (3, 8), (5, 16)])
@@ -111,6 +124,42 @@ def test_linear_g128_k_splits(split, waves):
     finally:
         fq.set_dispatch(0, 0, 0, 0)
     assert_close(y.cpu().numpy(), ry, slack)
+
+
+@pytest.mark.parametrize("split", [2, 3])
+@pytest.mark.parametrize("M", [70, 260])
+def test_linear_g128_tiled_k_splits(split, M):
+    say(f"linear_g128 tiled split={split} M={M}")
+    K, N = 2560, 160
+    w = synth.weights(N, K, 0.02, seed=9)
+    x = synth.activations(M, K, seed=10, outlier_frac=0.02)
+    _, _, ry, slack = reference(x, w, 6)
+    packed = fq.pack_w6(*fq.quant_w6(to_dev(w), 128), 128)
+    xq, sxg = fq.quant_act_g128(to_dev(x), 6)
+    fq.set_dispatch(2, split, 0, 0)
+    try:
+        y = fq.linear_g128(packed, N, K, xq, sxg,
+                           workspace=fq.make_workspace(M, N, K, DEV, extra=split * M * N * 4))
+        torch.cuda.synchronize()
+    finally:
+        fq.set_dispatch(0, 0, 0, 0)
+    assert_close(y.cpu().numpy(), ry, slack)
+
+
+def test_linear_g128_prefill_shape_sampled():
+    """LLaMA-2-13B gate+up projection (5120 -> 13824), prefill M = 2048 (tiled kernel)."""
+    say("linear_g128 13B 5120x13824 M=2048")
+    M, K, N = 2048, 5120, 13824
+    rows = np.unique(np.concatenate([[0, M - 1], np.random.default_rng(6).integers(0, M, 24)]))
+    cols = np.unique(np.concatenate([[0, 31, 32, N - 1],
+                                     np.random.default_rng(7).integers(0, N, 100)]))
+    x = synth.activations(M, K, seed=24, outlier_frac=0.01)
+    packed = fq.pack_w6(*fq.quant_w6(to_dev(synth.weights(N, K, 0.02, seed=23)), 128), 128)
+    w_cols = synth.weight_rows_at(N, K, 0.02, 23, cols)
+    _, _, ry, slack = reference(x[rows], w_cols, 8)
+    xq, sxg = fq.quant_act_g128(to_dev(x), 8)
+    y = fq.linear_g128(packed, N, K, xq, sxg).cpu().numpy()[np.ix_(rows, cols)]
+    assert_close(y, ry, slack)
 
 
 def test_linear_g128_decode_shape_sampled():

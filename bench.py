@@ -93,6 +93,150 @@ def sweep(args, torch, fq, synth, dev):
         del bufs
 
 
+def layer_table(args, torch, fq, synth, dev):
+    """One decoder layer's seven linears as four calls (fused QKV, O, fused gate+up, down), each
+    fed by the producer that quantizes its input: RMS norm + quantize before QKV and gate+up,
+    the stand-alone quantizer before O (its input comes from attention, which is not part of
+    this path), gated SiLU + quantize before down.  Two policies: the paper's (A8 on the down
+    projection only) and a layer running all seven linears at A8 (the flagged layers of the
+    13B configuration).  The launches are captured in a HIP graph and replayed."""
+    models = [("LLaMA-2-7B", 4096, 11008, 4096 * 3, 0, (1, 8, 512, 2048)),
+              ("LLaMA-2-13B, group-128 weight scales", 5120, 13824, 5120 * 3, 128, (32, 2048)),
+              ("LLaMA-2-70B (GQA: 10240-wide QKV)", 8192, 28672, 10240, 0, (1, 16, 1024, 4096))]
+    print("| model | M | policy | us per layer | TOP/s | weight GB/s |")
+    print("|---|---|---|---|---|---|")
+    for name, H, F, QKV, group, Ms in models:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(5)
+
+        def make(N, K):
+            w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+            p = fq.pack_w6(*fq.quant_w6(w, group), group)
+            del w
+            return p
+        w_qkv, w_o, w_gu, w_dn = make(QKV, H), make(H, H), make(2 * F, H), make(H, F)
+        gamma = torch.from_numpy(synth.norm_gain(H, seed=6)).to(dev)
+        wbytes = 0.75 * (QKV * H + H * H + 2 * F * H + H * F)
+        ops1 = 2.0 * (QKV * H + H * H + 2 * F * H + H * F)
+        for M in Ms:
+            h = torch.from_numpy(synth.activations(M, H, seed=7, outlier_frac=0.01)).to(dev)
+            attn = torch.from_numpy(synth.activations(M, H, seed=8, outlier_frac=0.01)).to(dev)
+            bufs = {k: (torch.empty((M, n), dtype=torch.int8, device=dev),
+                        torch.empty((M,), dtype=torch.float16, device=dev))
+                    for k, n in (("h", H), ("f", F))}
+            outs = {k: torch.empty((M, n), dtype=torch.float16, device=dev)
+                    for k, n in (("qkv", QKV), ("o", H), ("gu", 2 * F), ("dn", H))}
+            wss = {k: fq.make_workspace(M, n, kk, dev)
+                   for k, n, kk in (("qkv", QKV, H), ("o", H, H), ("gu", 2 * F, H), ("dn", H, F))}
+            for policy, bits in (("A6, A8 on down (the paper's)", (6, 6, 6, 8)),
+                                 ("all seven linears A8", (8, 8, 8, 8))):
+                def gemm(bits_):
+                    return fq.gemm_w6a6 if bits_ == 6 else fq.gemm_w6a8
+
+                def layer():
+                    xq, sx = fq.rmsnorm_quant(h, gamma, 1e-5, bits[0], out=bufs["h"])
+                    gemm(bits[0])(w_qkv, QKV, H, group, xq=xq, sx=sx, workspace=wss["qkv"], out=outs["qkv"])
+                    xq, sx = fq.quant_act(attn, bits[1], out=bufs["h"])
+                    gemm(bits[1])(w_o, H, H, group, xq=xq, sx=sx, workspace=wss["o"], out=outs["o"])
+                    xq, sx = fq.rmsnorm_quant(outs["o"], gamma, 1e-5, bits[2], out=bufs["h"])
+                    gemm(bits[2])(w_gu, 2 * F, H, group, xq=xq, sx=sx, workspace=wss["gu"], out=outs["gu"])
+                    xq, sx = fq.swiglu_quant(outs["gu"], bits[3], out=bufs["f"])
+                    gemm(bits[3])(w_dn, H, F, group, xq=xq, sx=sx, workspace=wss["dn"], out=outs["dn"])
+                stream = torch.cuda.Stream()
+                stream.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(stream):
+                    layer()
+                    torch.cuda.synchronize()
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph, stream=stream):
+                        layer()
+                    for _ in range(args.warmup):
+                        graph.replay()
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(args.steps):
+                        graph.replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / args.steps
+                print("| %s | %d | %s | %.1f | %.0f | %.0f |" % (name, M, policy, us, ops1 * M / us / 1e6,
+                                                              wbytes / us / 1e3), flush=True)
+        del w_qkv, w_o, w_gu, w_dn
+
+
+def ablation(args, torch, fq, synth, dev):
+    """GEMV time with one design choice of the streaming kernel undone per row (the paper's
+    Table 6 on this machine).  Each shape is replicated until the copies exceed twice the
+    Infinity Cache, the launches over all copies are captured in a HIP graph and the graph is
+    replayed, so a row is kernel time from cold HBM without host launch overhead."""
+    shapes = [("(1,4096)x(4096,4096) W6A6", 4096, 4096, 6, 44),
+              ("(1,28672)x(28672,8192) W6A8", 28672, 8192, 8, 3)]
+    rows = [("full design (automatic dispatch)", dict()),
+            ("no K split across workgroups", dict(split=1)),
+            ("4 wavefronts per workgroup instead of 8", dict(waves=4)),
+            ("16 wavefronts per workgroup", dict(waves=16)),
+            ("cached instead of non-temporal weight loads", dict(ablate=1)),
+            ("one weight tile in flight per wavefront instead of four", dict(ablate=2)),
+            ("two weight tiles in flight", dict(ablate=3)),
+            ("activations from global memory per tile, not staged in LDS", dict(ablate=4)),
+            ("separate quantize launch (kernel pair) instead of the fused prologue", dict(pair=True)),
+            ("fused quantize prologue (one launch from fp16 activations)", dict(fused=True))]
+    print("| variant | " + " | ".join(s[0] + " us (GB/s)" for s in shapes) + " |")
+    print("|---|" + "---|" * len(shapes))
+    table = {r[0]: [] for r in rows}
+    for name, K, N, bits, copies in shapes:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(77)
+        w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+        one = fq.pack_w6(*fq.quant_w6(w))
+        del w
+        packed = [one.clone() for _ in range(copies)]
+        x = torch.from_numpy(synth.activations(1, K, seed=78, outlier_frac=0.01)).to(dev)
+        xq, sx = fq.quant_act(x, bits)
+        y = torch.empty((1, N), dtype=torch.float16, device=dev)
+        ws = fq.make_workspace(1, N, K, dev)
+        gemv = fq.gemv_w6a6 if bits == 6 else fq.gemv_w6a8
+        nbytes = gemm_bytes(1, N, K)
+        for label, opt in rows:
+            fq.set_dispatch(1, opt.get("split", 0), opt.get("waves", 8 if "ablate" in opt else 0), 0)
+            fq.set_ablation(opt.get("ablate", 0))
+
+            def launches():
+                for p in packed:
+                    if opt.get("fused"):
+                        gemv(p, N, K, 0, x_fp16=x, workspace=ws, out=y)
+                    else:
+                        if opt.get("pair"):
+                            fq.quant_act(x, bits, out=(xq, sx))
+                        gemv(p, N, K, 0, xq=xq, sx=sx, workspace=ws, out=y)
+            try:
+                stream = torch.cuda.Stream()
+                stream.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(stream):
+                    launches()
+                    torch.cuda.synchronize()
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph, stream=stream):
+                        launches()
+                    for _ in range(args.warmup):
+                        graph.replay()
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(args.steps):
+                        graph.replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / (args.steps * copies)
+                table[label].append("%.2f (%.0f)" % (us, nbytes / us / 1e3))
+            finally:
+                fq.set_ablation(0)
+                fq.set_dispatch(0, 0, 0, 0)
+    for label, _ in rows:
+        print("| %s | " % label + " | ".join(table[label]) + " |", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +251,13 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line, print a table of per-layer GEMM / GEMV "
                          "times over token counts M = 1 .. 4096 (library's own dispatch)")
+    ap.add_argument("--layer", action="store_true",
+                    help="instead of the benchmark line, print the time of one decoder layer's "
+                         "seven linears (four GEMM calls fed by the fused producers) for the "
+                         "LLaMA-2 7B / 13B / 70B shapes")
+    ap.add_argument("--ablation", action="store_true",
+                    help="instead of the benchmark line, print the decode-kernel ablation table "
+                         "(one design choice undone per row) on the paper's Table-6 shapes")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); "
@@ -135,6 +286,10 @@ def main():
 
     if args.sweep:
         return sweep(args, torch, fq, synth, dev)
+    if args.ablation:
+        return ablation(args, torch, fq, synth, dev)
+    if args.layer:
+        return layer_table(args, torch, fq, synth, dev)
 
     # ---- resident inputs: packed weights, fp16 activations -----------------
     gen = torch.Generator(device=dev)

@@ -239,6 +239,22 @@ flexq_status flexq_linear_g128(const void *packed, const int8_t *xq,
 flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg);
 
 /*
+ * Ablation hook (measurement only, in the manner of the paper's Table 6): undo
+ * ONE design choice of the streaming decode kernel for the next calls.
+ *   0  nothing undone (the default)
+ *   1  weight tiles through ordinary cached loads instead of non-temporal ones
+ *      (Section 4.3.2's evict-first hint, undone)
+ *   2  one weight tile in flight per wavefront instead of four (Section 4.3.6's
+ *      multi-stage pipeline, undone)     3  two tiles in flight
+ *   4  activations loaded per tile from global memory instead of staged once
+ *      in LDS
+ * Applies to per-channel scales, M <= 32, pre-quantized activations and 8
+ * wavefronts per workgroup; other calls return FLEXQ_EHIP while a choice is
+ * set.  Process-wide; FLEXQ_EINVAL for unknown values.  Results are unchanged.
+ */
+flexq_status flexq_set_ablation(int choice);
+
+/*
  * Measurement helpers (no arithmetic of the method): the ceilings a roofline
  * fraction can be read against on the machine at hand.
  *

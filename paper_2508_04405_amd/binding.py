@@ -63,6 +63,8 @@ def load():
     lib.flexq_probe_hbm_read.argtypes = [vp, c_size, vp, vp]
     lib.flexq_probe_mfma_i8.restype = c_int
     lib.flexq_probe_mfma_i8.argtypes = [vp, vp, c_int, c_int, vp, vp]
+    lib.flexq_set_ablation.restype = c_int
+    lib.flexq_set_ablation.argtypes = [c_int]
     lib.flexq_set_dispatch.restype = c_int
     lib.flexq_set_dispatch.argtypes = [c_int, c_int, c_int, c_int]
     _lib = lib
@@ -93,6 +95,10 @@ def layout_version():
 
 def packed_bytes(N, K, group=0):
     return load().flexq_packed_bytes(N, K, group)
+
+
+def set_ablation(choice=0):
+    _check(load().flexq_set_ablation(choice))
 
 
 def set_dispatch(which=0, split_k=0, waves=0, gemm_cfg=0):

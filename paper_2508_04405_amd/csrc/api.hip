@@ -10,6 +10,7 @@ namespace {
 std::atomic<int> g_force_kernel{0};
 std::atomic<int> g_force_split{0};
 std::atomic<int> g_force_waves{0};
+std::atomic<int> g_ablate{0};
 std::atomic<int> g_force_gemm_cfg{0};
 
 constexpr int kMaxRowBlocks = FLEXQ_WORKSPACE_COUNTER_BYTES / 4;
@@ -182,6 +183,7 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     a.qmax = act_bits == 6 ? 31.0f : 127.0f;
     a.sxg = nullptr;
     a.sxg_stride = sxg_stride;
+    a.ablate = g_ablate.load();
 
     if (!stream_kernel) {
         // the tiled kernel addresses both operands with 32-bit buffer offsets
@@ -402,6 +404,13 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq, co
 {
     return linear(8, true, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
                   workspace_bytes, stream);
+}
+
+flexq_status flexq_set_ablation(int choice)
+{
+    if (choice < 0 || choice > 4) return FLEXQ_EINVAL;
+    g_ablate.store(choice);
+    return FLEXQ_OK;
 }
 
 flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg)

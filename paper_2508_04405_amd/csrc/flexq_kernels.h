@@ -23,6 +23,7 @@ struct LinearArgs {
     float qmax;              // kernel (31 or 127) instead of reading xq / sx; else null
     const uint16_t *sxg;     // group-wise activation scales [K/128][sxg_stride] (group-major),
     int sxg_stride;          // or null: one scale per token in sx (sxg needs group == 128)
+    int ablate;              // 0, or which design choice of the streaming kernel to undo (measurement)
 };
 
 hipError_t launch_quant_w6(const float *w, int N, int K, int group, int8_t *wq, uint16_t *sw,

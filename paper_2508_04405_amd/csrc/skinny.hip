@@ -40,13 +40,16 @@ struct Stage {
 
 // GROUP: 0 = one scale per output channel and per token; 1 = weight scales per 128-k
 // group (Section 4.1.1), one scale per token; 2 = both operands scaled per group (Eq. 7).
-template <int MT, int GROUP, bool XLDS>
+template <int MT, int GROUP, bool XLDS, bool NTW>
 __device__ __forceinline__ void load_stage(Stage<MT, XLDS> &s, const v4i *packed,
                                            const uint16_t *scales, const int8_t *const (&xrow)[MT],
                                            const bool (&xact)[MT], long tile_index, int t, int lane,
                                            const uint16_t *sxg, int sxg_stride)
 {
-    s.w = load_packed_tile(packed + tile_index * (FLEXQ_TILE_BYTES / 16), lane);
+    // NTW: non-temporal loads, so that the weight stream (used once) does not displace
+    // the activations in L2; the cached form exists for the ablation only
+    s.w = NTW ? load_packed_tile(packed + tile_index * (FLEXQ_TILE_BYTES / 16), lane)
+              : load_packed_tile_cached(packed + tile_index * (FLEXQ_TILE_BYTES / 16), lane);
     if (!XLDS) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -83,7 +86,7 @@ __device__ __forceinline__ unsigned prologue_code(uint16_t hbits, float sf, floa
     return (unsigned)((int)q & 0xff);
 }
 
-template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE>
+template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE, bool NTW = true>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void skinny_kernel(flexq::LinearArgs a)
 {
@@ -158,7 +161,7 @@ void skinny_kernel(flexq::LinearArgs a)
     for (int p = 0; p < P; ++p) {
         const int t = tw + W * p;
         if (t < t1)
-            load_stage<MT, GROUP, XLDS>(st[p], packed, a.scales, xrow, xact, tile_base + t, t, lane,
+            load_stage<MT, GROUP, XLDS, NTW>(st[p], packed, a.scales, xrow, xact, tile_base + t, t, lane,
                                         a.sxg, a.sxg_stride);
     }
 
@@ -327,7 +330,7 @@ void skinny_kernel(flexq::LinearArgs a)
                 }
                 const int tn = t + W * P;
                 if (tn < t1)
-                    load_stage<MT, GROUP, XLDS>(st[p], packed, a.scales, xrow, xact, tile_base + tn,
+                    load_stage<MT, GROUP, XLDS, NTW>(st[p], packed, a.scales, xrow, xact, tile_base + tn,
                                                 tn, lane, a.sxg, a.sxg_stride);
                 t += W;
             }
@@ -422,11 +425,11 @@ void skinny_kernel(flexq::LinearArgs a)
     }
 }
 
-template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE>
+template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE, bool NTW = true>
 hipError_t launch_one(const flexq::LinearArgs &a, hipStream_t st)
 {
     const unsigned blocks = (unsigned)(a.N / 32) * (unsigned)a.split_k;
-    auto kern = skinny_kernel<MT, GROUP, XLDS, FUSEQ, P, W, WPE>;
+    auto kern = skinny_kernel<MT, GROUP, XLDS, FUSEQ, P, W, WPE, NTW>;
     size_t dyn = 0;
     if (XLDS) {
         const int KT = a.K / 128;
@@ -457,6 +460,17 @@ hipError_t pick(const flexq::LinearArgs &a, int waves, hipStream_t st)
         if (waves == 16) return launch_one<1, G, true, true, 4, 16, 4>(a, st);
         if (waves == 8) return launch_one<1, G, true, true, 4, 8, 4>(a, st);
         return launch_one<1, G, true, true, 4, 4, 4>(a, st);
+    }
+    // Ablation variants (measurement only): one design choice of the decode kernel undone.
+    if (a.ablate != 0) {
+        if (GROUP != 0 || a.M > 32 || a.x_fp16 || waves != 8) return hipErrorInvalidValue;
+        constexpr int G = 0;
+        if (a.ablate == 4) return launch_one<1, G, false, false, 4, 8, 4>(a, st);   // no LDS staging
+        if (!xlds) return hipErrorInvalidValue;
+        if (a.ablate == 1) return launch_one<1, G, true, false, 4, 8, 4, false>(a, st);   // cached loads
+        if (a.ablate == 2) return launch_one<1, G, true, false, 1, 8, 4>(a, st);   // one tile in flight
+        if (a.ablate == 3) return launch_one<1, G, true, false, 2, 8, 4>(a, st);   // two tiles in flight
+        return hipErrorInvalidValue;
     }
     if (a.M <= 32) {
         if (xlds) {

@@ -119,4 +119,7 @@ def test_other_entry_points_argument_errors():
     assert lib.flexq_set_dispatch(3, 0, 0, 0) == -1
     assert lib.flexq_set_dispatch(0, 0, 5, 0) == -1
     assert lib.flexq_set_dispatch(0, 0, 0, 0) == 0
+    assert lib.flexq_set_ablation(5) == -1
+    assert lib.flexq_set_ablation(-1) == -1
+    assert lib.flexq_set_ablation(0) == 0
     assert b"shape" in lib.flexq_status_string(-2)

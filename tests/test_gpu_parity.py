@@ -241,6 +241,30 @@ def test_tiled_kernel_k_splits(split, M, group):
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
+@pytest.mark.parametrize("choice", [1, 2, 3, 4])
+@pytest.mark.parametrize("M", [1, 8, 32])
+def test_ablation_variants_compute_the_same(choice, M):
+    """The measurement variants of the streaming kernel (one design choice undone) are
+    still the same arithmetic."""
+    say(f"ablation choice={choice} M={M}")
+    K, N = 2048, 192
+    w = synth.weights(N, K, 0.02, seed=61)
+    x = synth.activations(M, K, seed=62, outlier_frac=0.02)
+    packed, _, _ = prepare(w)
+    xq, sx = fq.quant_act(to_dev(x), 8)
+    ref = oracle.linear(x, w, 8)
+    fq.set_dispatch(1, 0, 8, 0)
+    fq.set_ablation(choice)
+    try:
+        y, acc = fq.gemv_w6a8(packed, N, K, xq=xq, sx=sx, want_acc=True)
+        torch.cuda.synchronize()
+    finally:
+        fq.set_ablation(0)
+        fq.set_dispatch(0, 0)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
+    assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
+
+
 @pytest.mark.parametrize("kernel", ["stream", "tiled"])
 def test_extreme_codes_exact(kernel):
     say(f"extreme codes kernel={kernel}")

@@ -96,8 +96,9 @@ def sweep(args, torch, fq, synth, dev):
 def layer_table(args, torch, fq, synth, dev):
     """One decoder layer's seven linears as four calls (fused QKV, O, fused gate+up, down), each
     fed by the producer that quantizes its input: RMS norm + quantize before QKV and gate+up,
-    the stand-alone quantizer before O (its input comes from attention, which is not part of
-    this path), gated SiLU + quantize before down.  Two policies: the paper's (A8 on the down
+    the library's own quantize step before O (fp16 in: its input comes from attention, which is
+    not part of this path; decode batches quantize inside the GEMV), gated SiLU + quantize
+    before down.  Two policies: the paper's (A8 on the down
     projection only) and a layer running all seven linears at A8 (the flagged layers of the
     13B configuration).  The launches are captured in a HIP graph and replayed."""
     models = [("LLaMA-2-7B", 4096, 11008, 4096 * 3, 0, (1, 8, 512, 2048)),
@@ -136,8 +137,8 @@ def layer_table(args, torch, fq, synth, dev):
                 def layer():
                     xq, sx = fq.rmsnorm_quant(h, gamma, 1e-5, bits[0], out=bufs["h"])
                     gemm(bits[0])(w_qkv, QKV, H, group, xq=xq, sx=sx, workspace=wss["qkv"], out=outs["qkv"])
-                    xq, sx = fq.quant_act(attn, bits[1], out=bufs["h"])
-                    gemm(bits[1])(w_o, H, H, group, xq=xq, sx=sx, workspace=wss["o"], out=outs["o"])
+                    # fp16 in: the library quantizes (inside the GEMV for decode batches)
+                    gemm(bits[1])(w_o, H, H, group, x_fp16=attn, workspace=wss["o"], out=outs["o"])
                     xq, sx = fq.rmsnorm_quant(outs["o"], gamma, 1e-5, bits[2], out=bufs["h"])
                     gemm(bits[2])(w_gu, 2 * F, H, group, xq=xq, sx=sx, workspace=wss["gu"], out=outs["gu"])
                     xq, sx = fq.swiglu_quant(outs["gu"], bits[3], out=bufs["f"])
@@ -248,6 +249,8 @@ def main():
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="only run a plain device copy of known size (for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--gemm-cfg", type=int, default=0,
+                    help="force a tile configuration of the tiled kernel (0 = the library's choice)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line, print a table of per-layer GEMM / GEMV "
                          "times over token counts M = 1 .. 4096 (library's own dispatch)")
@@ -283,6 +286,8 @@ def main():
                           "bytes_written_per_copy": nbytes}))
         return
     fq.load()
+    if args.gemm_cfg:
+        fq.set_dispatch(0, 0, 0, args.gemm_cfg)
 
     if args.sweep:
         return sweep(args, torch, fq, synth, dev)

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexq.so")
-SOURCES = ["quant_pack.hip", "producers.hip", "skinny.hip", "gemm.hip", "probes.hip", "api.hip"]
+SOURCES = ["quant_pack.hip", "producers.hip", "skinny.hip", "gemm.hip", "gemm_wlds.hip", "probes.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

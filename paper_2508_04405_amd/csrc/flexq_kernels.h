@@ -53,5 +53,7 @@ hipError_t launch_skinny(const LinearArgs &a, int waves, hipStream_t st);
 bool skinny_can_fuse(int M, int K, int split_k);
 // Tiled MFMA kernel for large M.
 hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st);
+// 256x256 tiles with both operands through LDS: per-channel scales, no K split.
+hipError_t launch_gemm_wlds(const LinearArgs &a, hipStream_t st);
 
 }  // namespace flexq

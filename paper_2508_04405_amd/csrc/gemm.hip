@@ -25,36 +25,10 @@
 // share operand panels in that XCD's L2.
 #include "flexq_device.h"
 #include "flexq_kernels.h"
+#include "gemm_common.h"
 #include <type_traits>
 
 namespace {
-
-// swizzled byte offset of 16-byte chunk c (0..7) of row `row` in a stage
-__device__ __forceinline__ int lds_off(int row, int c)
-{
-    return row * 128 + ((c ^ ((row >> 1) & 7)) << 4);
-}
-
-// s_waitcnt vmcnt(N): at most N of this wavefront's vector-memory loads (in
-// issue order, LDS-DMA loads included) are still outstanding afterwards.
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() (and any
-// fence the compiler knows about) also waits for every outstanding global load
-// -- LDS-DMA loads share the counter -- which would drain the prefetch pipeline
-// at the end of each stage.  Here every wavefront has already waited, by count,
-// for exactly the loads that must have landed; its own LDS reads are complete
-// once lgkmcnt is zero.  The asm is opaque to the compiler, so no memory access
-// moves across it.
-__device__ __forceinline__ void lds_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
 
 template <int WM, int WN, int MT, int NT, int GROUP, int WPE>
 __global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
@@ -588,7 +562,15 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
         // of LLaMA-2 linears.
         const long tiles_big = (long)((a.M + 127) / 128) * ((a.N + 255) / 256);
         cfg = tiles_big <= 384 ? 8 : 7;
+        // 256x256 tiles with both operands through LDS bring the fewest bytes per MFMA
+        // through the vector-memory path, but run one workgroup per CU: worth it when the
+        // tiles come in (nearly) whole rounds of 256 (measured: +1..4 % on the 57344- and
+        // 28672-deep LLaMA-2-70B layers at 4096 tokens, -10 % at two and a half rounds)
+        const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
+        const long rounds = (t256 + 255) / 256;
+        if (cfg == 7 && a.group == 0 && t256 >= 512 && rounds * 256 * 20 <= t256 * 21) cfg = 12;
     }
+    if (cfg == 12 && a.split_k == 1) return launch_gemm_wlds(a, st);
     switch (cfg) {
     case 1: return launch_cfg<2, 2, 4, 4, 0, 1>(a, st);   // 256x256, 4 waves, 1 wave/SIMD
     case 2: return launch_cfg<2, 4, 4, 2, 0, 2>(a, st);   // 256x256, 8 waves (128x64 each)

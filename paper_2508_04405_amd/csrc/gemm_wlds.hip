@@ -1,0 +1,305 @@
+// Tiled i8-MFMA GEMM, 256x256 tile, BOTH operands through LDS.
+//
+// The 128x256 kernel is limited by power, and what costs power besides the
+// MFMAs is every byte a wavefront brings in through the vector-memory path:
+// timing probes put the packed-weight loads at about a fifth of its run time
+// and the activation DMA at a tenth, while doubling the LDS operand reads
+// costs 3 %.  This kernel therefore trades vector-memory bytes for LDS reads:
+// one workgroup of eight wavefronts (2 along m x 4 along n, 128x64 each) owns a
+// 256x256 tile, and a packed weight tile is brought into LDS ONCE per
+// workgroup (by DMA, like the activations) and read from there by the two
+// wavefronts that share its columns: 0.875 KB through the vector-memory path
+// per 32x32x128 block instead of 1.25.
+//
+//   LDS: three activation stages of 32 KiB (two stages ahead) and two weight
+//   stages of 24 KiB (one stage ahead: a weight stage is consumed -- copied to
+//   registers -- right at the start of its stage, so its buffer is free for the
+//   stage after next as soon as every wavefront has passed the next barrier);
+//   144 KiB, one workgroup per CU, two wavefronts per SIMD.
+//   Per stage and wavefront: 3 weight DMA loads, then 4 activation DMA loads;
+//   the hand-over waits until at most the 4 youngest are outstanding.
+//
+// Per-channel scales only, no K split: this is the kernel for large M and N.
+// Inner loop and epilogue follow the 128x256 kernel.
+#include "flexq_device.h"
+#include "flexq_kernels.h"
+#include "gemm_common.h"
+#include <type_traits>
+
+namespace {
+
+constexpr int BM = 256, BN = 256, WAVES = 8, MT = 4, NT = 2;
+constexpr int XSTAGE = BM * 128;               // bytes of one activation stage
+constexpr int WSTAGE = (BN / 32) * FLEXQ_TILE_BYTES;
+constexpr int WBASE = 3 * XSTAGE;
+constexpr int LDS_BYTES = WBASE + 2 * WSTAGE;
+constexpr int XDMA = BM / 8 / WAVES;           // 1 KiB activation DMA loads per wavefront and stage
+constexpr int WDMA = 3;                        // each wavefront fetches one weight tile (3 planes)
+static_assert(BN / 32 == WAVES, "one weight tile per wavefront");
+
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
+{
+#if defined(__HIP_DEVICE_COMPILE__)  // buffer-resource builtins exist in the device pass only
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int M = a.M, N = a.N, K = a.K;
+    const int KT = K / FLEXQ_TILE_K;
+
+    // ---- XCD-aware tile choice: blocks 8 apart share an XCD ---------------
+    const int nblk = tiles_m * tiles_n;
+    int bid = blockIdx.x;
+    {
+        const int per = nblk / 8, rem = nblk % 8;
+        const int xcd = bid % 8, slot = bid / 8;
+        bid = xcd * per + (xcd < rem ? xcd : rem) + slot;
+    }
+    constexpr int SUP_M = 8;  // super-block: 8 tiles along m, then next n
+    const int sup = bid / (SUP_M * tiles_n);
+    const int first_m = sup * SUP_M;
+    const int span_m = min(SUP_M, tiles_m - first_m);
+    const int in_sup = bid - sup * SUP_M * tiles_n;
+    const int tile_m = first_m + in_sup % span_m;
+    const int tile_n = in_sup / span_m;
+    const int bm0 = tile_m * BM, bn0 = tile_n * BN;
+
+    // ---- activations: global -> LDS by DMA; rows beyond M read as zero -----
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.xq, 0, (unsigned)((long)M * K), 0x00020000);
+    unsigned xoff[XDMA];
+#pragma unroll
+    for (int i = 0; i < XDMA; ++i) {
+        const int q = wave * XDMA + i;
+        const int row = 8 * q + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        xoff[i] = (unsigned)(bm0 + row) * (unsigned)K + 16u * c;
+    }
+    auto dma_x = [&](int kb, int buf) {
+#pragma unroll
+        for (int i = 0; i < XDMA; ++i) {
+            uint8_t *dst = lds + buf * XSTAGE + (wave * XDMA + i) * 1024;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                xrsrc, (void __attribute__((address_space(3))) *)dst, 16, xoff[i],
+                kb * FLEXQ_TILE_K, 0, 0);
+        }
+    };
+
+    // ---- packed weights: wavefront w brings tile w of the workgroup's eight
+    // column tiles into LDS, plane by plane, exactly as it lies in memory ------
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.packed, 0, (unsigned)((long)N * K / 4 * 3), 0x00020000);
+    // the SGPR offset is not range-checked: tiles past the last row block
+    // re-read the last one and are never stored
+    const int wtile = min(bn0 / 32 + wave, N / 32 - 1);
+    const unsigned wlane = (unsigned)lane * 16u;
+    auto dma_w = [&](int kb, int buf) {
+#pragma unroll
+        for (int p = 0; p < WDMA; ++p) {
+            uint8_t *dst = lds + WBASE + buf * WSTAGE + wave * FLEXQ_TILE_BYTES + p * 1024;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                wrsrc, (void __attribute__((address_space(3))) *)dst, 16, wlane,
+                (unsigned)(wtile * KT + kb) * FLEXQ_TILE_BYTES + 1024u * p, 0, 0);
+        }
+    };
+
+    v16i acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0;
+
+    // prologue: weights and activations of stage 0, activations of stage 1
+    dma_w(0, 0);
+    dma_x(0, 0);
+    if (KT > 1) dma_x(1, 1);
+    wait_vmcnt<0>();
+    lds_barrier();
+
+    const int arow = (wm * MT) * 32 + (lane & 31);
+    const int ahalf = lane >> 5;
+    const int wfrag = WBASE + (wn * NT) * FLEXQ_TILE_BYTES + lane * 16;   // this lane's piece of tile nt = 0
+
+    // operands that live across stages: the stage's packed tiles, the activation
+    // operands of two consecutive k-steps, the first weight operand of a stage
+    PackedTile wreg[NT];
+    v4i af[2][MT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const v4i *t = reinterpret_cast<const v4i *>(lds + wfrag + nt * FLEXQ_TILE_BYTES);
+        wreg[nt].q0 = t[0];
+        wreg[nt].q1 = t[64];
+        wreg[nt].q2 = t[128];
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+        af[0][mt] = *reinterpret_cast<const v4i *>(lds + lds_off(arow + 32 * mt, ahalf));
+    v4i bf_first = unpack_kstep(wreg[0], 0);
+
+    // One 128-k stage.  CUR = kb % 3 names the activation buffer; kb & 1 the weight buffer.
+    auto stage = [&](int kb, auto cur_tag) {
+        constexpr int CUR = decltype(cur_tag)::value;
+        constexpr int NXT2 = (CUR + 2) % 3;
+        const bool more1 = kb + 1 < KT, more2 = kb + 2 < KT;
+        // weights first: the hand-over waits for them and for everything older,
+        // while the activation loads issued after them may stay in flight
+        if (more1) dma_w(kb + 1, (kb + 1) & 1);
+        if (more2) dma_x(kb + 2, NXT2);
+
+        const uint8_t *xs = lds + CUR * XSTAGE;
+        const uint8_t *xn = lds + ((CUR + 1) % 3) * XSTAGE;
+        const uint8_t *wnb = lds + wfrag + ((kb + 1) & 1) * WSTAGE;
+        // Flat software pipeline over the 4 * NT (k-step, column tile) steps: LDS
+        // operand reads a k-step ahead, weight operands expanded one dword per MFMA in
+        // the shadow of the MFMA just issued.  The two wavefronts of a SIMD belong to
+        // the same workgroup and reach the stage boundary together, so nothing would
+        // cover the operand fetch of a new stage: the hand-over therefore sits BEFORE
+        // the last k-step.  By then this wavefront has read all it needs of stage kb
+        // (the operands of k-step 3 are in registers: activations were read during
+        // k-step 2, the weight operands expanded during steps 3 and 4), so after the
+        // barrier the packed tiles and first activation operands of stage kb + 1 are
+        // fetched from LDS while k-step 3's MFMAs run.
+        static_assert(NT == 2 && MT == 4, "the step table below is written for 4 x 2 blocks");
+        v4i bfc = bf_first, bf6, bf7;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int j = s >> 1, nt = s & 1;
+            if (nt == 0) {
+                if (j < 3) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
+                            xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
+                } else {
+                    // stage kb + 1 (weights and activations, every wavefront's share) must
+                    // have landed; the activations of stage kb + 2 may be in flight
+                    if (more2)
+                        wait_vmcnt<XDMA>();
+                    else
+                        wait_vmcnt<0>();
+                    lds_barrier();
+                    if (more1) {
+#pragma unroll
+                        for (int n2 = 0; n2 < NT; ++n2) {
+                            const v4i *t = reinterpret_cast<const v4i *>(wnb + n2 * FLEXQ_TILE_BYTES);
+                            wreg[n2].q0 = t[0];
+                            wreg[n2].q1 = t[64];
+                            wreg[n2].q2 = t[128];
+                        }
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            af[0][mt] = *reinterpret_cast<const v4i *>(xn + lds_off(arow + 32 * mt, ahalf));
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const v4i cur = s == 6 ? bf6 : s == 7 ? bf7 : bfc;
+            v4i nxt = bfc;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc[mt][nt] = mfma_i8(af[j & 1][mt], cur, acc[mt][nt]);
+                // shadow work of this MFMA: one dword of an operand that is due later
+                if (s < 5) nxt[mt] = unpack_kstep_dword(wreg[(s + 1) & 1], (s + 1) >> 1, mt);
+                if (s == 3) bf6[mt] = unpack_kstep_dword(wreg[0], 3, mt);
+                if (s == 4) bf7[mt] = unpack_kstep_dword(wreg[1], 3, mt);
+                if (s == 7) nxt[mt] = unpack_kstep_dword(wreg[0], 0, mt);   // the next stage's first
+                {
+                    int p0 = nxt[mt], p1 = bf6[mt], p2 = bf7[mt];
+                    asm volatile("" : "+v"(p0), "+v"(p1), "+v"(p2));   // pins the expansion here
+                    nxt[mt] = p0;
+                    bf6[mt] = p1;
+                    bf7[mt] = p2;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            bfc = nxt;
+        }
+        bf_first = bfc;
+    };
+
+    int kb = 0;
+    for (; kb + 2 < KT; kb += 3) {
+        stage(kb, std::integral_constant<int, 0>{});
+        stage(kb + 1, std::integral_constant<int, 1>{});
+        stage(kb + 2, std::integral_constant<int, 2>{});
+    }
+    if (kb < KT) stage(kb, std::integral_constant<int, 0>{});
+    if (kb + 1 < KT) stage(kb + 1, std::integral_constant<int, 1>{});
+
+    // ---- epilogue: as in the 128x256 kernel -----------------------------------
+    // After the last barrier nobody reads the stage buffers again, so each
+    // wavefront transposes its 32-row slabs through a region of its own (row
+    // stride NT*32 + 8 dwords), then every lane owns four consecutive columns of
+    // one row, applies sx[m] * sw[n] in fp32, and the lanes of a row store whole
+    // 128-byte runs of fp16.
+    constexpr int ESTRIDE = (NT * 32 + 8) * 4;
+    static_assert(3 * XSTAGE >= WAVES * 32 * ESTRIDE, "epilogue staging must fit the stage buffers");
+    constexpr int LPR = NT * 8;
+    constexpr int RPI = 64 / LPR;
+    uint8_t *stg = lds + wave * (32 * ESTRIDE);
+    const int ecol = (lane % LPR) * 4;
+    const int erow = lane / LPR;
+    const int n_lane = bn0 + wn * NT * 32 + ecol;
+    const bool cvalid = n_lane < N;
+    float swv[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) swv[c] = h2f(a.scales[cvalid ? n_lane + c : 0]);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int m_slab = bm0 + (wm * MT + mt) * 32;
+        if (m_slab >= M) break;                          // uniform: nothing below is stored
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                *reinterpret_cast<int *>(stg + mfma_row(r, lane) * ESTRIDE +
+                                         (nt * 32 + (lane & 31)) * 4) = acc[mt][nt][r] >> 2;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own region only: no barrier
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = i * RPI + erow;
+            const v4i q = *reinterpret_cast<const v4i *>(stg + row * ESTRIDE + ecol * 4);
+            const int m = m_slab + row;
+            if (m < M && cvalid) {
+                const float sxm = h2f(a.sx[m]);
+                uint16_t h[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) h[c] = f2h((float)q[c] * (sxm * swv[c]));
+                uint2 out2;
+                out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
+                out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
+                *reinterpret_cast<uint2 *>(a.y + (long)m * N + n_lane) = out2;
+                if (a.acc_out) *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n_lane) = q;
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next slab overwrites
+    }
+#endif
+}
+
+}  // namespace
+
+namespace flexq {
+
+hipError_t launch_gemm_wlds(const LinearArgs &a, hipStream_t st)
+{
+    if (a.group != 0 || a.split_k > 1 || a.sxg) return hipErrorInvalidValue;
+    const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_wlds_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gemm_wlds_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WAVES),
+                       LDS_BYTES, st, a, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+}  // namespace flexq

@@ -241,6 +241,27 @@ def test_tiled_kernel_k_splits(split, M, group):
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
+@pytest.mark.parametrize("cfg", [1, 2, 6, 7, 8, 12])
+@pytest.mark.parametrize("M,K,N", [(5, 128, 32), (130, 384, 96), (300, 640, 544), (513, 1280, 288)])
+def test_tiled_kernel_tile_shapes(cfg, M, K, N):
+    """Every selectable tile configuration of the tiled kernels, on ragged shapes of one,
+    three, five and ten 128-k stages."""
+    say(f"tile configuration {cfg} M={M} K={K} N={N}")
+    w = synth.weights(N, K, 0.02, seed=71)
+    x = synth.activations(M, K, seed=72, outlier_frac=0.02)
+    packed, _, _ = prepare(w)
+    xq, sx = fq.quant_act(to_dev(x), 8)
+    ref = oracle.linear(x, w, 8)
+    fq.set_dispatch(2, 1, 0, cfg)
+    try:
+        y, acc = fq.gemm_w6a8(packed, N, K, xq=xq, sx=sx, want_acc=True)
+        torch.cuda.synchronize()
+    finally:
+        fq.set_dispatch(0, 0, 0, 0)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
+    assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
+
+
 @pytest.mark.parametrize("choice", [1, 2, 3, 4])
 @pytest.mark.parametrize("M", [1, 8, 32])
 def test_ablation_variants_compute_the_same(choice, M):

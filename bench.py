@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
 # Bytes fetched past L2 + written, per launch, averaged over the four layers: rocprofv3 FETCH_SIZE and
 # WRITE_SIZE runs of this script, scaled on a 1 GiB device copy (x2.000 and x1.000); the runs, the
 # raw readings and the per-layer table are in profiles/bench_llama2_70b_linears_hbm_traffic.md.
-TRAFFIC_GEMM_M4096 = 1474.6e6 + 172.0e6
+TRAFFIC_GEMM_M4096 = 1202.5e6 + 172.0e6
 TRAFFIC_GEMV_M1 = 160.76e6 + 0.042e6
 SIGMA = 0.015
 LAYERS = [("qkv", 8192, 10240, 6), ("o", 8192, 8192, 6), ("gate_up", 8192, 57344, 6),
@@ -372,7 +372,9 @@ def main():
     gemm_tops = ops_step / gemm_s / 1e12
     launches = 4 * args.steps
     roofline = {
-        "bound": "mfma", "kernel": "gemm_kernel (i8 MFMA 32x32x32, tiled)",
+        "bound": "mfma",
+        "kernel": "gemm_wlds_kernel (256x256 tiles: o, gate_up, down) and gemm_kernel<1,4,4,2> (128x256: qkv), "
+                  "i8 MFMA 32x32x32",
         "achieved": round(gemm_tops, 2), "peak": PEAK_I8_TOPS / 1.0, "unit": "TOP/s",
         "frac": round(gemm_tops / PEAK_I8_TOPS, 4),
         "avg_launch_ms": round(gemm_s / 4 * 1e3, 4), "launches": launches,

@@ -411,8 +411,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
 #pragma unroll
     for (int c = 0; c < 4; ++c) swv[c] = GROUP ? 0.25f : h2f(a.scales[cvalid ? n_lane + c : 0]);
     // scale and store four columns of row m (q: exact int32 sums, or fp32 group sums)
-    auto finish = [&](const v4i &q, int m) {
-        const float sxm = GROUP == 2 ? 1.0f : h2f(a.sx[m]);   // mode 2 scaled per group already
+    auto finish = [&](const v4i &q, int m, float sxm) {
         uint16_t h[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c)
@@ -432,6 +431,15 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     for (int mt = 0; mt < MT; ++mt) {
         const int m_slab = bm0 + (wm * MT + mt) * 32;
         if (m_slab >= M) break;                          // uniform: nothing below is stored
+        // the slab's token scales, fetched together and ahead of the stores (a load per
+        // row inside the loop would wait a memory round trip each time: the compiler
+        // cannot move it above the stores, which might alias)
+        float sxv[32 / RPI];
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int m = m_slab + i * RPI + erow;
+            sxv[i] = (GROUP != 2 && m < M) ? h2f(a.sx[m]) : 1.0f;   // mode 2 scaled per group already
+        }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -449,7 +457,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             const int m = m_slab + row;
             if (m < M && cvalid) {
                 if (KS == 1) {
-                    finish(q, m);
+                    finish(q, m, sxv[i]);
                 } else {
                     // device-scope (sc1) 16-byte store: see the hand-off below
                     const unsigned off = (unsigned)((((long)ksplit * M + m) * N + n_lane) * 4);
@@ -512,7 +520,7 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
 #pragma unroll
                     for (int c = 0; c < 4; ++c) q[c] = __float_as_int(f[c]);
                 }
-                finish(q, m);
+                finish(q, m, GROUP == 2 ? 1.0f : h2f(a.sx[m]));
             }
         }
     }

@@ -249,32 +249,81 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     float swv[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) swv[c] = h2f(a.scales[cvalid ? n_lane + c : 0]);
+    // Whole slabs (every row below M, every column below N, no int32 copy wanted) take a
+    // path without per-row branches or 64-bit address arithmetic: the output is addressed
+    // as a buffer from this wavefront's corner, a lane's offset is fixed, the row offset is
+    // an SGPR; and the accumulators are staged as they are (4x the sum), the factor 1/4
+    // folded into the weight scale (a power of two: the rounded result is identical).
+    const bool cols_whole = bn0 + (wn + 1) * NT * 32 <= N;
+    const long corner = (long)(bm0 + wm * MT * 32) * N + bn0 + wn * NT * 32;
+    const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(a.y + corner), 0, (unsigned)(((long)(MT * 32 - 1) * N + NT * 32) * 2), 0x00020000);
+    const unsigned yoff = (unsigned)((erow * N + ecol) * 2);
+    float swq[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) swq[c] = 0.25f * swv[c];
+    // every token scale this wavefront will need, fetched in one go: a load per row
+    // inside the store loop would wait a memory round trip each time (the compiler cannot
+    // move it above the stores, which might alias), a batch per slab once per slab
+    float sxall[MT][32 / RPI];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int m = bm0 + (wm * MT + mt) * 32 + i * RPI + erow;
+            sxall[mt][i] = m < M ? h2f(a.sx[m]) : 0.0f;
+        }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m_slab = bm0 + (wm * MT + mt) * 32;
         if (m_slab >= M) break;                          // uniform: nothing below is stored
+        const bool whole = cols_whole && m_slab + 32 <= M && !a.acc_out;   // uniform
+        const float *sxv = sxall[mt];
+        if (whole) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+            for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                *reinterpret_cast<int *>(stg + mfma_row(r, lane) * ESTRIDE +
-                                         (nt * 32 + (lane & 31)) * 4) = acc[mt][nt][r] >> 2;
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own region only: no barrier
+                for (int r = 0; r < 16; ++r)
+                    *reinterpret_cast<int *>(stg + mfma_row(r, lane) * ESTRIDE +
+                                             (nt * 32 + (lane & 31)) * 4) = acc[mt][nt][r];
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own region only: no barrier
 #pragma unroll
-        for (int i = 0; i < 32 / RPI; ++i) {
-            const int row = i * RPI + erow;
-            const v4i q = *reinterpret_cast<const v4i *>(stg + row * ESTRIDE + ecol * 4);
-            const int m = m_slab + row;
-            if (m < M && cvalid) {
-                const float sxm = h2f(a.sx[m]);
+            for (int i = 0; i < 32 / RPI; ++i) {
+                const v4i q = *reinterpret_cast<const v4i *>(stg + (i * RPI + erow) * ESTRIDE + ecol * 4);
                 uint16_t h[4];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) h[c] = f2h((float)q[c] * (sxm * swv[c]));
-                uint2 out2;
+                for (int c = 0; c < 4; ++c) h[c] = f2h((float)q[c] * (sxv[i] * swq[c]));
+                typedef unsigned v2u __attribute__((ext_vector_type(2)));
+                v2u out2;
                 out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
                 out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
-                *reinterpret_cast<uint2 *>(a.y + (long)m * N + n_lane) = out2;
-                if (a.acc_out) *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n_lane) = q;
+                __builtin_amdgcn_raw_buffer_store_b64(out2, yrsrc, yoff,
+                                                      (unsigned)((mt * 32 + i * RPI) * N * 2), 0);
+            }
+        } else {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    *reinterpret_cast<int *>(stg + mfma_row(r, lane) * ESTRIDE +
+                                             (nt * 32 + (lane & 31)) * 4) = acc[mt][nt][r] >> 2;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < 32 / RPI; ++i) {
+                const int row = i * RPI + erow;
+                const v4i q = *reinterpret_cast<const v4i *>(stg + row * ESTRIDE + ecol * 4);
+                const int m = m_slab + row;
+                if (m < M && cvalid) {
+                    const float sxm = sxv[i];
+                    uint16_t h[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) h[c] = f2h((float)q[c] * (sxm * swv[c]));
+                    uint2 out2;
+                    out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
+                    out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
+                    *reinterpret_cast<uint2 *>(a.y + (long)m * N + n_lane) = out2;
+                    if (a.acc_out) *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n_lane) = q;
+                }
             }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next slab overwrites

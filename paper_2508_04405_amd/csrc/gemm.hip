@@ -572,11 +572,11 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
         cfg = tiles_big <= 384 ? 8 : 7;
         // 256x256 tiles with both operands through LDS bring the fewest bytes per MFMA
         // through the vector-memory path, but run one workgroup per CU: worth it when the
-        // tiles come in (nearly) whole rounds of 256 (measured: +1..4 % on the 57344- and
-        // 28672-deep LLaMA-2-70B layers at 4096 tokens, -10 % at two and a half rounds)
+        // tiles come in (nearly) whole rounds of 256 (measured on the LLaMA-2-70B layers: +1..7 %
+        // from one whole round up, +6 % at 1.875 rounds, -6..-10 % at one and a half or two and a half)
         const long t256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
         const long rounds = (t256 + 255) / 256;
-        if (cfg == 7 && a.group == 0 && t256 >= 512 && rounds * 256 * 20 <= t256 * 21) cfg = 12;
+        if (cfg == 7 && a.group == 0 && t256 >= 256 && rounds * 256 * 100 <= t256 * 107) cfg = 12;
     }
     if (cfg == 12 && a.split_k == 1) return launch_gemm_wlds(a, st);
     switch (cfg) {

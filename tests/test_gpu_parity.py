@@ -555,3 +555,37 @@ def test_13b_group128_sampled(K, N):
     for M, bits in ((32, 8), (32, 6), (2048, 6), (2048, 8)):
         say(f"13B group-128 K={K} N={N} M={M} A{bits}")
         check_sampled(packed, N, K, 0.02, seed, M, bits, group=128, n_rows=20, n_cols=60)
+
+
+# ------------------------------------------------ seeded random shapes, all modes
+
+def test_random_shapes_all_modes():
+    """Forty seeded random (M, K, N) with a random mode each: per-channel / group-128 weight
+    scales, A6 / A8, pre-quantized or fp16 activations, library's own dispatch."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        M = int(rng.choice([1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 300, 520]))
+        K = 128 * int(rng.integers(1, 24))
+        N = 32 * int(rng.integers(1, 30))
+        bits = int(rng.choice([6, 8]))
+        group = int(rng.choice([0, 128]))
+        fp16_in = bool(rng.integers(0, 2))
+        say(f"random case {case}: M={M} K={K} N={N} A{bits} group={group} fp16_in={fp16_in}")
+        w = synth.weights(N, K, 0.02, seed=9000 + case)
+        x = synth.activations(M, K, seed=9500 + case, outlier_frac=0.02)
+        ref = oracle.linear(x, w, bits, group)
+        packed, _, _ = prepare(w, group)
+        fn = fq.gemm_w6a6 if bits == 6 else fq.gemm_w6a8
+        want_acc = group == 0
+        if fp16_in:
+            out = fn(packed, N, K, group, x_fp16=to_dev(x), want_acc=want_acc)
+        else:
+            xq, sx = fq.quant_act(to_dev(x), bits)
+            assert np.array_equal(xq.cpu().numpy(), ref["xq"])
+            out = fn(packed, N, K, group, xq=xq, sx=sx, want_acc=want_acc)
+        torch.cuda.synchronize()
+        if want_acc:
+            assert np.array_equal(out[1].cpu().numpy().astype(np.int64), ref["acc"]), case
+            assert_y_close(out[0].cpu().numpy().view(np.float16), ref["y"])
+        else:
+            assert_y_close(out.cpu().numpy().view(np.float16), ref["y"], slack=group_slack(ref))

@@ -242,7 +242,8 @@ def test_tiled_kernel_k_splits(split, M, group):
 
 
 @pytest.mark.parametrize("cfg", [1, 2, 6, 7, 8, 12])
-@pytest.mark.parametrize("M,K,N", [(5, 128, 32), (130, 384, 96), (300, 640, 544), (513, 1280, 288)])
+@pytest.mark.parametrize("M,K,N", [(5, 128, 32), (130, 384, 96), (300, 640, 544), (513, 1280, 288),
+                                   (512, 256, 544)])
 def test_tiled_kernel_tile_shapes(cfg, M, K, N):
     """Every selectable tile configuration of the tiled kernels, on ragged shapes of one,
     three, five and ten 128-k stages."""
@@ -255,11 +256,13 @@ def test_tiled_kernel_tile_shapes(cfg, M, K, N):
     fq.set_dispatch(2, 1, 0, cfg)
     try:
         y, acc = fq.gemm_w6a8(packed, N, K, xq=xq, sx=sx, want_acc=True)
+        y_only = fq.gemm_w6a8(packed, N, K, xq=xq, sx=sx)      # whole slabs take a path of their own
         torch.cuda.synchronize()
     finally:
         fq.set_dispatch(0, 0, 0, 0)
     assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
     assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
+    assert torch.equal(y_only.view(torch.int16), y.view(torch.int16))
 
 
 @pytest.mark.parametrize("choice", [1, 2, 3, 4])

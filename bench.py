@@ -63,7 +63,7 @@ def sweep(args, torch, fq, synth, dev):
         del wq, sw
     print("| M | " + " | ".join("%s us (TOP/s, GB/s)" % L[0] for L in LAYERS) + " |")
     print("|---|" + "---|" * len(LAYERS))
-    for M in (1, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096):
+    for M in (1, 4, 8, 16, 32, 64, 128, 256, 512, 768, 1024, 1536, 2048, 3072, 4096):
         bufs = []
         for i, (name, K, N, bits) in enumerate(LAYERS):
             x = torch.from_numpy(synth.activations(M, K, seed=3000 + 10 * i + 1,
@@ -72,7 +72,8 @@ def sweep(args, torch, fq, synth, dev):
             bufs.append((xq, sx, torch.empty((M, N), dtype=torch.float16, device=dev),
                          fq.make_workspace(M, N, K, dev)))
         times = [[] for _ in LAYERS]
-        for rep in range(args.warmup + args.steps):
+
+        def cycle(record):
             for i, (name, K, N, bits) in enumerate(LAYERS):
                 xq, sx, y, ws = bufs[i]
                 fn = fq.gemm_w6a6 if bits == 6 else fq.gemm_w6a8
@@ -81,8 +82,19 @@ def sweep(args, torch, fq, synth, dev):
                 e0.record()
                 fn(packed[i], N, K, 0, xq=xq, sx=sx, workspace=ws, out=y)
                 e1.record()
-                if rep >= args.warmup:
+                if record:
                     times[i].append((e0, e1))
+
+        # warm up for at least 50 ms of GPU work (the host-side input generation above
+        # leaves the GPU idle, and its clock takes a while to come back up)
+        t_warm = time.perf_counter()
+        reps = 0
+        while reps < args.warmup or time.perf_counter() - t_warm < 0.05:
+            cycle(False)
+            torch.cuda.synchronize()
+            reps += 1
+        for rep in range(args.steps):
+            cycle(True)
         torch.cuda.synchronize()
         cells = []
         for i, (name, K, N, bits) in enumerate(LAYERS):

@@ -139,7 +139,9 @@ flexq_status flexq_swiglu_quant(const uint16_t *gate_up, int M, int F,
  * Bytes of workspace the GEMM / GEMV entry points need for (M,N,K): room for
  * split-K partial sums and their arrival counters, and for the quantized
  * activations when the quantize prologue is requested.  Never 0 for a valid
- * shape.  The workspace must be 256-byte aligned, and its first
+ * shape.  For M > 128, when the 256x256 output tiles do not come in a multiple
+ * of 256 (the CUs of an MI355X), it includes 128 MiB in which the workgroups
+ * sharing a tile of the last, partial round leave their int32 sums.  The workspace must be 256-byte aligned, and its first
  * FLEXQ_WORKSPACE_COUNTER_BYTES bytes must be zero before the first call that
  * uses it (flexq_workspace_init does that); every call leaves them zero again.
  * Calls that share a workspace must be ordered on one stream.

@@ -181,6 +181,7 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     a.group = group;
     a.counters = ws.counters;
     a.partial = ws.partial;
+    a.partial_bytes = ws.partial_capacity;
     a.x_fp16 = fuse ? x_fp16 : nullptr;
     a.qmax = act_bits == 6 ? 31.0f : 127.0f;
     a.sxg = nullptr;
@@ -202,7 +203,9 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
             a.split_k = (int)(ws.partial_capacity / per_split);
         if ((size_t)a.split_k * per_split >= ((size_t)1 << 32)) a.split_k = 1;   // 32-bit buffer offsets
         if (a.split_k < 2) a.split_k = 1;
-        return flexq::launch_gemm(a, g_force_gemm_cfg.load(), st) == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
+        int cfg = g_force_gemm_cfg.load();
+        if (cfg == 0 && g_force_split.load() > 0 && a.split_k > 1) cfg = 8;   // a forced split is honoured
+        return flexq::launch_gemm(a, cfg, st) == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
     }
     for (int m0 = 0; m0 < M; m0 += kSkinnyMaxM) {
         const int rows = M - m0 < kSkinnyMaxM ? M - m0 : kSkinnyMaxM;
@@ -360,6 +363,10 @@ size_t flexq_workspace_bytes(int M, int N, int K)
     {
         const int gs = choose_gemm_split(M, N, K);
         const size_t b = gs > 1 ? (size_t)gs * M * N * 4 : 0;
+        if (b > partial) partial = b;
+    }
+    if (M > kSkinnyMaxM) {   // the 256x256 kernel's tail cut along K
+        const size_t b = flexq::streamk_plan(M, N).partial_bytes;
         if (b > partial) partial = b;
     }
     return fixed_bytes(M, K) + round_up(partial, 256);

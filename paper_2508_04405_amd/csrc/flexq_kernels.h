@@ -18,6 +18,7 @@ struct LinearArgs {
     int32_t *acc_out;        // [M,N] or null
     unsigned *counters;      // zero on entry, zero on exit
     void *partial;           // split-K partial sums
+    size_t partial_bytes;    // capacity of that area
     int split_k;             // >= 1
     const uint16_t *x_fp16;  // streaming kernel only: quantize these fp16 activations in the
     float qmax;              // kernel (31 or 127) instead of reading xq / sx; else null
@@ -54,6 +55,19 @@ bool skinny_can_fuse(int M, int K, int split_k);
 // Tiled MFMA kernel for large M.
 hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st);
 // 256x256 tiles with both operands through LDS: per-channel scales, no K split.
-hipError_t launch_gemm_wlds(const LinearArgs &a, hipStream_t st);
+// tail_wgs = 0: one workgroup per tile.  tail_wgs > 0: persistent form of 256 workgroups;
+// the tiles beyond the last whole round of 256 are cut along K into tail_wgs equal runs
+// of 128-k stages, whose partial sums meet in the partial-sum area (it must hold
+// streamk_plan().partial_bytes; with less, the call falls back to one workgroup per tile).
+constexpr int kStreamKGrid = 256;   // workgroups of the persistent form: one per CU of an MI355X
+struct StreamKPlan {
+    int tiles, full_tiles, tail_tiles;   // 256x256 tiles: all, those in whole rounds, the rest
+    size_t partial_bytes;                // workspace for the partial sums of the rest
+};
+StreamKPlan streamk_plan(int M, int N);
+// Estimated time (microseconds) of the better of the two forms (of the first, if the tail
+// may not be cut), and that form's tail_wgs.
+double gemm_wlds_estimate_us(int M, int N, int K, bool may_cut, int *tail_wgs);
+hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_wgs, hipStream_t st);
 
 }  // namespace flexq

@@ -562,16 +562,16 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
         if (cfg == 21) return launch_cfg<1, 4, 4, 2, 1, 1>(a, st);      // 128x256, 1 wave/SIMD
         return launch_cfg<1, 4, 4, 1, 1, 2>(a, st);
     }
-    if (a.split_k > 1 && cfg == 0) cfg = 8;   // K splits are chosen for 128x128 tiles
     if (cfg == 0) {
-        // Three tile shapes: 128x256 (two workgroups per CU), 128x128 (three per CU) and
-        // 256x256 with both operands through LDS (one per CU, the fewest bytes per MFMA
-        // through the vector-memory path).  Which is fastest depends mostly on how evenly
-        // the tiles fill the 256 CUs, so the time of the busiest CU is estimated for each:
-        // its ceil(tiles / 256) tiles run `slots` at a time at the measured relative
-        // throughput of that many co-resident workgroups, a remainder at the throughput of
-        // fewer.  Fitted on the LLaMA-2-70B layers at 768..4096 tokens: picks the fastest
-        // shape in 25 of 28 cases, 0.5 % slower than the best on average.
+        // Four candidates: 128x256 tiles (two workgroups per CU), 128x128 (three per CU;
+        // the only shape with K splits), 256x256 with both operands through LDS (one per
+        // CU, the fewest bytes per MFMA through the vector-memory path), and the
+        // persistent form of the latter that cuts the tiles beyond the last whole round
+        // of 256 along K.  Which is fastest depends mostly on how evenly the work fills
+        // the 256 CUs, so the time of the busiest CU is estimated for each: its
+        // ceil(tiles / 256) tiles run `slots` at a time at the measured relative
+        // throughput of that many co-resident workgroups, a remainder at the throughput
+        // of fewer.  Fitted on the LLaMA-2-70B layers at 256..4096 tokens.
         auto busiest_cu = [](long tiles, double area, int slots, const double *throughput) {
             const long per_cu = (tiles + 255) / 256;
             const long full = per_cu / slots, rest = per_cu % slots;
@@ -579,16 +579,48 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
             if (rest) t += (double)rest * area / throughput[rest - 1];
             return t;
         };
-        static const double thr7[2] = {0.70, 1.00}, thr8[3] = {0.40, 0.75, 0.85}, thr12[1] = {1.03};
-        const long m128 = (a.M + 127) / 128, m256 = (a.M + 255) / 256;
-        const long n128 = (a.N + 127) / 128, n256 = (a.N + 255) / 256;
-        const double t7 = busiest_cu(m128 * n256, 128.0 * 256, 2, thr7);
-        const double t8 = busiest_cu(m128 * n128, 128.0 * 128, 3, thr8);
-        const double t12 = busiest_cu(m256 * n256, 256.0 * 256, 1, thr12);
-        cfg = t8 < t7 ? 8 : 7;
-        if (t12 < (cfg == 8 ? t8 : t7)) cfg = 12;
+        static const double thr7[2] = {0.70, 1.00}, thr8_busy[3] = {0.40, 0.75, 0.85};
+        // with at most one 128x128 workgroup per CU on the whole chip the clock is higher
+        static const double thr8_sparse[3] = {0.58, 0.75, 0.85};
+        const long m128 = (a.M + 127) / 128, n128 = (a.N + 127) / 128, n256 = (a.N + 255) / 256;
+        // microseconds per unit of tile area: a whole 256x256 tile (relative throughput
+        // 1.03) takes 1.556 us per 128-k stage plus 7 us
+        const double unit = (1.556 * (a.K / 128) + 7.0) * 1.03 / 65536.0;
+        double t_best;
+        if (a.split_k > 1) {   // K splits were chosen for 128x128 tiles; meeting costs about 11 us
+            cfg = 8;
+            const double *thr8 = m128 * n128 * a.split_k <= 256 ? thr8_sparse : thr8_busy;
+            t_best = busiest_cu(m128 * n128 * a.split_k, 128.0 * 128 / a.split_k, 3, thr8) * unit + 11.0;
+        } else {
+            const double t7 = busiest_cu(m128 * n256, 128.0 * 256, 2, thr7) * unit;
+            const double *thr8 = m128 * n128 <= 256 ? thr8_sparse : thr8_busy;
+            const double t8 = busiest_cu(m128 * n128, 128.0 * 128, 3, thr8) * unit;
+            cfg = t8 < t7 ? 8 : 7;
+            t_best = t8 < t7 ? t8 : t7;
+        }
+        if (a.M > 128) {
+            int tail_wgs = 0;
+            const bool may_cut = a.partial_bytes >= streamk_plan(a.M, a.N).partial_bytes;
+            double t = gemm_wlds_estimate_us(a.M, a.N, a.K, may_cut, &tail_wgs);
+            // a cut tail must promise 5 % (it adds workspace traffic the estimate is unsure
+            // of); else the tiles run whole, if that is the fastest
+            if (tail_wgs > 0 && t >= 0.95 * t_best)
+                t = gemm_wlds_estimate_us(a.M, a.N, a.K, false, &tail_wgs);
+            if (t < t_best) {
+                LinearArgs b = a;
+                b.split_k = 1;
+                return launch_gemm_wlds(b, tail_wgs, st);
+            }
+        }
     }
-    if (cfg == 12 && a.split_k == 1) return launch_gemm_wlds(a, st);
+    if (cfg == 12 && a.split_k == 1) return launch_gemm_wlds(a, 0, st);
+    if (cfg == 13 && a.split_k == 1) {
+        int tail_wgs = 0;
+        gemm_wlds_estimate_us(a.M, a.N, a.K, true, &tail_wgs);
+        // forced: cut the tail also where whole tiles are estimated to be faster
+        if (tail_wgs == 0) tail_wgs = kStreamKGrid;
+        return launch_gemm_wlds(a, tail_wgs, st);
+    }
     switch (cfg) {
     case 1: return launch_cfg<2, 2, 4, 4, 0, 1>(a, st);   // 256x256, 4 waves, 1 wave/SIMD
     case 2: return launch_cfg<2, 4, 4, 2, 0, 2>(a, st);   // 256x256, 8 waves (128x64 each)

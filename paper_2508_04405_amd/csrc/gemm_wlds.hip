@@ -19,8 +19,18 @@
 //   Per stage and wavefront: 3 weight DMA loads, then 4 activation DMA loads;
 //   the hand-over waits until at most the 4 youngest are outstanding.
 //
-// Per-channel scales only, no K split: this is the kernel for large M and N.
-// Inner loop and epilogue follow the 128x256 kernel.
+// Per-channel scales only: this is the kernel for large M and N.  Inner loop and
+// epilogue follow the 128x256 kernel.
+//
+// Two launch forms.  One workgroup per tile, when the tiles come in whole rounds
+// of the 256 CUs.  Otherwise a persistent form (SK) of 256 workgroups: each takes
+// its share of the whole rounds tile by tile, and the tiles of the last, partial
+// round are cut along K into equal contiguous runs of 128-k stages, one run per
+// workgroup, so that every CU is busy to the end.  A run that is not a whole tile
+// leaves its int32 sums in the workspace (exact, so the order of addition does
+// not matter); the workgroups of a tile add their stage counts to the tile's
+// counter, and the one that completes the count adds the others' sums to its own
+// registers and runs the epilogue.  Nobody waits for anybody.
 #include "flexq_device.h"
 #include "flexq_kernels.h"
 #include "gemm_common.h"
@@ -37,11 +47,16 @@ constexpr int XDMA = BM / 8 / WAVES;           // 1 KiB activation DMA loads per
 constexpr int WDMA = 3;                        // each wavefront fetches one weight tile (3 planes)
 static_assert(BN / 32 == WAVES, "one weight tile per wavefront");
 
+constexpr int SLOT_BYTES = BM * BN * 4;         // one workgroup's int32 sums of a tile
+
+template <bool SK>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
+void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_tiles, int tail_tiles,
+                      int tail_wgs)
 {
 #if defined(__HIP_DEVICE_COMPILE__)  // buffer-resource builtins exist in the device pass only
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    __shared__ int s_last;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -49,15 +64,55 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     const int wm = wave >> 2, wn = wave & 3;
     const int M = a.M, N = a.N, K = a.K;
     const int KT = K / FLEXQ_TILE_K;
-
-    // ---- XCD-aware tile choice: blocks 8 apart share an XCD ---------------
     const int nblk = tiles_m * tiles_n;
-    int bid = blockIdx.x;
-    {
+
+    // SK: workgroups 8 apart share an XCD; v numbers them XCD by XCD, so that the
+    // workgroups of one XCD work on neighbouring tiles (and neighbouring runs of the tail)
+    const int G = (int)gridDim.x;
+    const int v = SK ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : 0;
+    const int rounds = SK ? full_tiles / G : 0;
+    const long U = (long)tail_tiles * KT;           // 128-k stages of the tail
+    // the tail's runs are numbered so that every XCD takes a contiguous share of them,
+    // also when there are fewer runs than workgroups
+    int vt = -1;
+    if (SK) {
+        const int x = (int)(blockIdx.x % 8), slot = (int)(blockIdx.x / 8);
+        const int per = tail_wgs / 8, rem = tail_wgs % 8;
+        if (slot < per + (x < rem ? 1 : 0)) vt = x * per + min(x, rem) + slot;
+    }
+    long u0 = 0, u1 = 0;                            // this workgroup's run of stages
+    if (vt >= 0) {
+        u0 = (long)vt * U / tail_wgs;
+        u1 = (long)(vt + 1) * U / tail_wgs;
+    }
+    const long run_begin = u0;
+
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.xq, 0, (unsigned)((long)M * K), 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.packed, 0, (unsigned)((long)N * K / 4 * 3), 0x00020000);
+
+  for (int it = 0;; ++it) {
+    // ---- which tile, which stages [ks, ke) of it ---------------------------
+    int bid, ks = 0, ke = KT, tj = 0;
+    if (!SK) {
+        if (it) break;
+        // XCD-aware tile choice: blocks 8 apart share an XCD
+        bid = blockIdx.x;
         const int per = nblk / 8, rem = nblk % 8;
         const int xcd = bid % 8, slot = bid / 8;
         bid = xcd * per + (xcd < rem ? xcd : rem) + slot;
+    } else if (it < rounds) {
+        bid = (v / (G / 8)) * (full_tiles / 8) + it * (G / 8) + v % (G / 8);
+    } else {
+        if (u0 >= u1) break;
+        tj = (int)(u0 / KT);
+        ks = (int)(u0 - (long)tj * KT);
+        ke = (int)min((long)KT, ks + (u1 - u0));
+        bid = full_tiles + tj;
+        u0 += ke - ks;
     }
+    const int KN = ke - ks;
     constexpr int SUP_M = 8;  // super-block: 8 tiles along m, then next n
     const int sup = bid / (SUP_M * tiles_n);
     const int first_m = sup * SUP_M;
@@ -68,8 +123,7 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     const int bm0 = tile_m * BM, bn0 = tile_n * BN;
 
     // ---- activations: global -> LDS by DMA; rows beyond M read as zero -----
-    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.xq, 0, (unsigned)((long)M * K), 0x00020000);
+    // (stage numbers below count from ks)
     unsigned xoff[XDMA];
 #pragma unroll
     for (int i = 0; i < XDMA; ++i) {
@@ -84,14 +138,12 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             uint8_t *dst = lds + buf * XSTAGE + (wave * XDMA + i) * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 xrsrc, (void __attribute__((address_space(3))) *)dst, 16, xoff[i],
-                kb * FLEXQ_TILE_K, 0, 0);
+                (ks + kb) * FLEXQ_TILE_K, 0, 0);
         }
     };
 
     // ---- packed weights: wavefront w brings tile w of the workgroup's eight
     // column tiles into LDS, plane by plane, exactly as it lies in memory ------
-    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)a.packed, 0, (unsigned)((long)N * K / 4 * 3), 0x00020000);
     // the SGPR offset is not range-checked: tiles past the last row block
     // re-read the last one and are never stored
     const int wtile = min(bn0 / 32 + wave, N / 32 - 1);
@@ -102,7 +154,7 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             uint8_t *dst = lds + WBASE + buf * WSTAGE + wave * FLEXQ_TILE_BYTES + p * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 wrsrc, (void __attribute__((address_space(3))) *)dst, 16, wlane,
-                (unsigned)(wtile * KT + kb) * FLEXQ_TILE_BYTES + 1024u * p, 0, 0);
+                (unsigned)(wtile * KT + ks + kb) * FLEXQ_TILE_BYTES + 1024u * p, 0, 0);
         }
     };
 
@@ -117,7 +169,7 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     // prologue: weights and activations of stage 0, activations of stage 1
     dma_w(0, 0);
     dma_x(0, 0);
-    if (KT > 1) dma_x(1, 1);
+    if (KN > 1) dma_x(1, 1);
     wait_vmcnt<0>();
     lds_barrier();
 
@@ -145,7 +197,7 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     auto stage = [&](int kb, auto cur_tag) {
         constexpr int CUR = decltype(cur_tag)::value;
         constexpr int NXT2 = (CUR + 2) % 3;
-        const bool more1 = kb + 1 < KT, more2 = kb + 2 < KT;
+        const bool more1 = kb + 1 < KN, more2 = kb + 2 < KN;
         // weights first: the hand-over waits for them and for everything older,
         // while the activation loads issued after them may stay in flight
         if (more1) dma_w(kb + 1, (kb + 1) & 1);
@@ -223,13 +275,76 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     };
 
     int kb = 0;
-    for (; kb + 2 < KT; kb += 3) {
+    for (; kb + 2 < KN; kb += 3) {
         stage(kb, std::integral_constant<int, 0>{});
         stage(kb + 1, std::integral_constant<int, 1>{});
         stage(kb + 2, std::integral_constant<int, 2>{});
     }
-    if (kb < KT) stage(kb, std::integral_constant<int, 0>{});
-    if (kb + 1 < KT) stage(kb + 1, std::integral_constant<int, 1>{});
+    if (kb < KN) stage(kb, std::integral_constant<int, 0>{});
+    if (kb + 1 < KN) stage(kb + 1, std::integral_constant<int, 1>{});
+
+    // ---- a run that is not a whole tile: leave the sums, or collect the others' ----
+    if (SK && KN != KT) {
+        // [slot][wavefront][block mt, nt][quarter][lane] 16-byte pieces: every store and
+        // load below is one contiguous KiB per wavefront.  Cache policy bit 4 = sc1 =
+        // device scope: the access goes to memory all XCDs share.
+        constexpr int kScopeAgent = 16;
+        const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
+            a.partial, 0, (unsigned)(2 * G) * (unsigned)SLOT_BYTES, 0x00020000);
+        const unsigned in_slot = (unsigned)(wave * (SLOT_BYTES / WAVES) + lane * 16);
+        const long tile_begin = (long)tj * KT;
+        // a run leaves at most two partial tiles: slot 2 vt for the one it begins in,
+        // 2 vt + 1 for the one it ends in
+        const unsigned mine = (unsigned)(2 * vt + (run_begin < tile_begin ? 1 : 0)) * SLOT_BYTES + in_slot;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const v4u piece = {(unsigned)acc[mt][nt][4 * q], (unsigned)acc[mt][nt][4 * q + 1],
+                                       (unsigned)acc[mt][nt][4 * q + 2], (unsigned)acc[mt][nt][4 * q + 3]};
+                    __builtin_amdgcn_raw_buffer_store_b128(
+                        piece, prsrc, mine + (unsigned)(((mt * NT + nt) * 4 + q) * 1024), 0, kScopeAgent);
+                }
+        // Once the stores are acknowledged (vmcnt 0) they are visible device-wide; the
+        // barrier plus one relaxed device-scope add to the tile's stage count publishes
+        // them.  Whoever brings the count to KT is the last and resets it.
+        wait_vmcnt<0>();
+        lds_barrier();
+        if (tid == 0) {
+            const unsigned prev = __hip_atomic_fetch_add(&a.counters[tj], (unsigned)KN, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (prev + (unsigned)KN == (unsigned)KT);
+            if (s_last)
+                __hip_atomic_store(&a.counters[tj], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        lds_barrier();
+        if (!__builtin_amdgcn_readfirstlane(s_last)) continue;   // scalar branch: barriers follow
+        // the runs that meet this tile: the one holding its first stage through the one
+        // holding its last (run w is [w U / W, (w + 1) U / W))
+        const long W = tail_wgs;
+        const int va = (int)(((tile_begin + 1) * W + U - 1) / U) - 1;
+        const int vb = (int)(((tile_begin + KT) * W + U - 1) / U) - 1;
+        for (int w2 = va; w2 <= vb; ++w2) {
+            if (w2 == vt) continue;
+            const long begin2 = (long)w2 * U / W;
+            const unsigned theirs =
+                (unsigned)(2 * w2 + (begin2 < tile_begin ? 1 : 0)) * SLOT_BYTES + in_slot;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                v4u got[NT * 4];
+#pragma unroll
+                for (int i = 0; i < NT * 4; ++i)
+                    got[i] = __builtin_amdgcn_raw_buffer_load_b128(
+                        prsrc, theirs + (unsigned)((mt * NT * 4 + i) * 1024), 0, kScopeAgent);
+#pragma unroll
+                for (int i = 0; i < NT * 4; ++i)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[mt][i >> 2][4 * (i & 3) + c] += (int)got[i][c];
+            }
+        }
+    }
 
     // ---- epilogue: as in the 128x256 kernel -----------------------------------
     // After the last barrier nobody reads the stage buffers again, so each
@@ -328,6 +443,9 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next slab overwrites
     }
+    if (!SK) break;
+    lds_barrier();   // every wavefront is done with its staging region before the next run's DMA
+  }
 #endif
 }
 
@@ -335,19 +453,77 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
 
 namespace flexq {
 
-hipError_t launch_gemm_wlds(const LinearArgs &a, hipStream_t st)
+StreamKPlan streamk_plan(int M, int N)
+{
+    StreamKPlan p;
+    p.tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    p.full_tiles = p.tiles / kStreamKGrid * kStreamKGrid;
+    p.tail_tiles = p.tiles - p.full_tiles;
+    p.partial_bytes = p.tail_tiles ? (size_t)2 * kStreamKGrid * SLOT_BYTES : 0;
+    return p;
+}
+
+// Estimated run time in microseconds, measured constants of the MI355X: a 128-k
+// stage of a 256x256 tile takes 1.56 us at the clock this load sustains, prologue plus
+// epilogue 7 us per tile.  Meeting in the workspace costs 14 us plus 2 us per
+// workgroup of a tile when every tile is cut into the same number S of runs (one
+// partial tile per workgroup: 256 KiB written, the last to arrive reads the others');
+// about 45 us when the tail is simply cut into 256 equal runs, which then begin and
+// end inside tiles (two partial tiles per workgroup).
+double gemm_wlds_estimate_us(int M, int N, int K, bool may_cut, int *tail_wgs)
+{
+    const StreamKPlan p = streamk_plan(M, N);
+    const int KT = K / FLEXQ_TILE_K;
+    const double stage_us = 1.556, tile_us = stage_us * KT + 7.0;
+    const double whole_rounds = (double)(p.full_tiles / kStreamKGrid) * tile_us;
+    // every tail tile whole: one more round
+    double best = whole_rounds + (p.tail_tiles ? tile_us : 0.0);
+    *tail_wgs = 0;
+    if (p.tail_tiles == 0 || !may_cut) return best;
+    for (int S = 2; S <= 8 && p.tail_tiles * S <= kStreamKGrid && S <= KT; ++S) {
+        const double t = whole_rounds + stage_us * ((KT + S - 1) / S) + 7.0 + 14.0 + 2.0 * S;
+        if (t < best) {
+            best = t;
+            *tail_wgs = p.tail_tiles * S;
+        }
+    }
+    if ((long)p.tail_tiles * KT >= 2L * kStreamKGrid) {
+        const double t = whole_rounds + stage_us * KT * p.tail_tiles / kStreamKGrid + 7.0 + 45.0;
+        if (t < best) {
+            best = t;
+            *tail_wgs = kStreamKGrid;
+        }
+    }
+    return best;
+}
+
+hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_wgs, hipStream_t st)
 {
     if (a.group != 0 || a.split_k > 1 || a.sxg) return hipErrorInvalidValue;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_wlds_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_wlds_kernel<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_wlds_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(gemm_wlds_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WAVES),
-                       LDS_BYTES, st, a, tiles_m, tiles_n);
+    const StreamKPlan p = streamk_plan(a.M, a.N);
+    // (without room for the partial sums the tail tiles simply run whole)
+    if (tail_wgs <= 0 || p.tail_tiles == 0 || a.partial_bytes < p.partial_bytes) {
+        hipLaunchKernelGGL(gemm_wlds_kernel<false>, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WAVES),
+                           LDS_BYTES, st, a, tiles_m, tiles_n, 0, 0, 0);
+        return hipGetLastError();
+    }
+    // a run is at least one stage, and the tail has at most 256 runs
+    const long stages = (long)p.tail_tiles * (a.K / FLEXQ_TILE_K);
+    if (tail_wgs > kStreamKGrid) tail_wgs = kStreamKGrid;
+    if (tail_wgs > stages) tail_wgs = (int)stages;
+    hipLaunchKernelGGL(gemm_wlds_kernel<true>, dim3(kStreamKGrid), dim3(64 * WAVES), LDS_BYTES, st, a,
+                       tiles_m, tiles_n, p.full_tiles, p.tail_tiles, tail_wgs);
     return hipGetLastError();
 }
 

@@ -163,8 +163,14 @@ def layer_table(args, torch, fq, synth, dev):
                     graph = torch.cuda.CUDAGraph()
                     with torch.cuda.graph(graph, stream=stream):
                         layer()
-                    for _ in range(args.warmup):
+                    # warm up for at least 50 ms: the host-side set-up above left the GPU
+                    # idle, and its clock takes a while to come back up
+                    t_warm = time.perf_counter()
+                    reps = 0
+                    while reps < args.warmup or time.perf_counter() - t_warm < 0.05:
                         graph.replay()
+                        torch.cuda.synchronize()
+                        reps += 1
                     e0 = torch.cuda.Event(enable_timing=True)
                     e1 = torch.cuda.Event(enable_timing=True)
                     e0.record()
@@ -254,7 +260,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--prefill-m", type=int, default=4096)
     ap.add_argument("--decode-m", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")

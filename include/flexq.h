@@ -175,8 +175,8 @@ flexq_status flexq_workspace_init(void *workspace, size_t workspace_bytes,
  * group 128.  Any M >= 1 is accepted (the tiled kernel needs (M+256)*K and
  * 0.75*N*K below 2^32, else FLEXQ_ESHAPE); flexq_gemm_* pick the kernel from M,
  * flexq_gemv_* are the same calls under the name the decode path uses: for
- * M <= 32 (M <= 64 on layers of at most 2^26 weights) both run the
- * bandwidth-bound streaming kernel.
+ * M <= 32 (24 on layers wider than 32768; 64 on layers of at most 2^26 weights,
+ * 128 on layers of at most 2^24) both run the bandwidth-bound streaming kernel.
  */
 flexq_status flexq_gemm_w6a6(const void *packed, int group, const int8_t *xq,
                              const uint16_t *sx, const uint16_t *x_fp16, int M,

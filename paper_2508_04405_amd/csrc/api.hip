@@ -149,12 +149,17 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
 
     const int forced = g_force_kernel.load();
     // Measured cross-over between the streaming kernel and the tiled kernel with K splits:
-    // past 32 tokens the streaming kernel needs a second MFMA row tile and re-reads the
-    // activations once per 32 output channels, while the tiled kernel's time stays flat
-    // up to 128 tokens; only small layers (N*K <= 2^26) keep streaming up to 64.
+    // the streaming kernel re-reads the activations once per 32 output channels (and past
+    // 32 tokens needs a second MFMA row tile), while the tiled kernel's time stays flat up
+    // to 128 tokens but carries the fixed cost of its K splits on small layers.  So: up to
+    // 32 tokens stream (24 on very wide layers: the 57344-wide gate+up is 17 % faster tiled
+    // at 32), up to 64 on layers of at most 2^26 weights, up to 128 on layers of at most 2^24
+    // (LLaMA-2-7B's 4096 x 4096: 24 vs 31 us at 128 tokens).
     (void)prefer_stream;
     const bool tiled_ok = (long)(M + 256) * K < (1L << 32) && (long)N * K / 4 * 3 < (1L << 32);
-    bool stream_kernel = M <= 32 || (M <= 64 && ((long)N * K <= (1L << 26) || !tiled_ok));
+    const long weights = (long)N * K;
+    bool stream_kernel = M <= 24 || (M <= 32 && N < 32768) || (M <= 64 && weights <= (1L << 26)) ||
+                         (M <= 128 && weights <= (1L << 24)) || (M <= 64 && !tiled_ok);
     // group-wise activation scales reach the tiled kernel by 4-byte DMA loads: even stride
     if (sxg && (sxg_stride % 2 != 0 || !tiled_ok)) stream_kernel = true;
     if (forced == 1) stream_kernel = true;

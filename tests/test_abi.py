@@ -42,6 +42,28 @@ def test_sizes():
     assert lib.flexq_workspace_bytes(0, 8192, 8192) == 0
 
 
+def test_workspace_covers_the_partial_sums():
+    """Host logic only: the workspace holds the counters, the quantized activations of the
+    fused prologue, and the largest partial-sum area any kernel the dispatch may pick needs;
+    for more than 128 tokens that includes 128 MiB for the tiles of a partial last round
+    of 256, and nothing of the kind when the 256x256 tiles come in whole rounds."""
+    lib = fq.load()
+    fixed = lambda M, K: 16384 + -(-M * K // 256) * 256 + -(-M * 2 // 256) * 256
+    cut = 2 * 256 * 256 * 256 * 4
+    # 4096 x 8192 outputs = 512 tiles, 4096 x 57344 = 3584: whole rounds, nothing to cut;
+    # what remains is the streaming kernel's area for the row chunks of 128 tokens
+    assert lib.flexq_workspace_bytes(4096, 8192, 8192) == fixed(4096, 8192) + 128 * 8192 * 4
+    assert lib.flexq_workspace_bytes(4096, 57344, 8192) == fixed(4096, 8192) + 128 * 57344 * 4
+    # 4096 x 10240 = 640 tiles, 1024 x 8192 = 128: a partial round
+    assert lib.flexq_workspace_bytes(4096, 10240, 8192) == fixed(4096, 8192) + cut
+    assert lib.flexq_workspace_bytes(1024, 8192, 28672) == fixed(1024, 28672) + cut
+    # up to 128 tokens only the K splits of the streaming and 128x128 kernels count
+    small = lib.flexq_workspace_bytes(128, 8192, 8192)
+    assert fixed(128, 8192) < small < fixed(128, 8192) + 64 * 128 * 8192 * 4
+    # monotone enough for a caller that sizes one workspace for its largest batch
+    assert lib.flexq_workspace_bytes(1, 8192, 8192) <= small
+
+
 @pytest.mark.parametrize("fn", ["flexq_gemm_w6a6", "flexq_gemm_w6a8", "flexq_gemv_w6a6",
                                 "flexq_gemv_w6a8"])
 def test_linear_argument_errors(fn):

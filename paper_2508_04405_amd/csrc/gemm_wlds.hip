@@ -296,31 +296,50 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_ti
         // a run leaves at most two partial tiles: slot 2 vt for the one it begins in,
         // 2 vt + 1 for the one it ends in
         const unsigned mine = (unsigned)(2 * vt + (run_begin < tile_begin ? 1 : 0)) * SLOT_BYTES + in_slot;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const v4u piece = {(unsigned)acc[mt][nt][4 * q], (unsigned)acc[mt][nt][4 * q + 1],
-                                       (unsigned)acc[mt][nt][4 * q + 2], (unsigned)acc[mt][nt][4 * q + 3]};
-                    __builtin_amdgcn_raw_buffer_store_b128(
-                        piece, prsrc, mine + (unsigned)(((mt * NT + nt) * 4 + q) * 1024), 0, kScopeAgent);
-                }
-        // Once the stores are acknowledged (vmcnt 0) they are visible device-wide; the
-        // barrier plus one relaxed device-scope add to the tile's stage count publishes
-        // them.  Whoever brings the count to KT is the last and resets it.
-        wait_vmcnt<0>();
-        lds_barrier();
-        if (tid == 0) {
-            const unsigned prev = __hip_atomic_fetch_add(&a.counters[tj], (unsigned)KN, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (prev + (unsigned)KN == (unsigned)KT);
-            if (s_last)
-                __hip_atomic_store(&a.counters[tj], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // The tile a run ends in is begun by this workgroup and finished by its successor,
+        // which reached it first thing: by now it has most likely arrived, and so has
+        // everybody else.  One look at the counter tells (it only ever grows until the
+        // last arrival; a workgroup adds to it after its stores are acknowledged): then
+        // this workgroup is the last without storing its own sums first.
+        int early = 0;
+        if (run_begin < tile_begin) {
+            if (tid == 0) {
+                const unsigned seen = __hip_atomic_load(&a.counters[tj], __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+                s_last = (seen + (unsigned)KN == (unsigned)KT);
+                if (s_last)
+                    __hip_atomic_store(&a.counters[tj], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            lds_barrier();
+            early = __builtin_amdgcn_readfirstlane(s_last);
         }
-        lds_barrier();
-        if (!__builtin_amdgcn_readfirstlane(s_last)) continue;   // scalar branch: barriers follow
+        if (!early) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v4u piece = {(unsigned)acc[mt][nt][4 * q], (unsigned)acc[mt][nt][4 * q + 1],
+                                           (unsigned)acc[mt][nt][4 * q + 2], (unsigned)acc[mt][nt][4 * q + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            piece, prsrc, mine + (unsigned)(((mt * NT + nt) * 4 + q) * 1024), 0, kScopeAgent);
+                    }
+            // Once the stores are acknowledged (vmcnt 0) they are visible device-wide; the
+            // barrier plus one relaxed device-scope add to the tile's stage count publishes
+            // them.  Whoever brings the count to KT is the last and resets it.
+            wait_vmcnt<0>();
+            lds_barrier();
+            if (tid == 0) {
+                const unsigned prev = __hip_atomic_fetch_add(&a.counters[tj], (unsigned)KN, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT);
+                s_last = (prev + (unsigned)KN == (unsigned)KT);
+                if (s_last)
+                    __hip_atomic_store(&a.counters[tj], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            lds_barrier();
+            if (!__builtin_amdgcn_readfirstlane(s_last)) continue;   // scalar branch: barriers follow
+        }
         // the runs that meet this tile: the one holding its first stage through the one
         // holding its last (run w is [w U / W, (w + 1) U / W))
         const long W = tail_wgs;

@@ -538,12 +538,13 @@ def check_sampled(packed, N, K, sigma, seed, M, bits, group=0, prologue=False, n
 FULL = [
     # LLaMA-2-70B linears (the bench workload), then the 7B fused gate+up for a ragged N
     # (token counts 33..64 and 256 / 512 sit on the dispatch boundaries between the streaming
-    # kernel, the tiled kernel with K splits, and the two tile shapes)
+    # kernel, the tiled kernel with K splits, and the tile shapes; down at 512 / 1024 and
+    # gate+up at 1536 tokens run the persistent 256x256 kernel with its last round cut along K)
     ("70b_o", 8192, 8192, 0.015, [(1, 8), (16, 6), (48, 6), (64, 8), (128, 8), (1024, 6), (4096, 8)]),
     ("70b_qkv", 8192, 10240, 0.015, [(1, 6), (16, 8), (48, 8), (256, 6), (4096, 6)]),
-    ("70b_gate_up", 8192, 57344, 0.015, [(1, 6), (33, 8), (4096, 6)]),
+    ("70b_gate_up", 8192, 57344, 0.015, [(1, 6), (33, 8), (1536, 6), (4096, 6)]),
     ("70b_down", 28672, 8192, 0.015, [(1, 8), (16, 8), (40, 8), (128, 6), (256, 8), (512, 6),
-                                      (4096, 8)]),
+                                      (1024, 8), (4096, 8)]),
     ("7b_gate_up", 4096, 22016, 0.02, [(1, 8), (8, 8), (33, 6), (64, 8), (512, 6), (2048, 8)]),
 ]
 

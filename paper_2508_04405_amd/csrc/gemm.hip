@@ -485,43 +485,67 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     }
     lds_barrier();
     if (!s_last) return;
+    // A row of the tile per step: its four columns of every split are loaded, added in
+    // split order and stored.  The loads of the NEXT row (its first four splits and its
+    // token scale) are issued before this row is finished -- in program order the
+    // compiler may not lift a load above the stores of `finish`, and each row would then
+    // cost a full memory round trip of its own.
+    constexpr int ROWS_PER_SLAB = 32 / RPI, NROW = MT * ROWS_PER_SLAB;
+    auto row_of = [&](int it) {
+        return bm0 + (wm * MT + it / ROWS_PER_SLAB) * 32 + (it % ROWS_PER_SLAB) * RPI + erow;
+    };
+    auto issue4 = [&](int m, int k0, v4i (&v)[4]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int m_slab = bm0 + (wm * MT + mt) * 32;
-        if (m_slab >= M) break;
+        for (int u = 0; u < 4; ++u) {
+            const int k = k0 + u < KS ? k0 + u : KS - 1;
+            const unsigned off = (unsigned)((((long)k * M + m) * N + n_lane) * 4);
+            v[u] = (v4i)__builtin_amdgcn_raw_buffer_load_b128(prsrc, off, 0, kScopeAgent);
+        }
+    };
+    v4i ahead[4];
+    uint16_t sx_ahead = 0;
+    if (row_of(0) < M && cvalid) {
+        issue4(row_of(0), 0, ahead);
+        if (GROUP != 2) sx_ahead = a.sx[row_of(0)];
+    }
 #pragma unroll
-        for (int i = 0; i < 32 / RPI; ++i) {
-            const int m = m_slab + i * RPI + erow;
-            if (m < M && cvalid) {
-                v4i q = {0, 0, 0, 0};
-                float f[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                for (int k0 = 0; k0 < KS; k0 += 4) {       // four independent loads in flight
-                    v4i v[4];
+    for (int it = 0; it < NROW; ++it) {
+        const int m = row_of(it);
+        const bool valid = m < M && cvalid;
+        v4i v[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int k = k0 + u < KS ? k0 + u : KS - 1;
-                        const unsigned off = (unsigned)((((long)k * M + m) * N + n_lane) * 4);
-                        v[u] = (v4i)__builtin_amdgcn_raw_buffer_load_b128(prsrc, off, 0, kScopeAgent);
-                    }
+        for (int u = 0; u < 4; ++u) v[u] = ahead[u];
+        const float sxm = GROUP == 2 ? 1.0f : h2f(sx_ahead);
+        if (it + 1 < NROW) {
+            const int m2 = row_of(it + 1);
+            if (m2 < M && cvalid) {
+                issue4(m2, 0, ahead);
+                if (GROUP != 2) sx_ahead = a.sx[m2];
+            }
+        }
+        if (valid) {
+            v4i q = {0, 0, 0, 0};
+            float f[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int k0 = 0; k0 < KS; k0 += 4) {       // four independent loads in flight
+                if (k0) issue4(m, k0, v);
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        if (k0 + u < KS) {
+                for (int u = 0; u < 4; ++u) {
+                    if (k0 + u < KS) {
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                if (GROUP)
-                                    f[c] += __int_as_float(v[u][c]);
-                                else
-                                    q[c] += v[u][c];
-                            }
+                        for (int c = 0; c < 4; ++c) {
+                            if (GROUP)
+                                f[c] += __int_as_float(v[u][c]);
+                            else
+                                q[c] += v[u][c];
                         }
                     }
                 }
-                if (GROUP) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) q[c] = __float_as_int(f[c]);
-                }
-                finish(q, m, GROUP == 2 ? 1.0f : h2f(a.sx[m]));
             }
+            if (GROUP) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) q[c] = __float_as_int(f[c]);
+            }
+            finish(q, m, sxm);
         }
     }
 #endif

@@ -427,19 +427,23 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
     constexpr int kScopeAgent = 16;
     const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
         a.partial, 0, (unsigned)((long)KS * M * N * 4), 0x00020000);
+    // every token scale this wavefront will need, fetched in one go ahead of the stores: a
+    // load per row, or per slab, inside the loop would wait a memory round trip each time
+    // (the compiler cannot move it above the stores, which might alias)
+    float sxall[MT][32 / RPI];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int m = bm0 + (wm * MT + mt) * 32 + i * RPI + erow;
+            // (mode 2 is scaled per group already; K splits scale after they have met)
+            sxall[mt][i] = (GROUP != 2 && KS == 1 && m < M) ? h2f(a.sx[m]) : 1.0f;
+        }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m_slab = bm0 + (wm * MT + mt) * 32;
         if (m_slab >= M) break;                          // uniform: nothing below is stored
-        // the slab's token scales, fetched together and ahead of the stores (a load per
-        // row inside the loop would wait a memory round trip each time: the compiler
-        // cannot move it above the stores, which might alias)
-        float sxv[32 / RPI];
-#pragma unroll
-        for (int i = 0; i < 32 / RPI; ++i) {
-            const int m = m_slab + i * RPI + erow;
-            sxv[i] = (GROUP != 2 && m < M) ? h2f(a.sx[m]) : 1.0f;   // mode 2 scaled per group already
-        }
+        const float *sxv = sxall[mt];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll

@@ -624,3 +624,33 @@ def test_random_shapes_all_modes():
             assert_y_close(out[0].cpu().numpy().view(np.float16), ref["y"])
         else:
             assert_y_close(out.cpu().numpy().view(np.float16), ref["y"], slack=group_slack(ref))
+
+
+def test_random_shapes_forced_tiled_kernels():
+    """Thirty seeded random ragged (M, K, N), each on a forced tiled configuration: the
+    tile shapes, the 256x256 kernel in both forms, and the 128x128 kernel with a forced
+    number of K splits.  Two calls per case on one workspace (the counters must come back
+    to zero), int32 sums bit-exact."""
+    rng = np.random.default_rng(77)
+    for case in range(30):
+        M = int(rng.integers(1, 700))
+        K = 128 * int(rng.integers(1, 40))
+        N = 32 * int(rng.integers(1, 48))
+        cfg = int(rng.choice([7, 8, 12, 13, 13, 13]))
+        split = int(rng.integers(2, 9)) if cfg == 8 and rng.integers(0, 2) else 1
+        say(f"random tiled case {case}: M={M} K={K} N={N} cfg={cfg} split={split}")
+        w = synth.weights(N, K, 0.02, seed=9100 + case)
+        x = synth.activations(M, K, seed=9600 + case, outlier_frac=0.02)
+        ref = oracle.linear(x, w, 8)
+        packed, _, _ = prepare(w)
+        xq, sx = fq.quant_act(to_dev(x), 8)
+        ws = fq.make_workspace(M, N, K, extra=split * M * N * 4)
+        fq.set_dispatch(2, split, 0, cfg)
+        try:
+            for _ in range(2):
+                y, acc = run_linear(fq.gemm_w6a8, packed, N, K, 0, xq, sx, True, ws)
+                assert np.array_equal(acc.astype(np.int64), ref["acc"]), case
+                assert_y_close(y.view(np.float16), ref["y"])
+        finally:
+            fq.set_dispatch(0, 0, 0, 0)
+        assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0, case

@@ -61,7 +61,7 @@ def sweep(args, torch, fq, synth, dev):
             del w
         packed.append(fq.pack_w6(wq, sw))
         del wq, sw
-    print("| M | " + " | ".join("%s us (TOP/s, GB/s)" % L[0] for L in LAYERS) + " |")
+    print("| M | " + " | ".join("%s us kernel (TOP/s, GB/s)" % L[0] for L in LAYERS) + " |")
     print("|---|" + "---|" * len(LAYERS))
     for M in (1, 4, 8, 16, 32, 64, 128, 256, 512, 768, 1024, 1536, 2048, 3072, 4096):
         bufs = []
@@ -72,6 +72,7 @@ def sweep(args, torch, fq, synth, dev):
             bufs.append((xq, sx, torch.empty((M, N), dtype=torch.float16, device=dev),
                          fq.make_workspace(M, N, K, dev)))
         times = [[] for _ in LAYERS]
+        kinds = [None for _ in LAYERS]
 
         def cycle(record):
             for i, (name, K, N, bits) in enumerate(LAYERS):
@@ -84,6 +85,7 @@ def sweep(args, torch, fq, synth, dev):
                 e1.record()
                 if record:
                     times[i].append((e0, e1))
+                    kinds[i] = fq.last_dispatch()
 
         # warm up for at least 50 ms of GPU work (the host-side input generation above
         # leaves the GPU idle, and its clock takes a while to come back up)
@@ -99,8 +101,12 @@ def sweep(args, torch, fq, synth, dev):
         cells = []
         for i, (name, K, N, bits) in enumerate(LAYERS):
             us = sorted(a.elapsed_time(b) * 1e3 for a, b in times[i])[len(times[i]) // 2]
-            cells.append("%.1f (%.0f, %.0f)" % (us, 2.0 * M * N * K / us / 1e6,
-                                                gemm_bytes(M, N, K) / us / 1e3))
+            kern, splits = kinds[i]
+            label = {1: "s", 7: "a", 8: "b", 12: "c", 13: "p"}.get(kern, "?")
+            if splits > 1:
+                label += str(splits)
+            cells.append("%.1f %s (%.0f, %.0f)" % (us, label, 2.0 * M * N * K / us / 1e6,
+                                                   gemm_bytes(M, N, K) / us / 1e3))
         print("| %d | " % M + " | ".join(cells) + " |", flush=True)
         del bufs
 

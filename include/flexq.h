@@ -241,6 +241,15 @@ flexq_status flexq_linear_g128(const void *packed, const int8_t *xq,
 flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg);
 
 /*
+ * What the last GEMM / GEMV call of this process launched, for tests and tables:
+ * 1000 * c + s, with c = 1 for the streaming kernel, else the tile configuration of
+ * the tiled kernels (7: 128x256, 8: 128x128, 12: 256x256 with both operands through
+ * LDS, 13: its persistent form), and s = the number of K splits (for c = 13: the
+ * number of runs the last, partial round of tiles was cut into).  0 before any call.
+ */
+int flexq_last_dispatch(void);
+
+/*
  * Ablation hook (measurement only, in the manner of the paper's Table 6): undo
  * ONE design choice of the streaming decode kernel for the next calls.
  *   0  nothing undone (the default)

@@ -4,6 +4,6 @@
 draws the seeded synthetic inputs; `build` compiles the HIP sources.
 """
 from .binding import (FlexQError, gemm_w6a6, gemm_w6a8, gemv_w6a6, gemv_w6a8,  # noqa: F401
-                      layout_version, linear_g128, load, make_workspace, pack_w6, packed_bytes,
+                      last_dispatch, layout_version, linear_g128, load, make_workspace, pack_w6, packed_bytes,
                       probe_hbm_read, probe_mfma_i8, quant_act, quant_act_g128, quant_w6,
                       rmsnorm_quant, set_ablation, set_dispatch, swiglu_quant, unpack_w6, workspace_bytes)

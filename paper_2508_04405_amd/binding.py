@@ -65,6 +65,8 @@ def load():
     lib.flexq_probe_mfma_i8.argtypes = [vp, vp, c_int, c_int, vp, vp]
     lib.flexq_set_ablation.restype = c_int
     lib.flexq_set_ablation.argtypes = [c_int]
+    lib.flexq_last_dispatch.restype = c_int
+    lib.flexq_last_dispatch.argtypes = []
     lib.flexq_set_dispatch.restype = c_int
     lib.flexq_set_dispatch.argtypes = [c_int, c_int, c_int, c_int]
     _lib = lib
@@ -99,6 +101,13 @@ def packed_bytes(N, K, group=0):
 
 def set_ablation(choice=0):
     _check(load().flexq_set_ablation(choice))
+
+
+def last_dispatch():
+    """(kernel, splits) of the last GEMM / GEMV call: kernel 1 = streaming, else the tile
+    configuration; for configuration 13 the second number is the runs of its cut tail."""
+    code = load().flexq_last_dispatch()
+    return code // 1000, code % 1000
 
 
 def set_dispatch(which=0, split_k=0, waves=0, gemm_cfg=0):

@@ -12,6 +12,7 @@ std::atomic<int> g_force_split{0};
 std::atomic<int> g_force_waves{0};
 std::atomic<int> g_ablate{0};
 std::atomic<int> g_force_gemm_cfg{0};
+std::atomic<int> g_last_dispatch{0};
 
 constexpr int kMaxRowBlocks = FLEXQ_WORKSPACE_COUNTER_BYTES / 4;
 constexpr int kSkinnyMaxM = 128;
@@ -210,7 +211,10 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
         if (a.split_k < 2) a.split_k = 1;
         int cfg = g_force_gemm_cfg.load();
         if (cfg == 0 && g_force_split.load() > 0 && a.split_k > 1) cfg = 8;   // a forced split is honoured
-        return flexq::launch_gemm(a, cfg, st) == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
+        int chosen = 0, tail_runs = 0;
+        const hipError_t e = flexq::launch_gemm(a, cfg, st, &chosen, &tail_runs);
+        g_last_dispatch.store(chosen * 1000 + (chosen == 13 ? tail_runs : a.split_k));
+        return e == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
     }
     for (int m0 = 0; m0 < M; m0 += kSkinnyMaxM) {
         const int rows = M - m0 < kSkinnyMaxM ? M - m0 : kSkinnyMaxM;
@@ -228,6 +232,7 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
         if (a.split_k < 1) a.split_k = 1;
         if (flexq::launch_skinny(a, choose_waves(rows, N, K, a.split_k), st) != hipSuccess)
             return FLEXQ_EHIP;
+        g_last_dispatch.store(1000 + a.split_k);
     }
     return FLEXQ_OK;
 }
@@ -419,6 +424,8 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq, co
     return linear(8, true, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
                   workspace_bytes, stream);
 }
+
+int flexq_last_dispatch(void) { return g_last_dispatch.load(); }
 
 flexq_status flexq_set_ablation(int choice)
 {

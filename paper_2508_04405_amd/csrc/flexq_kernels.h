@@ -53,7 +53,10 @@ hipError_t launch_skinny(const LinearArgs &a, int waves, hipStream_t st);
 // True if the streaming kernel can quantize fp16 activations itself for this shape.
 bool skinny_can_fuse(int M, int K, int split_k);
 // Tiled MFMA kernel for large M.
-hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st);
+// `chosen` (may be null) receives the tile configuration that ran and, for the persistent
+// 256x256 form, the number of runs its tail was cut into.
+hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen = nullptr,
+                       int *tail_runs = nullptr);
 // 256x256 tiles with both operands through LDS: per-channel scales, no K split.
 // tail_wgs = 0: one workgroup per tile.  tail_wgs > 0: persistent form of 256 workgroups;
 // the tiles beyond the last whole round of 256 are cut along K into tail_wgs equal runs

@@ -579,15 +579,23 @@ hipError_t launch_cfg(const flexq::LinearArgs &a, hipStream_t st)
 
 namespace flexq {
 
-hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
+hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen, int *tail_runs)
 {
+    int unused_cfg, unused_runs;
+    if (!chosen) chosen = &unused_cfg;
+    if (!tail_runs) tail_runs = &unused_runs;
+    *tail_runs = 0;
+    *chosen = 8;   // the group modes run 128x128 tiles
     // Group-128 scales cost two vector operations per accumulator and group (int -> float,
     // multiply-add), as many cycles as the MFMAs: that mode is bound by the vector unit.
     // 128x128 tiles with two workgroups per CU keep the int32 sums out of the AGPR half
     // of the register file (which vector instructions cannot read directly).
     if (a.group != 0) {
         if (a.sxg) return launch_cfg<1, 4, 4, 1, 2, 2>(a, st);          // scales per group on both operands
-        if (cfg == 21) return launch_cfg<1, 4, 4, 2, 1, 1>(a, st);      // 128x256, 1 wave/SIMD
+        if (cfg == 21) {
+            *chosen = 21;
+            return launch_cfg<1, 4, 4, 2, 1, 1>(a, st);      // 128x256, 1 wave/SIMD
+        }
         return launch_cfg<1, 4, 4, 1, 1, 2>(a, st);
     }
     if (cfg == 0) {
@@ -637,16 +645,20 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
             if (t < t_best) {
                 LinearArgs b = a;
                 b.split_k = 1;
+                *chosen = tail_wgs > 0 ? 13 : 12;
+                *tail_runs = tail_wgs;
                 return launch_gemm_wlds(b, tail_wgs, st);
             }
         }
     }
+    *chosen = cfg;
     if (cfg == 12 && a.split_k == 1) return launch_gemm_wlds(a, 0, st);
     if (cfg == 13 && a.split_k == 1) {
         int tail_wgs = 0;
         gemm_wlds_estimate_us(a.M, a.N, a.K, true, &tail_wgs);
         // forced: cut the tail also where whole tiles are estimated to be faster
         if (tail_wgs == 0) tail_wgs = kStreamKGrid;
+        *tail_runs = tail_wgs;
         return launch_gemm_wlds(a, tail_wgs, st);
     }
     switch (cfg) {
@@ -655,7 +667,7 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st)
     case 6: return launch_cfg<1, 4, 8, 2, 0, 1>(a, st);   // 256x256, 4 waves side by side (256x64 each)
     case 7: return launch_cfg<1, 4, 4, 2, 0, 2>(a, st);   // 128x256, 4 waves side by side, 2 workgroups/CU
     case 8: return launch_cfg<1, 4, 4, 1, 0, 3>(a, st);   // 128x128, 4 waves side by side, 3 workgroups/CU
-    default: return launch_cfg<1, 4, 4, 2, 0, 2>(a, st);
+    default: *chosen = 7; return launch_cfg<1, 4, 4, 2, 0, 2>(a, st);
     }
 }
 

@@ -144,4 +144,5 @@ def test_other_entry_points_argument_errors():
     assert lib.flexq_set_ablation(5) == -1
     assert lib.flexq_set_ablation(-1) == -1
     assert lib.flexq_set_ablation(0) == 0
+    assert lib.flexq_last_dispatch() >= 0
     assert b"shape" in lib.flexq_status_string(-2)

@@ -654,3 +654,29 @@ def test_random_shapes_forced_tiled_kernels():
         finally:
             fq.set_dispatch(0, 0, 0, 0)
         assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0, case
+
+
+def test_dispatch_choices_on_the_70b_layers():
+    """Which kernel the library's own dispatch launches on the bench workload's layers
+    (outputs are checked elsewhere; this pins the choice itself): streaming kernel for
+    decode, 256x256 tiles in whole rounds at 4096 tokens, 128x256 for the 10240-wide QKV,
+    the persistent form with a cut tail for the down projection at 1024 tokens."""
+    say("dispatch choices")
+    dev = torch.device("cuda:0")
+
+    def launched(M, N, K):
+        packed = torch.zeros(fq.packed_bytes(N, K, 0), dtype=torch.uint8, device=dev)
+        xq = torch.zeros((M, K), dtype=torch.int8, device=dev)
+        sx = torch.ones((M,), dtype=torch.float16, device=dev)
+        fq.gemm_w6a8(packed, N, K, 0, xq=xq, sx=sx)
+        torch.cuda.synchronize()
+        return fq.last_dispatch()
+
+    assert launched(1, 8192, 8192)[0] == 1
+    assert launched(16, 8192, 28672)[0] == 1
+    assert launched(4096, 8192, 8192) == (12, 1)
+    assert launched(4096, 8192, 28672) == (12, 1)
+    assert launched(4096, 10240, 8192) == (7, 1)
+    assert launched(1024, 8192, 28672) == (13, 256)      # 128 tiles, two runs each
+    kernel, splits = launched(128, 8192, 8192)
+    assert kernel == 8 and splits > 1                     # 128x128 tiles with K splits

@@ -4,7 +4,23 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace flexq {
+
+// A kernel that needs more than 64 KiB of dynamic LDS must be told so once per device
+// (hipFuncSetAttribute).  `done` is that kernel's bit mask of devices already served.
+inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<unsigned long long> &done)
+{
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (device & 63);
+    if (done.load(std::memory_order_relaxed) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_relaxed);
+    return e;
+}
 
 // Everything a GEMM / GEMV launch needs.  Pointers are device pointers.
 struct LinearArgs {

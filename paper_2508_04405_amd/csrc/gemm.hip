@@ -562,13 +562,10 @@ hipError_t launch_cfg(const flexq::LinearArgs &a, hipStream_t st)
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const size_t lds_bytes = 3 * BM * 128 + (GROUP == 2 ? 4 * BM * 2 : 0);
     auto kern = gemm_kernel<WM, WN, MT, NT, GROUP, WPE>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<unsigned long long> lds_allowed{0};
+    if (hipError_t e = flexq::allow_dynamic_lds(reinterpret_cast<const void *>(kern), (int)lds_bytes, lds_allowed);
+        e != hipSuccess)
+        return e;
     if (a.split_k > 1 && tiles_m * tiles_n > 4096) return hipErrorInvalidValue;  // one counter per tile
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n * a.split_k)), dim3(64 * WM * WN),
                        lds_bytes, st, a, tiles_m, tiles_n);

@@ -520,16 +520,12 @@ hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_wgs, hipStream_t st)
 {
     if (a.group != 0 || a.split_k > 1 || a.sxg) return hipErrorInvalidValue;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_wlds_kernel<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_wlds_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<unsigned long long> lds_allowed[2];
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(gemm_wlds_kernel<false>), LDS_BYTES,
+                                     lds_allowed[0]);
+    if (e == hipSuccess)
+        e = allow_dynamic_lds(reinterpret_cast<const void *>(gemm_wlds_kernel<true>), LDS_BYTES, lds_allowed[1]);
+    if (e != hipSuccess) return e;
     const StreamKPlan p = streamk_plan(a.M, a.N);
     // (without room for the partial sums the tail tiles simply run whole)
     if (tail_wgs <= 0 || p.tail_tiles == 0 || a.partial_bytes < p.partial_bytes) {

@@ -435,14 +435,11 @@ hipError_t launch_one(const flexq::LinearArgs &a, hipStream_t st)
         const int KT = a.K / 128;
         const int max_tiles = (KT + a.split_k - 1) / a.split_k;
         dyn = (size_t)a.M * (max_tiles * 128 + 16);
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               kXldsBytes + 32 * 16);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        static std::atomic<unsigned long long> lds_allowed{0};
+        if (hipError_t e = flexq::allow_dynamic_lds(reinterpret_cast<const void *>(kern),
+                                                    kXldsBytes + 32 * 16, lds_allowed);
+            e != hipSuccess)
+            return e;
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(64 * W), dyn, st, a);
     return hipGetLastError();

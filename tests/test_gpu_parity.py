@@ -320,10 +320,13 @@ def test_ablation_variants_compute_the_same(choice, M):
     assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
 
 
-@pytest.mark.parametrize("kernel", ["stream", "tiled"])
-def test_extreme_codes_exact(kernel):
-    say(f"extreme codes kernel={kernel}")
-    M, K, N = 3, 28672, 64                      # the longest reduction of the workloads
+@pytest.mark.parametrize("K", [28672, 65536])   # the workloads' longest reduction; the longest allowed
+@pytest.mark.parametrize("kernel", ["stream", "tiled", "tiled 256x256", "tiled 256x256 cut"])
+def test_extreme_codes_exact(kernel, K):
+    """Every product at its extreme: the int32 sums (kept times four inside the kernels) reach
+    2^28 at K = 28672 and 2^30 at the largest K the library accepts."""
+    say(f"extreme codes kernel={kernel} K={K}")
+    M, N = (3 if kernel in ("stream", "tiled") else 130), 64   # the cut tail needs more than 128 tokens
     wq = np.full((N, K), -32, dtype=np.int8)
     wq[1] = 31
     xq = np.full((M, K), -128, dtype=np.int8)
@@ -334,11 +337,15 @@ def test_extreme_codes_exact(kernel):
     packed = fq.pack_w6(to_dev(wq), to_dev(sw))
     acc_ref = oracle.matmul(xq, wq)
     y_ref = oracle.dequant(acc_ref, sx, sw)
-    fq.set_dispatch(1 if kernel == "stream" else 2, 0)
+    cfg = {"stream": 0, "tiled": 0, "tiled 256x256": 12, "tiled 256x256 cut": 13}[kernel]
+    fq.set_dispatch(1 if kernel == "stream" else 2, 1 if cfg else 0, 0, cfg)
     try:
         y, acc = run_linear(fq.gemm_w6a8, packed, N, K, 0, to_dev(xq), to_dev(sx), True)
+        launched = fq.last_dispatch()
     finally:
         fq.set_dispatch(0, 0)
+    if cfg:
+        assert launched[0] == cfg
     assert acc[0, 0] == 32 * 128 * K
     assert np.array_equal(acc.astype(np.int64), acc_ref)
     assert_y_close(y.view(np.float16), y_ref)

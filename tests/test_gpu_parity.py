@@ -489,6 +489,47 @@ def test_graph_replay_matches_eager():
         assert_y_close(got[0].cpu().numpy().view(np.float16), ref["y"])
 
 
+def test_graph_replay_of_the_cut_tail():
+    """The persistent 256x256 kernel (partial sums and counters in the workspace, no
+    memset, nobody waits) captured in a HIP graph: three replays with fresh inputs, eager
+    work in between, each equal to the eager result and to the oracle."""
+    say("graph capture / replay, 256x256 tiles with the tail cut along K")
+    M, K, N = 300, 2304, 1120                    # 10 ragged tiles, 40 runs
+    w = synth.weights(N, K, 0.02, seed=41)
+    packed, _, _ = prepare(w)
+    x = to_dev(synth.activations(M, K, seed=42))
+    y = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    ws = fq.make_workspace(M, N, K)
+
+    def enqueue():
+        fq.set_dispatch(2, 1, 0, 13)
+        try:
+            fq.gemm_w6a8(packed, N, K, 0, x_fp16=x, workspace=ws, out=y)
+            assert fq.last_dispatch()[0] == 13
+        finally:
+            fq.set_dispatch(0, 0, 0, 0)
+
+    enqueue()
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            enqueue()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        x.copy_(to_dev(synth.activations(M, K, seed=500 + rep)))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        enqueue()                                # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(y, got), rep
+        ref = oracle.linear(x.cpu().numpy(), w, 8)
+        assert_y_close(got.cpu().numpy().view(np.float16), ref["y"])
+    assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
+
+
 # ------------------------------------------- full-size shapes, sampled outputs
 
 def build_packed(N, K, sigma, seed, group=0):

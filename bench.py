@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
 # Bytes fetched past L2 + written, per launch, averaged over the four layers: rocprofv3 FETCH_SIZE and
 # WRITE_SIZE runs of this script, scaled on a 1 GiB device copy (x2.000 and x1.000); the runs, the
 # raw readings and the per-layer table are in profiles/bench_llama2_70b_linears_hbm_traffic.md.
-TRAFFIC_GEMM_M4096 = 1202.5e6 + 172.0e6
+TRAFFIC_GEMM_M4096 = 1106.1e6 + 172.0e6
 TRAFFIC_GEMV_M1 = 160.76e6 + 0.042e6
 SIGMA = 0.015
 LAYERS = [("qkv", 8192, 10240, 6), ("o", 8192, 8192, 6), ("gate_up", 8192, 57344, 6),

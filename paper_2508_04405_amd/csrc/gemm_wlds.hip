@@ -113,7 +113,10 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_ti
             u0 += ke - ks;
         }
         const int KN = ke - ks;
-        constexpr int SUP_M = 8;  // super-block: 8 tiles along m, then next n
+        // The 32 tiles an XCD works on at a time share operand panels in its L2: a block of
+        // 4 tiles along m x 8 along n fetches the fewest bytes (4 activation panels of 2 MB
+        // per 8192 of K + 8 weight panels of 1.5 MB).
+        constexpr int SUP_M = 4;  // super-block: 4 tiles along m, then next n
         const int sup = bid / (SUP_M * tiles_n);
         const int first_m = sup * SUP_M;
         const int span_m = min(SUP_M, tiles_m - first_m);

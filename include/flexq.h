@@ -175,7 +175,7 @@ flexq_status flexq_workspace_init(void *workspace, size_t workspace_bytes,
  * group 128.  Any M >= 1 is accepted (the tiled kernel needs (M+256)*K and
  * 0.75*N*K below 2^32, else FLEXQ_ESHAPE); flexq_gemm_* pick the kernel from M,
  * flexq_gemv_* are the same calls under the name the decode path uses: for
- * M <= 32 (24 on layers wider than 32768; 64 on layers of at most 2^26 weights,
+ * M <= 32 (24 on layers wider than 32768; 64 on layers of at most 2^25 weights,
  * 128 on layers of at most 2^24) both run the bandwidth-bound streaming kernel.
  */
 flexq_status flexq_gemm_w6a6(const void *packed, int group, const int8_t *xq,
@@ -243,8 +243,8 @@ flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg)
 /*
  * What the last GEMM / GEMV call of this process launched, for tests and tables:
  * 1000 * c + s, with c = 1 for the streaming kernel, else the tile configuration of
- * the tiled kernels (7: 128x256, 8: 128x128, 12: 256x256 with both operands through
- * LDS, 13: its persistent form), and s = the number of K splits (for c = 13: the
+ * the tiled kernels (5: 64x128, 7: 128x256, 8: 128x128, 12: 256x256 with both operands
+ * through LDS, 13: its persistent form), and s = the number of K splits (for c = 13: the
  * number of runs the last, partial round of tiles was cut into).  0 before any call.
  */
 int flexq_last_dispatch(void);

@@ -154,12 +154,14 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     // 32 tokens needs a second MFMA row tile), while the tiled kernel's time stays flat up
     // to 128 tokens but carries the fixed cost of its K splits on small layers.  So: up to
     // 32 tokens stream (24 on very wide layers: the 57344-wide gate+up is 17 % faster tiled
-    // at 32), up to 64 on layers of at most 2^26 weights, up to 128 on layers of at most 2^24
-    // (LLaMA-2-7B's 4096 x 4096: 24 vs 31 us at 128 tokens).
+    // at 32), up to 64 on layers of at most 2^25 weights (2^26 with group-wise scales, which
+    // have no 64-row tile), up to 128 on layers of at most 2^24 (LLaMA-2-7B's 4096 x 4096:
+    // 24 vs 31 us at 128 tokens).
     (void)prefer_stream;
     const bool tiled_ok = (long)(M + 256) * K < (1L << 32) && (long)N * K / 4 * 3 < (1L << 32);
     const long weights = (long)N * K;
-    bool stream_kernel = M <= 24 || (M <= 32 && N < 32768) || (M <= 64 && weights <= (1L << 26)) ||
+    bool stream_kernel = M <= 24 || (M <= 32 && N < 32768) ||
+                         (M <= 64 && weights <= (group == 0 ? (1L << 25) : (1L << 26))) ||
                          (M <= 128 && weights <= (1L << 24)) || (M <= 64 && !tiled_ok);
     // group-wise activation scales reach the tiled kernel by 4-byte DMA loads: even stride
     if (sxg && (sxg_stride % 2 != 0 || !tiled_ok)) stream_kernel = true;

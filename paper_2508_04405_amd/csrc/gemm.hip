@@ -315,7 +315,8 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
             // MFMA of step s, i.e. in the shadow of the MFMA just issued.  The
             // scheduling barriers keep that order (left alone, the scheduler sinks the
             // LDS reads next to their first use and gathers the MFMAs).
-            static_assert(MT >= 4, "one dword of the next operand per MFMA");
+            static_assert(MT == 2 || MT >= 4, "one dword of the next operand per MFMA, or two");
+            constexpr int DPM = MT >= 4 ? 1 : 4 / MT;   // dwords of the next operand per MFMA
             v4i af[2][MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -335,8 +336,11 @@ void gemm_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     acc[mt][nt] = mfma_i8(af[j & 1][mt], bfc, acc[mt][nt]);
-                    if (mt < 4 && s + 1 < 4 * NT)
-                        bfn[mt] = unpack_kstep_dword(wreg[CUR][(s + 1) % NT], (s + 1) / NT, mt);
+                    if (mt * DPM < 4 && s + 1 < 4 * NT) {
+#pragma unroll
+                        for (int d = mt * DPM; d < (mt + 1) * DPM; ++d)
+                            bfn[d] = unpack_kstep_dword(wreg[CUR][(s + 1) % NT], (s + 1) / NT, d);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 bfc = bfn;
@@ -620,6 +624,12 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
         // 1.03) takes 1.556 us per 128-k stage plus 7 us
         const double unit = (1.556 * (a.K / 128) + 7.0) * 1.03 / 65536.0;
         double t_best;
+        if (a.M <= 64) {
+            // every token fits a 64-row tile: half the MFMAs and half the activation bytes
+            // of the 128x128 tile, same columns and K splits (5-10 % faster, measured)
+            *chosen = 5;
+            return launch_cfg<1, 4, 2, 1, 0, 4>(a, st);
+        }
         if (a.split_k > 1) {   // K splits were chosen for 128x128 tiles; meeting costs about 11 us
             cfg = 8;
             const double *thr8 = m128 * n128 * a.split_k <= 256 ? thr8_sparse : thr8_busy;
@@ -664,6 +674,7 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
     case 6: return launch_cfg<1, 4, 8, 2, 0, 1>(a, st);   // 256x256, 4 waves side by side (256x64 each)
     case 7: return launch_cfg<1, 4, 4, 2, 0, 2>(a, st);   // 128x256, 4 waves side by side, 2 workgroups/CU
     case 8: return launch_cfg<1, 4, 4, 1, 0, 3>(a, st);   // 128x128, 4 waves side by side, 3 workgroups/CU
+    case 5: return launch_cfg<1, 4, 2, 1, 0, 4>(a, st);   // 64x128, 4 waves side by side, 4 workgroups/CU
     default: *chosen = 7; return launch_cfg<1, 4, 4, 2, 0, 2>(a, st);
     }
 }

@@ -241,7 +241,7 @@ def test_tiled_kernel_k_splits(split, M, group):
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 6, 7, 8, 12, 13])
+@pytest.mark.parametrize("cfg", [1, 2, 5, 6, 7, 8, 12, 13])
 @pytest.mark.parametrize("M,K,N", [(5, 128, 32), (130, 384, 96), (300, 640, 544), (513, 1280, 288),
                                    (512, 256, 544)])
 def test_tiled_kernel_tile_shapes(cfg, M, K, N):

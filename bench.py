@@ -45,7 +45,7 @@ def gemm_bytes(M, N, K):
     return 0.75 * N * K + 2 * N + M * K + 2 * M + 2 * M * N
 
 
-def sweep(args, torch, fq, synth, dev):
+def sweep(args, torch, fq, fqdev, synth, dev):
     """Per-layer time of the linear-layer call (pre-quantized activations) for each token
     count, the four layers cycled so that every launch streams its weights from HBM."""
     gen = torch.Generator(device=dev)
@@ -77,7 +77,7 @@ def sweep(args, torch, fq, synth, dev):
         def cycle(record):
             for i, (name, K, N, bits) in enumerate(LAYERS):
                 xq, sx, y, ws = bufs[i]
-                fn = fq.gemm_w6a6 if bits == 6 else fq.gemm_w6a8
+                fn = fqdev.gemm_w6a6 if bits == 6 else fqdev.gemm_w6a8   # (reports what it launched)
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
                 e0.record()
@@ -85,7 +85,7 @@ def sweep(args, torch, fq, synth, dev):
                 e1.record()
                 if record:
                     times[i].append((e0, e1))
-                    kinds[i] = fq.last_dispatch()
+                    kinds[i] = fqdev.last_dispatch()
 
         # warm up for at least 50 ms of GPU work (the host-side input generation above
         # leaves the GPU idle, and its clock takes a while to come back up)
@@ -111,7 +111,7 @@ def sweep(args, torch, fq, synth, dev):
         del bufs
 
 
-def layer_table(args, torch, fq, synth, dev):
+def layer_table(args, torch, fq, fqdev, synth, dev):
     """One decoder layer's seven linears as four calls (fused QKV, O, fused gate+up, down), each
     fed by the producer that quantizes its input: RMS norm + quantize before QKV and gate+up,
     the library's own quantize step before O (fp16 in: its input comes from attention, which is
@@ -190,7 +190,7 @@ def layer_table(args, torch, fq, synth, dev):
         del w_qkv, w_o, w_gu, w_dn
 
 
-def ablation(args, torch, fq, synth, dev):
+def ablation(args, torch, fq, fqdev, synth, dev):
     """GEMV time with one design choice of the streaming kernel undone per row (the paper's
     Table 6 on this machine).  Each shape is replicated until the copies exceed twice the
     Infinity Cache, the launches over all copies are captured in a HIP graph and the graph is
@@ -221,11 +221,11 @@ def ablation(args, torch, fq, synth, dev):
         xq, sx = fq.quant_act(x, bits)
         y = torch.empty((1, N), dtype=torch.float16, device=dev)
         ws = fq.make_workspace(1, N, K, dev)
-        gemv = fq.gemv_w6a6 if bits == 6 else fq.gemv_w6a8
+        gemv = fqdev.gemv_w6a6 if bits == 6 else fqdev.gemv_w6a8
         nbytes = gemm_bytes(1, N, K)
         for label, opt in rows:
-            fq.set_dispatch(1, opt.get("split", 0), opt.get("waves", 8 if "ablate" in opt else 0), 0)
-            fq.set_ablation(opt.get("ablate", 0))
+            fqdev.set_dispatch(1, opt.get("split", 0), opt.get("waves", 8 if "ablate" in opt else 0), 0)
+            fqdev.set_ablation(opt.get("ablate", 0))
 
             def launches():
                 for p in packed:
@@ -256,8 +256,8 @@ def ablation(args, torch, fq, synth, dev):
                 us = e0.elapsed_time(e1) * 1e3 / (args.steps * copies)
                 table[label].append("%.2f (%.0f)" % (us, nbytes / us / 1e3))
             finally:
-                fq.set_ablation(0)
-                fq.set_dispatch(0, 0, 0, 0)
+                fqdev.set_ablation(0)
+                fqdev.set_dispatch(0, 0, 0, 0)
     for label, _ in rows:
         print("| %s | " % label + " | ".join(table[label]) + " |", flush=True)
 
@@ -293,7 +293,7 @@ def main():
     import numpy as np
     import torch
     import paper_2508_04405_amd as fq
-    from paper_2508_04405_amd import synth
+    from paper_2508_04405_amd import dev as fqdev, synth
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -310,15 +310,19 @@ def main():
                           "bytes_written_per_copy": nbytes}))
         return
     fq.load()
+    # the product library runs the benchmark; a forced tile configuration needs the
+    # development library (same sources, per-call overrides)
+    lin = fq
     if args.gemm_cfg:
-        fq.set_dispatch(0, 0, 0, args.gemm_cfg)
+        fqdev.set_dispatch(0, 0, 0, args.gemm_cfg)
+        lin = fqdev
 
     if args.sweep:
-        return sweep(args, torch, fq, synth, dev)
+        return sweep(args, torch, fq, fqdev, synth, dev)
     if args.ablation:
-        return ablation(args, torch, fq, synth, dev)
+        return ablation(args, torch, fq, fqdev, synth, dev)
     if args.layer:
-        return layer_table(args, torch, fq, synth, dev)
+        return layer_table(args, torch, fq, fqdev, synth, dev)
 
     # ---- resident inputs: packed weights, fp16 activations -----------------
     gen = torch.Generator(device=dev)
@@ -357,9 +361,7 @@ def main():
                  out=b["y"])
             return
         fq.quant_act(b["x"], layer["bits"], out=(b["xq"], b["sx"]))
-        gemm = fq.gemm_w6a6 if layer["bits"] == 6 else fq.gemm_w6a8
-        if tag == "decode":
-            gemm = fq.gemv_w6a6 if layer["bits"] == 6 else fq.gemv_w6a8
+        gemm = lin.gemm_w6a6 if layer["bits"] == 6 else lin.gemm_w6a8
         if events is not None:
             e0 = torch.cuda.Event(enable_timing=True)
             e1 = torch.cuda.Event(enable_timing=True)
@@ -444,21 +446,21 @@ def main():
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     for layer in layers:                                   # warm-up
-        fq.probe_hbm_read(layer["packed"], sink)
+        fqdev.probe_hbm_read(layer["packed"], sink)
     torch.cuda.synchronize()
     e0.record()
     for _ in range(args.steps):
         for layer in layers:                               # 642 MB per pass: cold, like the GEMV
-            fq.probe_hbm_read(layer["packed"], sink)
+            fqdev.probe_hbm_read(layer["packed"], sink)
     e1.record()
     torch.cuda.synchronize()
     read_gbs = sum(L["packed"].numel() for L in layers) * args.steps / (e0.elapsed_time(e1) * 1e-3) / 1e9
     a_ops, b_ops = layers[0]["prefill"]["xq"], layers[0]["packed"]
-    fq.probe_mfma_i8(a_ops, b_ops, 50, 512, sink)
+    fqdev.probe_mfma_i8(a_ops, b_ops, 50, 512, sink)
     torch.cuda.synchronize()
     iters = 4000                                           # ~1 ms, like one GEMM launch
     e0.record()
-    fq.probe_mfma_i8(a_ops, b_ops, iters, 512, sink)
+    fqdev.probe_mfma_i8(a_ops, b_ops, iters, 512, sink)
     e1.record()
     torch.cuda.synchronize()
     mfma_tops = 2.0 * 32768 * 16 * iters * 4 * 512 / (e0.elapsed_time(e1) * 1e-3) / 1e12

@@ -140,8 +140,10 @@ flexq_status flexq_swiglu_quant(const uint16_t *gate_up, int M, int F,
  * split-K partial sums and their arrival counters, and for the quantized
  * activations when the quantize prologue is requested.  Never 0 for a valid
  * shape.  For M > 128, when the 256x256 output tiles do not come in a multiple
- * of 256 (the CUs of an MI355X), it includes 128 MiB in which the workgroups
- * sharing a tile of the last, partial round leave their int32 sums.  The workspace must be 256-byte aligned, and its first
+ * of 256 (the CUs of an MI355X), it includes up to 128 MiB (512 KiB per 128-k
+ * stage of those tiles, at most 256 of them) in which the workgroups sharing a
+ * tile of the last, partial round leave their int32 sums.  It depends on M, N
+ * and K only.  The workspace must be 256-byte aligned, and its first
  * FLEXQ_WORKSPACE_COUNTER_BYTES bytes must be zero before the first call that
  * uses it (flexq_workspace_init does that); every call leaves them zero again.
  * Calls that share a workspace must be ordered on one stream.
@@ -229,64 +231,6 @@ flexq_status flexq_linear_g128(const void *packed, const int8_t *xq,
                                const uint16_t *sxg, int sxg_stride, int M,
                                int N, int K, uint16_t *y, void *workspace,
                                size_t workspace_bytes, void *stream);
-
-/*
- * Tuning hook for experiments and tests: force the kernel the next calls use.
- * which: 0 = automatic, 1 = streaming (skinny) kernel, 2 = tiled GEMM kernel.
- * split_k: 0 = automatic, else the number of K splits of the streaming kernel.
- * waves: 0 = automatic, else wavefronts per workgroup of the streaming kernel
- * (4, 8 or 16).  gemm_cfg: 0 = automatic, else a tile configuration of the
- * tiled kernel.  Process-wide; returns FLEXQ_EINVAL for unknown values.
- */
-flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg);
-
-/*
- * What the last GEMM / GEMV call of this process launched, for tests and tables:
- * 1000 * c + s, with c = 1 for the streaming kernel, else the tile configuration of
- * the tiled kernels (5: 64x128, 7: 128x256, 8: 128x128, 12: 256x256 with both operands
- * through LDS, 13: its persistent form), and s = the number of K splits (for c = 13: the
- * number of runs the last, partial round of tiles was cut into).  0 before any call.
- */
-int flexq_last_dispatch(void);
-
-/*
- * Ablation hook (measurement only, in the manner of the paper's Table 6): undo
- * ONE design choice of the streaming decode kernel for the next calls.
- *   0  nothing undone (the default)
- *   1  weight tiles through ordinary cached loads instead of non-temporal ones
- *      (Section 4.3.2's evict-first hint, undone)
- *   2  one weight tile in flight per wavefront instead of four (Section 4.3.6's
- *      multi-stage pipeline, undone)     3  two tiles in flight
- *   4  activations loaded per tile from global memory instead of staged once
- *      in LDS
- * Applies to per-channel scales, M <= 32, pre-quantized activations and 8
- * wavefronts per workgroup; other calls return FLEXQ_EHIP while a choice is
- * set.  Process-wide; FLEXQ_EINVAL for unknown values.  Results are unchanged.
- */
-flexq_status flexq_set_ablation(int choice);
-
-/*
- * Measurement helpers (no arithmetic of the method): the ceilings a roofline
- * fraction can be read against on the machine at hand.
- *
- * flexq_probe_hbm_read: a kernel that only reads `bytes` bytes at `src` (dev,
- * 16-byte aligned) with 16-byte loads, 12 KiB in flight per wavefront.  bytes /
- * its duration is the read bandwidth a streaming kernel can reach at that size.
- *
- * flexq_probe_mfma_i8: `workgroups` workgroups of four wavefronts each issue
- * iters * 16 independent v_mfma_i32_32x32x32_i8 on operands held in registers,
- * taken from the first 16 KiB at a_operands (int8 activation codes) and
- * b_operands (packed weight bytes, low two bits cleared as the kernels do).
- * 2 * 32768 * 16 * iters * 4 * workgroups / its duration is the int8 rate the
- * matrix pipe sustains on such data.
- *
- * `sink` (dev, 4 bytes) is never written in practice; it keeps the work alive.
- */
-flexq_status flexq_probe_hbm_read(const void *src, size_t bytes, void *sink,
-                                  void *stream);
-flexq_status flexq_probe_mfma_i8(const void *a_operands, const void *b_operands,
-                                 int iters, int workgroups, void *sink,
-                                 void *stream);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,85 @@
+/*
+ * flexq_dev.h -- C ABI of the DEVELOPMENT library, libflexq_dev.so.
+ *
+ * Test and measurement infrastructure, not part of the product: the same sources
+ * as libflexq.so compiled with FLEXQ_DEV, which adds (a) the linear-layer call
+ * with per-call overrides of the kernel choice, (b) kernel variants that undo one
+ * design choice of the decode kernel (in the manner of the paper's Table 6) and
+ * tile shapes the dispatch never picks, (c) two probes of the machine's ceilings.
+ * libflexq.so exports none of this and contains none of those kernels.  Nothing
+ * here keeps state between calls.  Conventions as in flexq.h.
+ */
+#ifndef FLEXQ_DEV_H
+#define FLEXQ_DEV_H
+
+#include "flexq.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Overrides for ONE call; every field 0 = the library's own choice.
+ *   kernel    1 = streaming (skinny) kernel, 2 = tiled GEMM kernels
+ *   split_k   number of K splits (streaming kernel; 128x128 tiles), at most 64
+ *   waves     wavefronts per workgroup of the streaming kernel: 4, 8 or 16
+ *   gemm_cfg  tile configuration of the tiled kernels (the codes flexq_dev_linear
+ *             reports back, below)
+ *   ablate    undo one design choice of the streaming decode kernel (Table 6):
+ *             1  weight tiles through ordinary cached loads instead of non-temporal
+ *                ones (Section 4.3.2's evict-first hint, undone)
+ *             2  one weight tile in flight per wavefront instead of four (Section
+ *                4.3.6's multi-stage pipeline, undone)      3  two tiles in flight
+ *             4  activations loaded per tile from global memory instead of staged
+ *                once in LDS
+ *             (per-channel scales, M <= 32, pre-quantized activations, waves = 8;
+ *             other calls return FLEXQ_EHIP while a choice is set)
+ */
+typedef struct {
+    int kernel, split_k, waves, gemm_cfg, ablate;
+} flexq_dev_tuning;
+
+/*
+ * flexq_gemm_w6a6 / _w6a8 / flexq_linear_g128 (Section 4.2 Eq. 5, Eq. 7) with
+ * overrides.  act_bits 6 or 8; sxg non-NULL selects group-wise activation scales
+ * (then group must be 128, sx and x_fp16 NULL).  tuning NULL = automatic; any
+ * field out of range -> FLEXQ_EINVAL before anything else happens.  *dispatched
+ * (may be NULL) receives what was launched: 1000 * c + s, c = 1 for the streaming
+ * kernel, else the tile configuration (5: 64x128, 7: 128x256, 8: 128x128,
+ * 12: 256x256 with both operands through LDS, one workgroup per tile,
+ * 13: its persistent form), s = the number of K splits (for 13: the number of
+ * runs the last, partial round of tiles was cut into).  Results are the same
+ * whatever the overrides.
+ */
+flexq_status flexq_dev_linear(const flexq_dev_tuning *tuning, int act_bits, const void *packed,
+                              int group, const int8_t *xq, const uint16_t *sx,
+                              const uint16_t *x_fp16, const uint16_t *sxg, int sxg_stride,
+                              int M, int N, int K, uint16_t *y, int32_t *acc_out,
+                              void *workspace, size_t workspace_bytes, void *stream,
+                              int *dispatched);
+
+/*
+ * Measurement helpers (no arithmetic of the method): the ceilings a roofline
+ * fraction can be read against on the machine at hand.
+ *
+ * flexq_dev_probe_hbm_read: a kernel that only reads `bytes` bytes at `src` (dev,
+ * 16-byte aligned) with 16-byte loads, 12 KiB in flight per wavefront.  bytes /
+ * its duration is the read bandwidth a streaming kernel can reach at that size.
+ *
+ * flexq_dev_probe_mfma_i8: `workgroups` workgroups of four wavefronts each issue
+ * iters * 16 independent v_mfma_i32_32x32x32_i8 on operands held in registers,
+ * taken from the first 16 KiB at a_operands (int8 activation codes) and
+ * b_operands (packed weight bytes, low two bits cleared as the kernels do).
+ * 2 * 32768 * 16 * iters * 4 * workgroups / its duration is the int8 rate the
+ * matrix pipe sustains on such data.
+ *
+ * `sink` (dev, 4 bytes) is never written in practice; it keeps the work alive.
+ */
+flexq_status flexq_dev_probe_hbm_read(const void *src, size_t bytes, void *sink, void *stream);
+flexq_status flexq_dev_probe_mfma_i8(const void *a_operands, const void *b_operands, int iters,
+                                     int workgroups, void *sink, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXQ_DEV_H */

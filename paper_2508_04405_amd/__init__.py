@@ -1,9 +1,11 @@
 """MI355X-native W6A6 / W6A8 quantized linear layer (GEMM + decode GEMV).
 
 `binding` is the thin ctypes layer over the C ABI in include/flexq.h; `synth`
-draws the seeded synthetic inputs; `build` compiles the HIP sources.
+draws the seeded synthetic inputs; `build` compiles the HIP sources; `dev` (not
+imported here) binds the development library of include/flexq_dev.h for tests
+and measurement tables.
 """
 from .binding import (FlexQError, gemm_w6a6, gemm_w6a8, gemv_w6a6, gemv_w6a8,  # noqa: F401
-                      last_dispatch, layout_version, linear_g128, load, make_workspace, pack_w6, packed_bytes,
-                      probe_hbm_read, probe_mfma_i8, quant_act, quant_act_g128, quant_w6,
-                      rmsnorm_quant, set_ablation, set_dispatch, swiglu_quant, unpack_w6, workspace_bytes)
+                      layout_version, linear_g128, load, make_workspace,
+                      pack_w6, packed_bytes, quant_act, quant_act_g128, quant_w6, rmsnorm_quant,
+                      swiglu_quant, unpack_w6, workspace_bytes)

@@ -20,12 +20,12 @@ class FlexQError(RuntimeError):
 
 
 def load():
-    """Load libflexq.so (building it first only if it has never been built)."""
+    """Load libflexq.so, building it first if it is missing or older than its sources."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        from . import build as _build
+    from . import build as _build
+    if _build.sources_newer_than(LIB_PATH):
         _build.build()
     lib = ctypes.CDLL(LIB_PATH)
     c_int, c_size, vp = ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
@@ -59,16 +59,6 @@ def load():
         fn = getattr(lib, name)
         fn.restype = c_int
         fn.argtypes = [vp, c_int, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp, c_size, vp]
-    lib.flexq_probe_hbm_read.restype = c_int
-    lib.flexq_probe_hbm_read.argtypes = [vp, c_size, vp, vp]
-    lib.flexq_probe_mfma_i8.restype = c_int
-    lib.flexq_probe_mfma_i8.argtypes = [vp, vp, c_int, c_int, vp, vp]
-    lib.flexq_set_ablation.restype = c_int
-    lib.flexq_set_ablation.argtypes = [c_int]
-    lib.flexq_last_dispatch.restype = c_int
-    lib.flexq_last_dispatch.argtypes = []
-    lib.flexq_set_dispatch.restype = c_int
-    lib.flexq_set_dispatch.argtypes = [c_int, c_int, c_int, c_int]
     _lib = lib
     return lib
 
@@ -97,35 +87,6 @@ def layout_version():
 
 def packed_bytes(N, K, group=0):
     return load().flexq_packed_bytes(N, K, group)
-
-
-def set_ablation(choice=0):
-    _check(load().flexq_set_ablation(choice))
-
-
-def last_dispatch():
-    """(kernel, splits) of the last GEMM / GEMV call: kernel 1 = streaming, else the tile
-    configuration; for configuration 13 the second number is the runs of its cut tail."""
-    code = load().flexq_last_dispatch()
-    return code // 1000, code % 1000
-
-
-def set_dispatch(which=0, split_k=0, waves=0, gemm_cfg=0):
-    _check(load().flexq_set_dispatch(which, split_k, waves, gemm_cfg))
-
-
-def probe_hbm_read(buf, sink):
-    """Enqueue the read-only streaming kernel over `buf` (any dtype, contiguous)."""
-    _check(load().flexq_probe_hbm_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink),
-                                       _stream()))
-
-
-def probe_mfma_i8(a_operands, b_operands, iters, workgroups, sink):
-    """Enqueue the MFMA-only kernel; operands are read from the first 16 KiB of each buffer."""
-    assert a_operands.numel() * a_operands.element_size() >= 16384
-    assert b_operands.numel() * b_operands.element_size() >= 16384
-    _check(load().flexq_probe_mfma_i8(_ptr(a_operands), _ptr(b_operands), iters, workgroups,
-                                      _ptr(sink), _stream()))
 
 
 def quant_w6(w, group=0):
@@ -301,3 +262,4 @@ def gemv_w6a6(packed, N, K, group=0, xq=None, sx=None, x_fp16=None, workspace=No
 def gemv_w6a8(packed, N, K, group=0, xq=None, sx=None, x_fp16=None, workspace=None,
               want_acc=False, out=None):
     return _linear("flexq_gemv_w6a8", packed, N, K, group, xq, sx, x_fp16, workspace, want_acc, out)
+

@@ -3,16 +3,14 @@
 #include "../../include/flexq.h"
 #include "flexq_kernels.h"
 
-#include <atomic>
+#include "api_internal.h"
+
+// The library keeps no mutable state: every choice below is a function of the call's
+// arguments (and, in the development build only, of the Tuning passed with the call).
 
 namespace {
 
-std::atomic<int> g_force_kernel{0};
-std::atomic<int> g_force_split{0};
-std::atomic<int> g_force_waves{0};
-std::atomic<int> g_ablate{0};
-std::atomic<int> g_force_gemm_cfg{0};
-std::atomic<int> g_last_dispatch{0};
+using flexq::Tuning;
 
 constexpr int kMaxRowBlocks = FLEXQ_WORKSPACE_COUNTER_BYTES / 4;
 constexpr int kSkinnyMaxM = 128;
@@ -37,9 +35,8 @@ size_t scale_count(int N, int K, int group) { return group == 0 ? (size_t)N : (s
 // further only adds hand-offs.  So split just enough to reach 128 workgroups,
 // keep at least two tiles per wavefront, and keep the partial-sum traffic (8 bytes
 // per split, token and column) under a ninth of the weight stream.
-int choose_split(int M, int N, int K)
+int choose_split(int M, int N, int K, int forced = 0)
 {
-    const int forced = g_force_split.load();
     const int kt = K / 128;
     int ks;
     if (forced > 0) {
@@ -62,12 +59,12 @@ int choose_split(int M, int N, int K)
 // split until there is about one block per CU (measured optimum on MI355X: 4 splits
 // at M = 128, 2 at M = 256), keeping at least four 128-k stages per block and the
 // partial-sum traffic (8 bytes per split and output) under the weight bytes.
-int choose_gemm_split(int M, int N, int K)
+int choose_gemm_split(int M, int N, int K, int forced = 0)
 {
     const int kt = K / 128;
     int ks;
-    if (g_force_split.load() > 0) {
-        ks = g_force_split.load();
+    if (forced > 0) {
+        ks = forced;
     } else {
         const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
         // about one block per CU; two per CU once there are several row tiles and K is
@@ -86,9 +83,8 @@ int choose_gemm_split(int M, int N, int K)
 }
 
 // Wavefronts per workgroup of the streaming kernel.
-int choose_waves(int M, int N, int K, int ks)
+int choose_waves(int M, int N, int K, int ks, int forced = 0)
 {
-    const int forced = g_force_waves.load();
     if (forced > 0) return forced;
     const int tiles = K / 128 / ks;
     // few row blocks and long rows (the 7B / 13B down projections at one to four tokens):
@@ -125,10 +121,36 @@ Workspace carve(void *ws, size_t bytes, int M, int K)
     return w;
 }
 
-flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int group, const int8_t *xq,
-                    const uint16_t *sx, const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
-                    int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream,
-                    const uint16_t *sxg = nullptr, int sxg_stride = 0)
+size_t workspace_bytes_for(int M, int N, int K)
+{
+    if (M < 1 || check_shape(N, K, 0) != FLEXQ_OK) return 0;
+    size_t partial = 0;
+    const int top = M < kSkinnyMaxM ? M : kSkinnyMaxM;
+    for (int m = 1; m <= top; ++m) {
+        const int ks = choose_split(m, N, K);
+        const size_t b = ks > 1 ? (size_t)ks * m * N * 4 : 0;
+        if (b > partial) partial = b;
+    }
+    {
+        const int gs = choose_gemm_split(M, N, K);
+        const size_t b = gs > 1 ? (size_t)gs * M * N * 4 : 0;
+        if (b > partial) partial = b;
+    }
+    if (M > kSkinnyMaxM) {   // the 256x256 kernel's tail cut along K
+        const size_t b = flexq::streamk_plan(M, N, K).partial_bytes;
+        if (b > partial) partial = b;
+    }
+    return fixed_bytes(M, K) + round_up(partial, 256);
+}
+
+}  // namespace
+
+namespace flexq {
+
+flexq_status linear_check(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
+                          const uint16_t *x_fp16, int M, int N, int K, const uint16_t *y,
+                          const int32_t *acc_out, const void *workspace, size_t workspace_bytes,
+                          const uint16_t *sxg, int sxg_stride)
 {
     if (!packed || !y || M < 1) return FLEXQ_EINVAL;
     if (sxg) {   // scales per token and group: pre-quantized activations, group-128 weights
@@ -142,13 +164,26 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     if (!aligned16(packed) || !aligned16(y) || (acc_out && !aligned16(acc_out)) ||
         (x_fp16 && !aligned16(x_fp16)) || (!x_fp16 && !aligned16(xq)))
         return FLEXQ_EALIGN;
-    if (!workspace || workspace_bytes < flexq_workspace_bytes(M, N, K)) return FLEXQ_EWORKSPACE;
+    if (!workspace || workspace_bytes < workspace_bytes_for(M, N, K)) return FLEXQ_EWORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return FLEXQ_EALIGN;
+    return FLEXQ_OK;
+}
+
+flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, int group,
+                         const int8_t *xq, const uint16_t *sx, const uint16_t *x_fp16, int M, int N, int K,
+                         uint16_t *y, int32_t *acc_out, void *workspace, size_t workspace_bytes,
+                         void *stream, const uint16_t *sxg, int sxg_stride, int *dispatched)
+{
+    if (dispatched) *dispatched = 0;
+    if (flexq_status s = linear_check(packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
+                                      workspace_bytes, sxg, sxg_stride);
+        s != FLEXQ_OK)
+        return s;
 
     hipStream_t st = (hipStream_t)stream;
     Workspace ws = carve(workspace, workspace_bytes, M, K);
 
-    const int forced = g_force_kernel.load();
+    const int forced = tune.kernel;
     // Measured cross-over between the streaming kernel and the tiled kernel with K splits:
     // the streaming kernel re-reads the activations once per 32 output channels (and past
     // 32 tokens needs a second MFMA row tile), while the tiled kernel's time stays flat up
@@ -157,7 +192,6 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     // at 32), up to 64 on layers of at most 2^25 weights (2^26 with group-wise scales, which
     // have no 64-row tile), up to 128 on layers of at most 2^24 (LLaMA-2-7B's 4096 x 4096:
     // 24 vs 31 us at 128 tokens).
-    (void)prefer_stream;
     const bool tiled_ok = (long)(M + 256) * K < (1L << 32) && (long)N * K / 4 * 3 < (1L << 32);
     const long weights = (long)N * K;
     bool stream_kernel = M <= 24 || (M <= 32 && N < 32768) ||
@@ -171,7 +205,7 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     // Small decode batches: the streaming kernel quantizes the activations itself.
     // (Each workgroup then scans the token's whole fp16 row, which pays off while a
     // CU runs only a few workgroups: measured break-even near 1024 workgroups.)
-    const int ks0 = choose_split(M, N, K);
+    const int ks0 = choose_split(M, N, K, tune.split_k);
     const bool fuse = x_fp16 && stream_kernel && (long)(N / 32) * ks0 <= 1024 &&
                       flexq::skinny_can_fuse(M, K, ks0);
     if (x_fp16 && !fuse) {
@@ -194,28 +228,28 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
     a.qmax = act_bits == 6 ? 31.0f : 127.0f;
     a.sxg = nullptr;
     a.sxg_stride = sxg_stride;
-    a.ablate = g_ablate.load();
+    a.ablate = tune.ablate;
 
     if (!stream_kernel) {
         // the tiled kernel addresses both operands with 32-bit buffer offsets
-        if ((long)(M + 256) * K >= (1L << 32) || (long)N * K / 4 * 3 >= (1L << 32)) return FLEXQ_ESHAPE;
+        if (!tiled_ok) return FLEXQ_ESHAPE;
         a.xq = xq;
         a.sx = sx;
         a.sxg = sxg;
         a.M = M;
         a.y = y;
         a.acc_out = acc_out;
-        a.split_k = choose_gemm_split(M, N, K);
+        a.split_k = choose_gemm_split(M, N, K, tune.split_k);
         const size_t per_split = (size_t)M * N * 4;
         if ((size_t)a.split_k * per_split > ws.partial_capacity)
             a.split_k = (int)(ws.partial_capacity / per_split);
         if ((size_t)a.split_k * per_split >= ((size_t)1 << 32)) a.split_k = 1;   // 32-bit buffer offsets
         if (a.split_k < 2) a.split_k = 1;
-        int cfg = g_force_gemm_cfg.load();
-        if (cfg == 0 && g_force_split.load() > 0 && a.split_k > 1) cfg = 8;   // a forced split is honoured
+        int cfg = tune.gemm_cfg;
+        if (cfg == 0 && tune.split_k > 0 && a.split_k > 1) cfg = 8;   // a forced split is honoured
         int chosen = 0, tail_runs = 0;
         const hipError_t e = flexq::launch_gemm(a, cfg, st, &chosen, &tail_runs);
-        g_last_dispatch.store(chosen * 1000 + (chosen == 13 ? tail_runs : a.split_k));
+        if (dispatched) *dispatched = chosen * 1000 + (chosen >= 13 ? tail_runs : a.split_k);
         return e == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
     }
     for (int m0 = 0; m0 < M; m0 += kSkinnyMaxM) {
@@ -226,21 +260,28 @@ flexq_status linear(int act_bits, bool prefer_stream, const void *packed, int gr
         a.M = rows;
         a.y = y + (size_t)m0 * N;
         a.acc_out = acc_out ? acc_out + (size_t)m0 * N : nullptr;
-        a.split_k = choose_split(rows, N, K);
+        a.split_k = choose_split(rows, N, K, tune.split_k);
         // never outgrow the partial-sum area the caller provided
         const size_t per_split = (size_t)rows * N * 4;
         if ((size_t)a.split_k * per_split > ws.partial_capacity)
             a.split_k = (int)(ws.partial_capacity / per_split);
         if (a.split_k < 1) a.split_k = 1;
-        if (flexq::launch_skinny(a, choose_waves(rows, N, K, a.split_k), st) != hipSuccess)
+        if (flexq::launch_skinny(a, choose_waves(rows, N, K, a.split_k, tune.waves), st) != hipSuccess)
             return FLEXQ_EHIP;
-        g_last_dispatch.store(1000 + a.split_k);
+        if (dispatched) *dispatched = 1000 + a.split_k;
     }
     return FLEXQ_OK;
 }
 
+}  // namespace flexq
+
+namespace {
+
+const flexq::Tuning kAuto{};
+
 }  // namespace
 
+#pragma GCC visibility push(default)
 extern "C" {
 
 const char *flexq_status_string(flexq_status s)
@@ -359,30 +400,11 @@ flexq_status flexq_linear_g128(const void *packed, const int8_t *xq, const uint1
                                size_t workspace_bytes, void *stream)
 {
     if (!sxg) return FLEXQ_EINVAL;
-    return linear(8, true, packed, 128, xq, nullptr, nullptr, M, N, K, y, nullptr, workspace,
-                  workspace_bytes, stream, sxg, sxg_stride);
+    return flexq::linear_impl(kAuto, 8, packed, 128, xq, nullptr, nullptr, M, N, K, y, nullptr, workspace,
+                              workspace_bytes, stream, sxg, sxg_stride, nullptr);
 }
 
-size_t flexq_workspace_bytes(int M, int N, int K)
-{
-    if (M < 1 || check_shape(N, K, 0) != FLEXQ_OK) return 0;
-    size_t partial = 0;
-    const int top = M < kSkinnyMaxM ? M : kSkinnyMaxM;
-    for (int m = 1; m <= top; ++m) {
-        const size_t b = (size_t)choose_split(m, N, K) * m * N * 4;
-        if (b > partial) partial = b;
-    }
-    {
-        const int gs = choose_gemm_split(M, N, K);
-        const size_t b = gs > 1 ? (size_t)gs * M * N * 4 : 0;
-        if (b > partial) partial = b;
-    }
-    if (M > kSkinnyMaxM) {   // the 256x256 kernel's tail cut along K
-        const size_t b = flexq::streamk_plan(M, N).partial_bytes;
-        if (b > partial) partial = b;
-    }
-    return fixed_bytes(M, K) + round_up(partial, 256);
-}
+size_t flexq_workspace_bytes(int M, int N, int K) { return workspace_bytes_for(M, N, K); }
 
 flexq_status flexq_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -399,53 +421,33 @@ flexq_status flexq_gemm_w6a6(const void *packed, int group, const int8_t *xq, co
                              const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
                              int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return linear(6, false, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
-                  workspace_bytes, stream);
+    return flexq::linear_impl(kAuto, 6, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
+                              workspace_bytes, stream, nullptr, 0, nullptr);
 }
 
 flexq_status flexq_gemm_w6a8(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
                              const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
                              int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return linear(8, false, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
-                  workspace_bytes, stream);
+    return flexq::linear_impl(kAuto, 8, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
+                              workspace_bytes, stream, nullptr, 0, nullptr);
 }
 
 flexq_status flexq_gemv_w6a6(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
                              const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
                              int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return linear(6, true, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
-                  workspace_bytes, stream);
+    return flexq::linear_impl(kAuto, 6, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
+                              workspace_bytes, stream, nullptr, 0, nullptr);
 }
 
 flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
                              const uint16_t *x_fp16, int M, int N, int K, uint16_t *y,
                              int32_t *acc_out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return linear(8, true, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
-                  workspace_bytes, stream);
-}
-
-int flexq_last_dispatch(void) { return g_last_dispatch.load(); }
-
-flexq_status flexq_set_ablation(int choice)
-{
-    if (choice < 0 || choice > 4) return FLEXQ_EINVAL;
-    g_ablate.store(choice);
-    return FLEXQ_OK;
-}
-
-flexq_status flexq_set_dispatch(int which, int split_k, int waves, int gemm_cfg)
-{
-    if (gemm_cfg < 0 || gemm_cfg > 32) return FLEXQ_EINVAL;
-    g_force_gemm_cfg.store(gemm_cfg);
-    if (which < 0 || which > 2 || split_k < 0 || split_k > 64) return FLEXQ_EINVAL;
-    if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return FLEXQ_EINVAL;
-    g_force_kernel.store(which);
-    g_force_split.store(split_k);
-    g_force_waves.store(waves);
-    return FLEXQ_OK;
+    return flexq::linear_impl(kAuto, 8, packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
+                              workspace_bytes, stream, nullptr, 0, nullptr);
 }
 
 }  // extern "C"
+#pragma GCC visibility pop

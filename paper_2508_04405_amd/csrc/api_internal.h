@@ -1,0 +1,33 @@
+// What the C ABI in api.hip shares with the development entry points (dev_api.hip,
+// built into libflexq_dev.so only): the one function behind every linear-layer call.
+#pragma once
+#include "../../include/flexq.h"
+
+namespace flexq {
+
+// Per-call overrides of the library's own kernel choice; all zero = automatic.
+// The product entry points always pass all zeros.
+struct Tuning {
+    int kernel = 0;     // 1 = streaming kernel, 2 = tiled kernels
+    int split_k = 0;    // K splits (streaming kernel, 128x128 tiles)
+    int waves = 0;      // wavefronts per workgroup of the streaming kernel: 4, 8, 16
+    int gemm_cfg = 0;   // tile configuration of the tiled kernels
+    int ablate = 0;     // development build: one design choice of the streaming kernel undone
+};
+
+// The argument checks of linear_impl alone (host only, launches nothing).
+flexq_status linear_check(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
+                          const uint16_t *x_fp16, int M, int N, int K, const uint16_t *y,
+                          const int32_t *acc_out, const void *workspace, size_t workspace_bytes,
+                          const uint16_t *sxg, int sxg_stride);
+
+// act_bits 6 or 8.  sxg non-null: group-wise activation scales (group must be 128).
+// *dispatched (may be null) receives 1000 * c + s: c = 1 for the streaming kernel, else
+// the tile configuration that ran; s = its K splits (for the forms that cut their last
+// round of tiles: the number of pieces).
+flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, int group,
+                         const int8_t *xq, const uint16_t *sx, const uint16_t *x_fp16, int M, int N, int K,
+                         uint16_t *y, int32_t *acc_out, void *workspace, size_t workspace_bytes,
+                         void *stream, const uint16_t *sxg, int sxg_stride, int *dispatched);
+
+}  // namespace flexq

@@ -22,6 +22,23 @@ inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<u
     return e;
 }
 
+// Compute units of the current device (cached per device; 0 if the query fails).  The
+// persistent launch forms and their tile order are laid out for the MI355X's 256 CUs in
+// 8 XCDs and are only used when the device really has that many.
+inline int device_cu_count()
+{
+    static std::atomic<int> cached[64];
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return 0;
+    std::atomic<int> &slot = cached[device & 63];
+    int n = slot.load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
+        slot.store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
 // Everything a GEMM / GEMV launch needs.  Pointers are device pointers.
 struct LinearArgs {
     const void *packed;      // tiles, then scales
@@ -83,7 +100,7 @@ struct StreamKPlan {
     int tiles, full_tiles, tail_tiles;   // 256x256 tiles: all, those in whole rounds, the rest
     size_t partial_bytes;                // workspace for the partial sums of the rest
 };
-StreamKPlan streamk_plan(int M, int N);
+StreamKPlan streamk_plan(int M, int N, int K);
 // Estimated time (microseconds) of the better of the two forms (of the first, if the tail
 // may not be cut), and that form's tail_wgs.
 double gemm_wlds_estimate_us(int M, int N, int K, bool may_cut, int *tail_wgs);

@@ -593,10 +593,12 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
     // of the register file (which vector instructions cannot read directly).
     if (a.group != 0) {
         if (a.sxg) return launch_cfg<1, 4, 4, 1, 2, 2>(a, st);          // scales per group on both operands
+#ifdef FLEXQ_DEV
         if (cfg == 21) {
             *chosen = 21;
             return launch_cfg<1, 4, 4, 2, 1, 1>(a, st);      // 128x256, 1 wave/SIMD
         }
+#endif
         return launch_cfg<1, 4, 4, 1, 1, 2>(a, st);
     }
     if (cfg == 0) {
@@ -643,7 +645,8 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
         }
         if (a.M > 128) {
             int tail_wgs = 0;
-            const bool may_cut = a.partial_bytes >= streamk_plan(a.M, a.N).partial_bytes;
+            const bool may_cut = a.partial_bytes >= streamk_plan(a.M, a.N, a.K).partial_bytes &&
+                                 device_cu_count() == kStreamKGrid;
             double t = gemm_wlds_estimate_us(a.M, a.N, a.K, may_cut, &tail_wgs);
             // a cut tail must promise 5 % (it adds workspace traffic the estimate is unsure
             // of); else the tiles run whole, if that is the fastest
@@ -669,9 +672,11 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
         return launch_gemm_wlds(a, tail_wgs, st);
     }
     switch (cfg) {
+#ifdef FLEXQ_DEV   // shapes the dispatch never picks: kept selectable for comparisons
     case 1: return launch_cfg<2, 2, 4, 4, 0, 1>(a, st);   // 256x256, 4 waves, 1 wave/SIMD
     case 2: return launch_cfg<2, 4, 4, 2, 0, 2>(a, st);   // 256x256, 8 waves (128x64 each)
     case 6: return launch_cfg<1, 4, 8, 2, 0, 1>(a, st);   // 256x256, 4 waves side by side (256x64 each)
+#endif
     case 7: return launch_cfg<1, 4, 4, 2, 0, 2>(a, st);   // 128x256, 4 waves side by side, 2 workgroups/CU
     case 8: return launch_cfg<1, 4, 4, 1, 0, 3>(a, st);   // 128x128, 4 waves side by side, 3 workgroups/CU
     case 5: return launch_cfg<1, 4, 2, 1, 0, 4>(a, st);   // 64x128, 4 waves side by side, 4 workgroups/CU

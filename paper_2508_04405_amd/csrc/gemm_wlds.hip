@@ -293,7 +293,7 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_ti
             // device scope: the access goes to memory all XCDs share.
             constexpr int kScopeAgent = 16;
             const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
-                a.partial, 0, (unsigned)(2 * G) * (unsigned)SLOT_BYTES, 0x00020000);
+                a.partial, 0, (unsigned)(2 * tail_wgs) * (unsigned)SLOT_BYTES, 0x00020000);
             const unsigned in_slot = (unsigned)(wave * (SLOT_BYTES / WAVES) + lane * 16);
             const long tile_begin = (long)tj * KT;
             // a run leaves at most two partial tiles: slot 2 vt for the one it begins in,
@@ -475,13 +475,15 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_ti
 
 namespace flexq {
 
-StreamKPlan streamk_plan(int M, int N)
+StreamKPlan streamk_plan(int M, int N, int K)
 {
     StreamKPlan p;
     p.tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     p.full_tiles = p.tiles / kStreamKGrid * kStreamKGrid;
     p.tail_tiles = p.tiles - p.full_tiles;
-    p.partial_bytes = p.tail_tiles ? (size_t)2 * kStreamKGrid * SLOT_BYTES : 0;
+    // two slots per run; a run is at least one 128-k stage, and there are at most 256 runs
+    const long stages = (long)p.tail_tiles * (K / FLEXQ_TILE_K);
+    p.partial_bytes = (size_t)2 * (size_t)(stages < kStreamKGrid ? stages : kStreamKGrid) * SLOT_BYTES;
     return p;
 }
 
@@ -494,7 +496,7 @@ StreamKPlan streamk_plan(int M, int N)
 // end inside tiles (two partial tiles per workgroup).
 double gemm_wlds_estimate_us(int M, int N, int K, bool may_cut, int *tail_wgs)
 {
-    const StreamKPlan p = streamk_plan(M, N);
+    const StreamKPlan p = streamk_plan(M, N, K);
     const int KT = K / FLEXQ_TILE_K;
     const double stage_us = 1.556, tile_us = stage_us * KT + 7.0;
     const double whole_rounds = (double)(p.full_tiles / kStreamKGrid) * tile_us;
@@ -529,9 +531,11 @@ hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_wgs, hipStream_t st)
     if (e == hipSuccess)
         e = allow_dynamic_lds(reinterpret_cast<const void *>(gemm_wlds_kernel<true>), LDS_BYTES, lds_allowed[1]);
     if (e != hipSuccess) return e;
-    const StreamKPlan p = streamk_plan(a.M, a.N);
-    // (without room for the partial sums the tail tiles simply run whole)
-    if (tail_wgs <= 0 || p.tail_tiles == 0 || a.partial_bytes < p.partial_bytes) {
+    const StreamKPlan p = streamk_plan(a.M, a.N, a.K);
+    // (without room for the partial sums, or on a device that is not 256 CUs wide, the
+    // tail tiles simply run whole)
+    if (tail_wgs <= 0 || p.tail_tiles == 0 || a.partial_bytes < p.partial_bytes ||
+        device_cu_count() != kStreamKGrid) {
         hipLaunchKernelGGL(gemm_wlds_kernel<false>, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WAVES),
                            LDS_BYTES, st, a, tiles_m, tiles_n, 0, 0, 0);
         return hipGetLastError();

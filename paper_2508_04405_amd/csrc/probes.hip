@@ -3,8 +3,8 @@
 // buffer from HBM, and how fast the matrix pipe runs the i8 MFMA on operands
 // with the bit statistics of the real workload (the chip lowers its clock with
 // switching activity, so this is well under the published peak).  No part of
-// the linear layer's arithmetic.
-#include "../../include/flexq.h"
+// the linear layer's arithmetic; built into the development library only.
+#include "../../include/flexq_dev.h"
 #include "flexq_device.h"
 
 namespace {
@@ -56,9 +56,10 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const v4i *__restrict__
 
 }  // namespace
 
+#pragma GCC visibility push(default)
 extern "C" {
 
-flexq_status flexq_probe_hbm_read(const void *src, size_t bytes, void *sink, void *stream)
+flexq_status flexq_dev_probe_hbm_read(const void *src, size_t bytes, void *sink, void *stream)
 {
     if (!src || !sink || bytes < 1024) return FLEXQ_EINVAL;
     if ((reinterpret_cast<uintptr_t>(src) & 15u) != 0) return FLEXQ_EALIGN;
@@ -70,7 +71,7 @@ flexq_status flexq_probe_hbm_read(const void *src, size_t bytes, void *sink, voi
     return hipGetLastError() == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
 }
 
-flexq_status flexq_probe_mfma_i8(const void *a_operands, const void *b_operands, int iters,
+flexq_status flexq_dev_probe_mfma_i8(const void *a_operands, const void *b_operands, int iters,
                                  int workgroups, void *sink, void *stream)
 {
     if (!a_operands || !b_operands || !sink || iters < 1 || workgroups < 1) return FLEXQ_EINVAL;
@@ -83,3 +84,4 @@ flexq_status flexq_probe_mfma_i8(const void *a_operands, const void *b_operands,
 }
 
 }  // extern "C"
+#pragma GCC visibility pop

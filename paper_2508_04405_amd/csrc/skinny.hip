@@ -458,7 +458,11 @@ hipError_t pick(const flexq::LinearArgs &a, int waves, hipStream_t st)
         if (waves == 8) return launch_one<1, G, true, true, 4, 8, 4>(a, st);
         return launch_one<1, G, true, true, 4, 4, 4>(a, st);
     }
-    // Ablation variants (measurement only): one design choice of the decode kernel undone.
+    // Ablation variants (development build, measurement only): one design choice of the
+    // decode kernel undone.
+#ifndef FLEXQ_DEV
+    if (a.ablate != 0) return hipErrorInvalidValue;
+#else
     if (a.ablate != 0) {
         if (GROUP != 0 || a.M > 32 || a.x_fp16 || waves != 8) return hipErrorInvalidValue;
         constexpr int G = 0;
@@ -469,6 +473,7 @@ hipError_t pick(const flexq::LinearArgs &a, int waves, hipStream_t st)
         if (a.ablate == 3) return launch_one<1, G, true, false, 2, 8, 4>(a, st);   // two tiles in flight
         return hipErrorInvalidValue;
     }
+#endif
     if (a.M <= 32) {
         if (xlds) {
             if (waves == 16) return launch_one<1, GROUP, true, false, 4, 16, 4>(a, st);

@@ -7,25 +7,45 @@ import re
 import pytest
 
 import paper_2508_04405_amd as fq
+from paper_2508_04405_amd import dev
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 P16 = ctypes.c_void_p(0x1000)          # a non-null, 256-byte aligned fake pointer
 ODD = ctypes.c_void_p(0x1008)          # 8-byte aligned only
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "flexq.h")).read()
+def _declared(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(flexq_[a-z0-9_]+)\s*\(", text)))
 
 
+def _exported(path):
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], check=True, capture_output=True, text=True)
+    return sorted(line.split()[-1] for line in out.stdout.splitlines() if " T " in line)
+
+
 def test_every_declared_symbol_is_exported():
     lib = fq.load()
-    names = _declared()
+    names = _declared("flexq.h")
     assert {"flexq_pack_w6", "flexq_quant_act", "flexq_gemm_w6a6", "flexq_gemm_w6a8",
             "flexq_gemv_w6a8"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
+    dlib = dev.load()
+    for n in names + _declared("flexq_dev.h"):
+        assert hasattr(dlib, n), n
+
+
+def test_the_product_library_exports_the_header_and_nothing_else():
+    """No tuning hook, probe or other development entry point in libflexq.so: its exported
+    functions are exactly the ones include/flexq.h declares."""
+    fq.load()
+    from paper_2508_04405_amd import binding
+    assert _exported(binding.LIB_PATH) == _declared("flexq.h")
+    dev.load()
+    assert _exported(dev.LIB_PATH) == sorted(set(_declared("flexq.h") + _declared("flexq_dev.h")))
 
 
 def test_sizes():
@@ -50,13 +70,17 @@ def test_workspace_covers_the_partial_sums():
     lib = fq.load()
     fixed = lambda M, K: 16384 + -(-M * K // 256) * 256 + -(-M * 2 // 256) * 256
     cut = 2 * 256 * 256 * 256 * 4
-    # 4096 x 8192 outputs = 512 tiles, 4096 x 57344 = 3584: whole rounds, nothing to cut;
-    # what remains is the streaming kernel's area for the row chunks of 128 tokens
-    assert lib.flexq_workspace_bytes(4096, 8192, 8192) == fixed(4096, 8192) + 128 * 8192 * 4
-    assert lib.flexq_workspace_bytes(4096, 57344, 8192) == fixed(4096, 8192) + 128 * 57344 * 4
+    # 4096 x 8192 outputs = 512 tiles, 4096 x 57344 = 3584: whole rounds, nothing to cut,
+    # and no K splits either
+    assert lib.flexq_workspace_bytes(4096, 8192, 8192) == fixed(4096, 8192)
+    assert lib.flexq_workspace_bytes(4096, 57344, 8192) == fixed(4096, 8192)
     # 4096 x 10240 = 640 tiles, 1024 x 8192 = 128: a partial round
     assert lib.flexq_workspace_bytes(4096, 10240, 8192) == fixed(4096, 8192) + cut
     assert lib.flexq_workspace_bytes(1024, 8192, 28672) == fixed(1024, 28672) + cut
+    # a lone 256x256 tile of two 128-k stages can be cut in two at most: four slots
+    assert lib.flexq_workspace_bytes(200, 256, 256) == fixed(200, 256) + 4 * 256 * 256 * 4
+    # the answer depends on the shape alone (nothing a caller did before changes it)
+    assert lib.flexq_workspace_bytes(1024, 8192, 28672) == dev.load().flexq_workspace_bytes(1024, 8192, 28672)
     # up to 128 tokens only the K splits of the streaming and 128x128 kernels count
     small = lib.flexq_workspace_bytes(128, 8192, 8192)
     assert fixed(128, 8192) < small < fixed(128, 8192) + 64 * 128 * 8192 * 4
@@ -135,14 +159,30 @@ def test_other_entry_points_argument_errors():
     assert lib.flexq_unpack_w6(P16, 96, 300, 0, P16, P16, None) == -2
     assert lib.flexq_workspace_init(None, 1 << 20, None) == -1
     assert lib.flexq_workspace_init(P16, 16, None) == -5
-    assert lib.flexq_probe_hbm_read(None, 4096, P16, None) == -1
-    assert lib.flexq_probe_hbm_read(ODD, 4096, P16, None) == -3
-    assert lib.flexq_probe_mfma_i8(P16, P16, 0, 1, P16, None) == -1
-    assert lib.flexq_set_dispatch(3, 0, 0, 0) == -1
-    assert lib.flexq_set_dispatch(0, 0, 5, 0) == -1
-    assert lib.flexq_set_dispatch(0, 0, 0, 0) == 0
-    assert lib.flexq_set_ablation(5) == -1
-    assert lib.flexq_set_ablation(-1) == -1
-    assert lib.flexq_set_ablation(0) == 0
-    assert lib.flexq_last_dispatch() >= 0
     assert b"shape" in lib.flexq_status_string(-2)
+
+
+def test_dev_entry_points_argument_errors():
+    d = dev.load()
+    assert d.flexq_dev_probe_hbm_read(None, 4096, P16, None) == -1
+    assert d.flexq_dev_probe_hbm_read(ODD, 4096, P16, None) == -3
+    assert d.flexq_dev_probe_mfma_i8(P16, P16, 0, 1, P16, None) == -1
+    big = 1 << 30
+
+    def call(tuning, bits=8, **kw):
+        a = dict(packed=P16, group=0, xq=P16, sx=P16, x=None, sxg=None, stride=0, M=4, N=128, K=256,
+                 y=P16, acc=None, ws=P16, wsb=big)
+        a.update(kw)
+        t = dev.Tuning(**tuning) if tuning is not None else None
+        return d.flexq_dev_linear(t, bits, a["packed"], a["group"], a["xq"], a["sx"], a["x"], a["sxg"],
+                                  a["stride"], a["M"], a["N"], a["K"], a["y"], a["acc"], a["ws"],
+                                  a["wsb"], None, None)
+
+    zero = dict(kernel=0, split_k=0, waves=0, gemm_cfg=0, ablate=0)
+    for bad in (dict(kernel=3), dict(waves=5), dict(split_k=65), dict(gemm_cfg=33), dict(ablate=5),
+                dict(ablate=-1), dict(kernel=-1)):
+        assert call(dict(zero, **bad)) == -1, bad
+    assert call(zero, bits=7) == -1
+    assert call(zero, y=None) == -1              # the same checks as the product call, host side
+    assert call(None, N=100) == -2
+    assert call(zero, ws=None) == -5

@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import paper_2508_04405_amd as fq
-from paper_2508_04405_amd import synth
+from paper_2508_04405_amd import dev, synth
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -39,6 +39,13 @@ def assert_y_close(got, want, slack=None):
         err = np.abs(got.astype(np.float64) - want.astype(np.float64))
         ulp = np.abs(want.astype(np.float64)) * 2.0**-10 + 2.0**-24
         bad &= err > ulp + slack
+        # The bound is a worst case; with rounding errors of random sign the fp32 sum of G
+        # terms is off by about sqrt(G) 2^-25 of a typical term, which crosses a second
+        # fp16 boundary only where the terms cancel almost completely.  So at most one
+        # output in a thousand (two, for small cases) may lie beyond one ulp at all.
+        beyond = int((d > 1).sum())
+        say(f"    group mode: {d.size} outputs, beyond 1 ulp: {beyond}, worst distance {int(d.max())} ulp")
+        assert beyond <= max(2, d.size // 1000), (beyond, d.size)
     assert not bad.any(), (int(bad.sum()), got[bad][:5], want[bad][:5])
     rel = np.abs(got.astype(np.float64) - want.astype(np.float64))
     big = np.abs(want.astype(np.float64)) > 2.0**-14
@@ -182,12 +189,12 @@ def test_linear_per_channel(M, K, N, bits, kernel):
     assert np.array_equal(wq.cpu().numpy(), ref["wq"])
     xq, sx = fq.quant_act(to_dev(x), bits)
     assert np.array_equal(xq.cpu().numpy(), ref["xq"])
-    fq.set_dispatch(1 if kernel == "stream" else 2, 0)
+    dev.set_dispatch(1 if kernel == "stream" else 2, 0)
     try:
-        fn = {6: fq.gemm_w6a6, 8: fq.gemm_w6a8}[bits]
+        fn = {6: dev.gemm_w6a6, 8: dev.gemm_w6a8}[bits]
         y, acc = run_linear(fn, packed, N, K, 0, xq, sx, True)
     finally:
-        fq.set_dispatch(0, 0)
+        dev.set_dispatch(0, 0)
     assert np.array_equal(acc.astype(np.int64), ref["acc"])
     assert_y_close(y.view(np.float16), ref["y"])
 
@@ -204,14 +211,14 @@ def test_stream_kernel_k_splits(split, M, waves):
     packed, _, _ = prepare(w)
     xq, sx = fq.quant_act(to_dev(x), 8)
     ws = fq.make_workspace(M, N, K, extra=split * M * N * 4)
-    fq.set_dispatch(1, split, waves)
+    dev.set_dispatch(1, split, waves)
     try:
         for _ in range(3):                      # counters must return to zero each call
-            y, acc = run_linear(fq.gemv_w6a8, packed, N, K, 0, xq, sx, True, ws)
+            y, acc = run_linear(dev.gemv_w6a8, packed, N, K, 0, xq, sx, True, ws)
             assert np.array_equal(acc.astype(np.int64), ref["acc"])
             assert_y_close(y.view(np.float16), ref["y"])
     finally:
-        fq.set_dispatch(0, 0)
+        dev.set_dispatch(0, 0)
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
@@ -227,17 +234,17 @@ def test_tiled_kernel_k_splits(split, M, group):
     packed, _, _ = prepare(w, group)
     xq, sx = fq.quant_act(to_dev(x), 8)
     ws = fq.make_workspace(M, N, K, extra=split * M * N * 4)
-    fq.set_dispatch(2, split, 0, 0)
+    dev.set_dispatch(2, split, 0, 0)
     try:
         for _ in range(2):                      # counters must return to zero each call
-            y, acc = run_linear(fq.gemm_w6a8, packed, N, K, group, xq, sx, group == 0, ws)
+            y, acc = run_linear(dev.gemm_w6a8, packed, N, K, group, xq, sx, group == 0, ws)
             if group == 0:
                 assert np.array_equal(acc.astype(np.int64), ref["acc"])
                 assert_y_close(y.view(np.float16), ref["y"])
             else:
                 assert_y_close(y.view(np.float16), ref["y"], slack=group_slack(ref))
     finally:
-        fq.set_dispatch(0, 0, 0, 0)
+        dev.set_dispatch(0, 0, 0, 0)
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
@@ -253,13 +260,13 @@ def test_tiled_kernel_tile_shapes(cfg, M, K, N):
     packed, _, _ = prepare(w)
     xq, sx = fq.quant_act(to_dev(x), 8)
     ref = oracle.linear(x, w, 8)
-    fq.set_dispatch(2, 1, 0, cfg)
+    dev.set_dispatch(2, 1, 0, cfg)
     try:
-        y, acc = fq.gemm_w6a8(packed, N, K, xq=xq, sx=sx, want_acc=True)
-        y_only = fq.gemm_w6a8(packed, N, K, xq=xq, sx=sx)      # whole slabs take a path of their own
+        y, acc = dev.gemm_w6a8(packed, N, K, xq=xq, sx=sx, want_acc=True)
+        y_only = dev.gemm_w6a8(packed, N, K, xq=xq, sx=sx)      # whole slabs take a path of their own
         torch.cuda.synchronize()
     finally:
-        fq.set_dispatch(0, 0, 0, 0)
+        dev.set_dispatch(0, 0, 0, 0)
     assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
     assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
     # (not bit for bit the same as y: the compiler is free to round the fp32 product to
@@ -282,16 +289,16 @@ def test_tiled_kernel_tail_cut_along_k(M, K, N):
     xq, sx = fq.quant_act(to_dev(x), 8)
     ref = oracle.linear(x, w, 8)
     ws = fq.make_workspace(M, N, K)
-    fq.set_dispatch(2, 1, 0, 13)
+    dev.set_dispatch(2, 1, 0, 13)
     try:
         for _ in range(2):
-            y, acc = run_linear(fq.gemm_w6a8, packed, N, K, 0, xq, sx, True, ws)
+            y, acc = run_linear(dev.gemm_w6a8, packed, N, K, 0, xq, sx, True, ws)
             assert np.array_equal(acc.astype(np.int64), ref["acc"])
             assert_y_close(y.view(np.float16), ref["y"])
-        y_only = fq.gemm_w6a8(packed, N, K, xq=xq, sx=sx, workspace=ws)
+        y_only = dev.gemm_w6a8(packed, N, K, xq=xq, sx=sx, workspace=ws)
         torch.cuda.synchronize()
     finally:
-        fq.set_dispatch(0, 0, 0, 0)
+        dev.set_dispatch(0, 0, 0, 0)
     assert_y_close(y_only.cpu().numpy().view(np.float16), ref["y"])
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
@@ -308,14 +315,14 @@ def test_ablation_variants_compute_the_same(choice, M):
     packed, _, _ = prepare(w)
     xq, sx = fq.quant_act(to_dev(x), 8)
     ref = oracle.linear(x, w, 8)
-    fq.set_dispatch(1, 0, 8, 0)
-    fq.set_ablation(choice)
+    dev.set_dispatch(1, 0, 8, 0)
+    dev.set_ablation(choice)
     try:
-        y, acc = fq.gemv_w6a8(packed, N, K, xq=xq, sx=sx, want_acc=True)
+        y, acc = dev.gemv_w6a8(packed, N, K, xq=xq, sx=sx, want_acc=True)
         torch.cuda.synchronize()
     finally:
-        fq.set_ablation(0)
-        fq.set_dispatch(0, 0)
+        dev.set_ablation(0)
+        dev.set_dispatch(0, 0)
     assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
     assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
 
@@ -338,12 +345,12 @@ def test_extreme_codes_exact(kernel, K):
     acc_ref = oracle.matmul(xq, wq)
     y_ref = oracle.dequant(acc_ref, sx, sw)
     cfg = {"stream": 0, "tiled": 0, "tiled 256x256": 12, "tiled 256x256 cut": 13}[kernel]
-    fq.set_dispatch(1 if kernel == "stream" else 2, 1 if cfg else 0, 0, cfg)
+    dev.set_dispatch(1 if kernel == "stream" else 2, 1 if cfg else 0, 0, cfg)
     try:
-        y, acc = run_linear(fq.gemm_w6a8, packed, N, K, 0, to_dev(xq), to_dev(sx), True)
-        launched = fq.last_dispatch()
+        y, acc = run_linear(dev.gemm_w6a8, packed, N, K, 0, to_dev(xq), to_dev(sx), True)
+        launched = dev.last_dispatch()
     finally:
-        fq.set_dispatch(0, 0)
+        dev.set_dispatch(0, 0)
     if cfg:
         assert launched[0] == cfg
     assert acc[0, 0] == 32 * 128 * K
@@ -362,11 +369,11 @@ def test_linear_group128(M, K, N, kernel):
     assert np.array_equal(wq.cpu().numpy(), ref["wq"])
     assert np.array_equal(sw.cpu().numpy().view(np.uint16), ref["sw"].view(np.uint16))
     xq, sx = fq.quant_act(to_dev(x), 8)
-    fq.set_dispatch(1 if kernel == "stream" else 2, 0)
+    dev.set_dispatch(1 if kernel == "stream" else 2, 0)
     try:
-        y, _ = run_linear(fq.gemm_w6a8, packed, N, K, 128, xq, sx, False)
+        y, _ = run_linear(dev.gemm_w6a8, packed, N, K, 128, xq, sx, False)
     finally:
-        fq.set_dispatch(0, 0)
+        dev.set_dispatch(0, 0)
     assert_y_close(y.view(np.float16), ref["y"], slack=group_slack(ref))
     # the integer group partials: per-channel calls on 128-wide K slices
     g = 1
@@ -388,14 +395,14 @@ def test_quantize_prologue(bits, M):
     if M > 1:
         x[M - 1, :] = 0                          # a token of zeros: scale 1.0, zero output
     ref = oracle.linear(x, w, bits)
-    fn = {6: fq.gemm_w6a6, 8: fq.gemm_w6a8}[bits]
+    fn = {6: dev.gemm_w6a6, 8: dev.gemm_w6a8}[bits]
     for split in (0, 2):                         # M <= 8: quantized inside the streaming kernel
-        fq.set_dispatch(0, split, 0, 0)
+        dev.set_dispatch(0, split, 0, 0)
         try:
             y, acc = fn(packed, N, K, 0, x_fp16=to_dev(x), want_acc=True)
             torch.cuda.synchronize()
         finally:
-            fq.set_dispatch(0, 0, 0, 0)
+            dev.set_dispatch(0, 0, 0, 0)
         assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
         assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
     # the two activation widths really differ
@@ -439,11 +446,11 @@ def test_smallest_and_longest_shapes(kernel, M, K, N):
     packed = fq.pack_w6(to_dev(wq), to_dev(sw))
     acc_ref = oracle.matmul(xq, wq)
     y_ref = oracle.dequant(acc_ref, sx, sw)
-    fq.set_dispatch(1 if kernel == "stream" else 2, 0, 0, 0)
+    dev.set_dispatch(1 if kernel == "stream" else 2, 0, 0, 0)
     try:
-        y, acc = run_linear(fq.gemm_w6a8, packed, N, K, 0, to_dev(xq), to_dev(sx), True)
+        y, acc = run_linear(dev.gemm_w6a8, packed, N, K, 0, to_dev(xq), to_dev(sx), True)
     finally:
-        fq.set_dispatch(0, 0, 0, 0)
+        dev.set_dispatch(0, 0, 0, 0)
     if K == 65536:
         assert acc[0, 0] == 32 * 128 * K          # 2^28: the 4x internal sum is 2^30
     assert np.array_equal(acc.astype(np.int64), acc_ref)
@@ -502,12 +509,12 @@ def test_graph_replay_of_the_cut_tail():
     ws = fq.make_workspace(M, N, K)
 
     def enqueue():
-        fq.set_dispatch(2, 1, 0, 13)
+        dev.set_dispatch(2, 1, 0, 13)
         try:
-            fq.gemm_w6a8(packed, N, K, 0, x_fp16=x, workspace=ws, out=y)
-            assert fq.last_dispatch()[0] == 13
+            dev.gemm_w6a8(packed, N, K, 0, x_fp16=x, workspace=ws, out=y)
+            assert dev.last_dispatch()[0] == 13
         finally:
-            fq.set_dispatch(0, 0, 0, 0)
+            dev.set_dispatch(0, 0, 0, 0)
 
     enqueue()
     torch.cuda.synchronize()
@@ -547,13 +554,29 @@ def build_packed(N, K, sigma, seed, group=0):
     return packed
 
 
-def check_sampled(packed, N, K, sigma, seed, M, bits, group=0, prologue=False, n_rows=30, n_cols=124):
-    """Sampled rows x columns against the oracle with full-K dot products, plus
-    the size-independent property acc(-x) = -acc(x) on every output."""
+def stratified(total, block, rng, extra=()):
+    """One seeded index in every `block`-wide slice of range(total), plus `extra`."""
+    starts = np.arange(0, total, block)
+    picks = starts + rng.integers(0, block, starts.size)
+    return np.unique(np.concatenate([np.minimum(picks, total - 1), np.asarray(extra, dtype=np.int64)]))
+
+
+def sampled_columns(N, K, sigma, seed):
+    """The output columns a full-size case checks, and their weight rows: one column in
+    every 32-column block (every weight tile, hence every workgroup tile and every slot of
+    the kernels' tile orders, is hit), plus the edges of the first two blocks and the last."""
+    cols = stratified(N, 32, np.random.default_rng(seed + 1), [0, 31, 32, N - 1])
+    return cols, synth.weight_rows_at(N, K, sigma, seed, cols)
+
+
+def check_sampled(packed, N, K, sigma, seed, M, bits, cols, w_cols, group=0, prologue=False):
+    """One row in every 32-row block x one column in every 32-column block against the
+    oracle with full-K dot products, through the product entry points: once asking for the
+    int32 sums as well, once for the fp16 output alone (the call a user and bench.py make;
+    the kernels store whole tiles on a path of their own then).  Plus the size-independent
+    property acc(-x) = -acc(x) on every output."""
     rng = np.random.default_rng(seed + 17 * M + bits)
-    cols = np.unique(np.concatenate([[0, 31, 32, N - 1], rng.integers(0, N, n_cols)]))
-    rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, n_rows)]))
-    w_cols = synth.weight_rows_at(N, K, sigma, seed, cols)
+    rows = stratified(M, 32, rng, [0, M - 1])
     x = synth.activations(M, K, seed=seed + M, outlier_frac=0.01)
     ref = oracle.linear(x[rows], w_cols, bits, group)
     ws = fq.make_workspace(M, N, K)
@@ -561,19 +584,26 @@ def check_sampled(packed, N, K, sigma, seed, M, bits, group=0, prologue=False, n
     fn = {(6, True): fq.gemv_w6a6, (8, True): fq.gemv_w6a8, (6, False): fq.gemm_w6a6,
           (8, False): fq.gemm_w6a8}[(bits, stream)]
     want_acc = group == 0
+    rows_t, cols_t = to_dev(rows), to_dev(cols)
+
+    def pick(t):
+        return t[rows_t][:, cols_t].cpu().numpy()
+
     if prologue:
         out = fn(packed, N, K, group, x_fp16=to_dev(x), want_acc=want_acc, workspace=ws)
+        y_only = fn(packed, N, K, group, x_fp16=to_dev(x), workspace=ws) if want_acc else None
     else:
         xq, sx = fq.quant_act(to_dev(x), bits)
-        assert np.array_equal(xq.cpu().numpy()[rows], ref["xq"])
-        assert np.array_equal(sx.cpu().numpy().view(np.uint16)[rows], ref["sx"].view(np.uint16))
+        assert np.array_equal(xq[rows_t].cpu().numpy(), ref["xq"])
+        assert np.array_equal(sx[rows_t].cpu().numpy().view(np.uint16), ref["sx"].view(np.uint16))
         out = fn(packed, N, K, group, xq=xq, sx=sx, want_acc=want_acc, workspace=ws)
+        y_only = fn(packed, N, K, group, xq=xq, sx=sx, workspace=ws) if want_acc else None
     torch.cuda.synchronize()
-    y = (out[0] if want_acc else out).cpu().numpy()[np.ix_(rows, cols)]
+    y = pick(out[0] if want_acc else out)
     if want_acc:
-        acc = out[1].cpu().numpy()[np.ix_(rows, cols)]
-        assert np.array_equal(acc.astype(np.int64), ref["acc"])
+        assert np.array_equal(pick(out[1]).astype(np.int64), ref["acc"])
         assert_y_close(y.view(np.float16), ref["y"])
+        assert_y_close(pick(y_only).view(np.float16), ref["y"])
         if not prologue:
             neg = (-xq.to(torch.int16)).clamp(-128, 127).to(torch.int8)
             _, acc2 = fn(packed, N, K, 0, xq=neg, sx=sx, want_acc=True, workspace=ws)
@@ -584,16 +614,23 @@ def check_sampled(packed, N, K, sigma, seed, M, bits, group=0, prologue=False, n
 
 
 FULL = [
-    # LLaMA-2-70B linears (the bench workload), then the 7B fused gate+up for a ragged N
-    # (token counts 33..64 and 256 / 512 sit on the dispatch boundaries between the streaming
-    # kernel, the tiled kernel with K splits, and the tile shapes; down at 512 / 1024 and
-    # gate+up at 1536 tokens run the persistent 256x256 kernel with its last round cut along K)
-    ("70b_o", 8192, 8192, 0.015, [(1, 8), (16, 6), (48, 6), (64, 8), (128, 8), (1024, 6), (4096, 8)]),
-    ("70b_qkv", 8192, 10240, 0.015, [(1, 6), (16, 8), (48, 8), (256, 6), (4096, 6)]),
-    ("70b_gate_up", 8192, 57344, 0.015, [(1, 6), (33, 8), (1536, 6), (4096, 6)]),
+    # LLaMA-2-70B linears (the bench workload) over the configuration's token counts
+    # 1, 16, 128, 1024, 4096 for every layer, plus token counts on the dispatch boundaries
+    # between the streaming kernel, the tiled kernel with K splits, and the tile shapes
+    # (33..64, 256, 512, 1536, 2048, 3072: partial rounds of 256x256 tiles);
+    # then the LLaMA-2-7B linears at its decode (1, 8) and prefill (512, 2048, 4096) counts.
+    ("70b_o", 8192, 8192, 0.015, [(1, 8), (16, 6), (48, 6), (64, 8), (128, 8), (1024, 6), (3072, 6),
+                                  (4096, 8)]),
+    ("70b_qkv", 8192, 10240, 0.015, [(1, 6), (16, 8), (48, 8), (128, 6), (256, 6), (1024, 8), (2048, 6),
+                                     (4096, 6)]),
+    ("70b_gate_up", 8192, 57344, 0.015, [(1, 6), (16, 8), (33, 8), (128, 6), (1024, 6), (1536, 6),
+                                         (4096, 6)]),
     ("70b_down", 28672, 8192, 0.015, [(1, 8), (16, 8), (40, 8), (128, 6), (256, 8), (512, 6),
                                       (1024, 8), (4096, 8)]),
-    ("7b_gate_up", 4096, 22016, 0.02, [(1, 8), (8, 8), (33, 6), (64, 8), (512, 6), (2048, 8)]),
+    ("7b_qkv", 4096, 12288, 0.02, [(8, 8), (512, 6), (2048, 8), (4096, 6)]),
+    ("7b_o", 4096, 4096, 0.02, [(8, 8), (512, 8), (2048, 6), (4096, 8)]),
+    ("7b_gate_up", 4096, 22016, 0.02, [(1, 8), (8, 8), (33, 6), (64, 8), (512, 6), (2048, 8), (4096, 6)]),
+    ("7b_down", 11008, 4096, 0.02, [(8, 8), (512, 6), (2048, 8), (4096, 8)]),
 ]
 
 
@@ -602,12 +639,13 @@ def test_full_size_sampled(name, K, N, sigma, cases):
     seed = 4000 + K + N
     say(f"full size {name}: generating and packing W[{N},{K}]")
     packed = build_packed(N, K, sigma, seed)
+    cols, w_cols = sampled_columns(N, K, sigma, seed)
     for M, bits in cases:
-        say(f"full size {name}: M={M} A{bits}")
-        check_sampled(packed, N, K, sigma, seed, M, bits)
+        say(f"full size {name}: M={M} A{bits}, {cols.size} columns")
+        check_sampled(packed, N, K, sigma, seed, M, bits, cols, w_cols)
     M, bits = cases[-1]
     say(f"full size {name}: M={M} A{bits} with the quantize prologue")
-    check_sampled(packed, N, K, sigma, seed, M, bits, prologue=True)
+    check_sampled(packed, N, K, sigma, seed, M, bits, cols, w_cols, prologue=True)
 
 
 @pytest.mark.parametrize("K,N", [(4096, 12288), (4096, 4096), (11008, 4096)])
@@ -635,9 +673,10 @@ def test_13b_group128_sampled(K, N):
     seed = 6000 + K + N
     say(f"13B group-128 K={K} N={N}: packing")
     packed = build_packed(N, K, 0.02, seed, group=128)
+    cols, w_cols = sampled_columns(N, K, 0.02, seed)
     for M, bits in ((32, 8), (32, 6), (2048, 6), (2048, 8)):
         say(f"13B group-128 K={K} N={N} M={M} A{bits}")
-        check_sampled(packed, N, K, 0.02, seed, M, bits, group=128, n_rows=20, n_cols=60)
+        check_sampled(packed, N, K, 0.02, seed, M, bits, cols, w_cols, group=128)
 
 
 # ------------------------------------------------ seeded random shapes, all modes
@@ -693,14 +732,14 @@ def test_random_shapes_forced_tiled_kernels():
         packed, _, _ = prepare(w)
         xq, sx = fq.quant_act(to_dev(x), 8)
         ws = fq.make_workspace(M, N, K, extra=split * M * N * 4)
-        fq.set_dispatch(2, split, 0, cfg)
+        dev.set_dispatch(2, split, 0, cfg)
         try:
             for _ in range(2):
-                y, acc = run_linear(fq.gemm_w6a8, packed, N, K, 0, xq, sx, True, ws)
+                y, acc = run_linear(dev.gemm_w6a8, packed, N, K, 0, xq, sx, True, ws)
                 assert np.array_equal(acc.astype(np.int64), ref["acc"]), case
                 assert_y_close(y.view(np.float16), ref["y"])
         finally:
-            fq.set_dispatch(0, 0, 0, 0)
+            dev.set_dispatch(0, 0, 0, 0)
         assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0, case
 
 
@@ -710,15 +749,14 @@ def test_dispatch_choices_on_the_70b_layers():
     decode, 256x256 tiles in whole rounds at 4096 tokens, 128x256 for the 10240-wide QKV,
     the persistent form with a cut tail for the down projection at 1024 tokens."""
     say("dispatch choices")
-    dev = torch.device("cuda:0")
 
     def launched(M, N, K):
-        packed = torch.zeros(fq.packed_bytes(N, K, 0), dtype=torch.uint8, device=dev)
-        xq = torch.zeros((M, K), dtype=torch.int8, device=dev)
-        sx = torch.ones((M,), dtype=torch.float16, device=dev)
-        fq.gemm_w6a8(packed, N, K, 0, xq=xq, sx=sx)
+        packed = torch.zeros(fq.packed_bytes(N, K, 0), dtype=torch.uint8, device=DEV)
+        xq = torch.zeros((M, K), dtype=torch.int8, device=DEV)
+        sx = torch.ones((M,), dtype=torch.float16, device=DEV)
+        dev.gemm_w6a8(packed, N, K, 0, xq=xq, sx=sx)
         torch.cuda.synchronize()
-        return fq.last_dispatch()
+        return dev.last_dispatch()
 
     assert launched(1, 8192, 8192)[0] == 1
     assert launched(16, 8192, 28672)[0] == 1
@@ -728,3 +766,41 @@ def test_dispatch_choices_on_the_70b_layers():
     assert launched(1024, 8192, 28672) == (13, 256)      # 128 tiles, two runs each
     kernel, splits = launched(128, 8192, 8192)
     assert kernel == 8 and splits > 1                     # 128x128 tiles with K splits
+
+
+def test_soak_of_the_hand_offs():
+    """The three paths whose workgroups hand partial sums to one another through the
+    workspace (K splits of the streaming kernel, K splits of the 128x128 tiles, the cut tail
+    of the persistent 256x256 kernel): 2000 back-to-back calls each on one workspace, every
+    result compared bit for bit with the first (itself checked against the oracle), stopping
+    at the first mismatch; the counters end at zero."""
+    paths = [("streaming kernel, 4 K splits", 9, 2048, 192, dict(which=1, split_k=4, waves=8)),
+             ("128x128 tiles, 3 K splits", 130, 1536, 288, dict(which=2, split_k=3, gemm_cfg=8)),
+             ("256x256 tiles, tail cut along K", 300, 1152, 544, dict(which=2, split_k=1, gemm_cfg=13))]
+    for name, M, K, N, force in paths:
+        say(f"soak: {name}: M={M} K={K} N={N}")
+        w = synth.weights(N, K, 0.02, seed=91)
+        x = synth.activations(M, K, seed=92, outlier_frac=0.02)
+        ref = oracle.linear(x, w, 8)
+        packed, _, _ = prepare(w)
+        xq, sx = fq.quant_act(to_dev(x), 8)
+        ws = fq.make_workspace(M, N, K, extra=force["split_k"] * M * N * 4)
+        y = torch.empty((M, N), dtype=torch.float16, device=DEV)
+        dev.set_dispatch(**force)
+        try:
+            _, acc = dev.gemm_w6a8(packed, N, K, 0, xq=xq, sx=sx, want_acc=True, workspace=ws)
+            first = dev.gemm_w6a8(packed, N, K, 0, xq=xq, sx=sx, workspace=ws)
+            torch.cuda.synchronize()
+            launched = dev.last_dispatch()
+            assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
+            assert_y_close(first.cpu().numpy().view(np.float16), ref["y"])
+            differs = torch.zeros(1, dtype=torch.int32, device=DEV)
+            for rep in range(2000):
+                dev.gemm_w6a8(packed, N, K, 0, xq=xq, sx=sx, workspace=ws, out=y)
+                differs += (y != first).any()
+                if rep % 100 == 99:
+                    assert int(differs.item()) == 0, (name, "a call among", rep - 99, "..", rep, "differs")
+        finally:
+            dev.set_dispatch(0, 0, 0, 0)
+        assert launched[0] == (1 if force["which"] == 1 else force["gemm_cfg"]) and launched[1] > 1, launched
+        assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0

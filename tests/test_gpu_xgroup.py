@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import paper_2508_04405_amd as fq
-from paper_2508_04405_amd import synth
+from paper_2508_04405_amd import dev, synth
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -47,25 +47,42 @@ def test_quant_act_g128_bit_exact(M, K, bits):
     assert np.array_equal(xq.cpu().numpy(), rq)
 
 
+def summation_slack(acc_g, sxg, sw):
+    """Eq. 7 summed in fp32 in the kernel's own order.  Every rounding is at most 2^-24 of
+    a partial sum, itself at most T = sum_g |sx_g sw_g acc_g|.  The kernels make: one
+    rounding per term (its product, or the fused multiply-add that adds it), one more per
+    term where both scales multiply it separately, at most G - 1 further additions when
+    the wavefronts' and K splits' partial sums are combined (an empty partial adds
+    exactly), and one for the token scale applied at the end: fewer than
+    (2 G + 4) 2^-24 T = (G + 2) 2^-23 T in all, which is the slack returned."""
+    terms = np.abs(acc_g.astype(np.float64) * sw.astype(np.float64)[None, :, :] *
+                   sxg.astype(np.float64)[:, None, :])
+    return terms.sum(2) * (terms.shape[2] + 2) * 2.0**-23
+
+
 def reference(x16, w, bits):
     wq, sw = oracle.quantize(w, 6, 128)
     xq, sxg = oracle.quantize(x16.astype(np.float32), bits, 128)
     acc_g = oracle.matmul(xq, wq, 128)                               # [M, N, G]
     y = oracle.dequant_xgroup(acc_g, sxg, sw)
-    terms = np.abs(acc_g.astype(np.float64) * sw.astype(np.float64)[None, :, :] *
-                   sxg.astype(np.float64)[:, None, :])
-    G = terms.shape[2]
-    # fp32: each term is rounded twice before it is added, the sum G times
-    slack = terms.sum(2) * (G + 2) * 2.0**-23
-    return xq, sxg, y, slack
+    return xq, sxg, y, summation_slack(acc_g, sxg, sw)
 
 
-def assert_close(got, want, slack):
+def assert_close(got, want, slack, what=""):
+    """Within one fp16 ulp, or within one ulp plus the fp32 summation bound `slack`.  The
+    bound is a worst case: with rounding errors of random sign the fp32 sum is off by about
+    sqrt(G) 2^-25 of a typical term, which moves a result past a second fp16 boundary only
+    where the terms cancel almost completely.  So besides the bound itself, at most one
+    output in a thousand (two outputs, for small cases) may need it, and the worst distance
+    is printed."""
     d = np.abs(ordered(got) - ordered(want))
     err = np.abs(got.astype(np.float64) - want.astype(np.float64))
     ulp = np.abs(want.astype(np.float64)) * 2.0**-10 + 2.0**-24
     bad = (d > 1) & (err > ulp + slack)
+    beyond = int((d > 1).sum())
+    print(f"    {what} outputs {d.size}, beyond 1 ulp: {beyond}, worst distance {int(d.max())} ulp", flush=True)
     assert not bad.any(), (int(bad.sum()), got[bad][:5], want[bad][:5])
+    assert beyond <= max(2, d.size // 1000), (beyond, d.size)
 
 
 CASES = [(1, 256, 128), (4, 1280, 160), (8, 4096, 64), (32, 1024, 320), (33, 640, 96),
@@ -77,12 +94,12 @@ CASES = [(1, 256, 128), (4, 1280, 160), (8, 4096, 64), (32, 1024, 320), (33, 640
 @pytest.mark.parametrize("M,K,N", CASES)
 def test_linear_g128(M, K, N, bits, kernel):
     say(f"linear_g128 M={M} K={K} N={N} A{bits} {kernel}")
-    fq.set_dispatch({"auto": 0, "stream": 1, "tiled": 2}[kernel], 0, 0, 0)
+    dev.set_dispatch({"auto": 0, "stream": 1, "tiled": 2}[kernel], 0, 0, 0)
     try:
         run_linear_g128(M, K, N, bits)
         torch.cuda.synchronize()
     finally:
-        fq.set_dispatch(0, 0, 0, 0)
+        dev.set_dispatch(0, 0, 0, 0)
 
 
 def run_linear_g128(M, K, N, bits):
@@ -93,18 +110,21 @@ def run_linear_g128(M, K, N, bits):
     xq, sxg = fq.quant_act_g128(to_dev(x), bits)
     assert np.array_equal(xq.cpu().numpy(), rq)
     assert np.array_equal(sxg.cpu().numpy().view(np.uint16)[:, :M], rsg.view(np.uint16).T)
-    y = fq.linear_g128(packed, N, K, xq, sxg)
-    assert_close(y.cpu().numpy(), ry, slack)
-    # scales that are constant along K must reproduce the per-token entry point
+    y = dev.linear_g128(packed, N, K, xq, sxg)
+    assert_close(y.cpu().numpy(), ry, slack, "group scales:")
+    # scales that are constant along K must reproduce the per-token entry point: both
+    # against the oracle on those flat scales, with the summation bound of THOSE terms
     sx = sxg[0, :M].contiguous()
     flat = sxg[0][None, :].expand(K // 128, sxg.shape[1]).contiguous()
-    y_tok = fq.gemv_w6a8(packed, N, K, 128, xq=xq, sx=sx)
-    y_grp = fq.linear_g128(packed, N, K, xq, flat)
-    # (fp32 sums in different orders: the same bound as against the oracle)
-    ref_flat = oracle.dequant_xgroup(oracle.matmul(rq, oracle.quantize(w, 6, 128)[0], 128),
-                                     np.repeat(rsg[:, :1], K // 128, 1), oracle.quantize(w, 6, 128)[1])
-    assert_close(y_grp.cpu().numpy(), ref_flat, slack * 4 + np.abs(ref_flat.astype(np.float64)) * 2.0**-9)
-    assert_close(y_tok.cpu().numpy(), ref_flat, slack * 4 + np.abs(ref_flat.astype(np.float64)) * 2.0**-9)
+    y_tok = dev.gemv_w6a8(packed, N, K, 128, xq=xq, sx=sx)
+    y_grp = dev.linear_g128(packed, N, K, xq, flat)
+    wq_ref, sw_ref = oracle.quantize(w, 6, 128)
+    acc_g = oracle.matmul(rq, wq_ref, 128)
+    sx_flat = np.repeat(rsg[:, :1], K // 128, 1)
+    ref_flat = oracle.dequant_xgroup(acc_g, sx_flat, sw_ref)
+    slack_flat = summation_slack(acc_g, sx_flat, sw_ref)
+    assert_close(y_grp.cpu().numpy(), ref_flat, slack_flat, "flat scales, group entry:")
+    assert_close(y_tok.cpu().numpy(), ref_flat, slack_flat, "flat scales, token entry:")
 
 
 @pytest.mark.parametrize("split,waves", [(2, 4), (3, 8), (5, 16)])
@@ -116,13 +136,13 @@ def test_linear_g128_k_splits(split, waves):
     _, _, ry, slack = reference(x, w, 8)
     packed = fq.pack_w6(*fq.quant_w6(to_dev(w), 128), 128)
     xq, sxg = fq.quant_act_g128(to_dev(x), 8)
-    fq.set_dispatch(1, split, waves, 0)
+    dev.set_dispatch(1, split, waves, 0)
     try:
-        y = fq.linear_g128(packed, N, K, xq, sxg,
-                           workspace=fq.make_workspace(M, N, K, DEV, extra=split * M * N * 4))
+        y = dev.linear_g128(packed, N, K, xq, sxg,
+                            workspace=fq.make_workspace(M, N, K, DEV, extra=split * M * N * 4))
         torch.cuda.synchronize()
     finally:
-        fq.set_dispatch(0, 0, 0, 0)
+        dev.set_dispatch(0, 0, 0, 0)
     assert_close(y.cpu().numpy(), ry, slack)
 
 
@@ -136,13 +156,13 @@ def test_linear_g128_tiled_k_splits(split, M):
     _, _, ry, slack = reference(x, w, 6)
     packed = fq.pack_w6(*fq.quant_w6(to_dev(w), 128), 128)
     xq, sxg = fq.quant_act_g128(to_dev(x), 6)
-    fq.set_dispatch(2, split, 0, 0)
+    dev.set_dispatch(2, split, 0, 0)
     try:
-        y = fq.linear_g128(packed, N, K, xq, sxg,
-                           workspace=fq.make_workspace(M, N, K, DEV, extra=split * M * N * 4))
+        y = dev.linear_g128(packed, N, K, xq, sxg,
+                            workspace=fq.make_workspace(M, N, K, DEV, extra=split * M * N * 4))
         torch.cuda.synchronize()
     finally:
-        fq.set_dispatch(0, 0, 0, 0)
+        dev.set_dispatch(0, 0, 0, 0)
     assert_close(y.cpu().numpy(), ry, slack)
 
 

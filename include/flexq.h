@@ -232,6 +232,30 @@ flexq_status flexq_linear_g128(const void *packed, const int8_t *xq,
                                int N, int K, uint16_t *y, void *workspace,
                                size_t workspace_bytes, void *stream);
 
+/*
+ * For callers that cannot allocate device memory -- code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc: flexq_gemv_w6a8 (same
+ * arguments, same results, same status codes) without the workspace arguments.
+ * The K-split counters, the partial sums and the quantize prologue's codes live in
+ * a fixed array of FLEXQ_NOALLOC_SCRATCH_BYTES inside the library's device image
+ * instead (one copy per GPU, held until the process ends).  The call allocates and
+ * frees nothing and only enqueues kernels on `stream`: a small fill kernel that
+ * zeroes the counter area, then what flexq_gemv_w6a8 would enqueue.  The first
+ * call on a device looks up the array's address (once per device) and is best made
+ * outside a capture.
+ *   - FLEXQ_EWORKSPACE if flexq_workspace_bytes(M, N, K) exceeds
+ *     FLEXQ_NOALLOC_SCRATCH_BYTES (decode shapes fit: the LLaMA-2-70B layers up to
+ *     64 tokens need under 10 MiB); nothing is launched then.
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap on one
+ *     GPU (different streams, no ordering between them) race, and must use
+ *     flexq_gemv_w6a8 with workspaces of their own instead.
+ */
+#define FLEXQ_NOALLOC_SCRATCH_BYTES (16u << 20)
+flexq_status flexq_gemv_w6a8_noalloc(const void *packed, int group, const int8_t *xq,
+                                     const uint16_t *sx, const uint16_t *x_fp16, int M,
+                                     int N, int K, uint16_t *y, int32_t *acc_out,
+                                     void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,8 @@ def load():
         fn = getattr(lib, name)
         fn.restype = c_int
         fn.argtypes = [vp, c_int, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp, c_size, vp]
+    lib.flexq_gemv_w6a8_noalloc.restype = c_int
+    lib.flexq_gemv_w6a8_noalloc.argtypes = [vp, c_int, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -263,3 +265,21 @@ def gemv_w6a8(packed, N, K, group=0, xq=None, sx=None, x_fp16=None, workspace=No
               want_acc=False, out=None):
     return _linear("flexq_gemv_w6a8", packed, N, K, group, xq, sx, x_fp16, workspace, want_acc, out)
 
+
+def gemv_w6a8_noalloc(packed, N, K, group=0, xq=None, sx=None, x_fp16=None, want_acc=False, out=None):
+    """flexq_gemv_w6a8 on the library's own fixed scratch array: no workspace argument,
+    nothing allocated by the call itself (the outputs here are made by torch unless given)."""
+    lib = load()
+    _dev(packed, torch.uint8)
+    if x_fp16 is not None:
+        _dev(x_fp16, torch.float16)
+        M, dev = x_fp16.shape[0], x_fp16.device
+    else:
+        _dev(xq, torch.int8)
+        _dev(sx, torch.float16)
+        M, dev = xq.shape[0], xq.device
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=dev)
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    _check(lib.flexq_gemv_w6a8_noalloc(_ptr(packed), group, _ptr(xq), _ptr(sx), _ptr(x_fp16), M, N, K,
+                                       _ptr(y), _ptr(acc), _stream()))
+    return (y, acc) if want_acc else y

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
     lib = fq.load()
     names = _declared("flexq.h")
     assert {"flexq_pack_w6", "flexq_quant_act", "flexq_gemm_w6a6", "flexq_gemm_w6a8",
-            "flexq_gemv_w6a8"} <= set(names)
+            "flexq_gemv_w6a8", "flexq_gemv_w6a8_noalloc"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     dlib = dev.load()
@@ -160,6 +160,33 @@ def test_other_entry_points_argument_errors():
     assert lib.flexq_workspace_init(None, 1 << 20, None) == -1
     assert lib.flexq_workspace_init(P16, 16, None) == -5
     assert b"shape" in lib.flexq_status_string(-2)
+
+
+def test_noalloc_entry_point_argument_errors():
+    """The entry point without a workspace checks like flexq_gemv_w6a8, before it touches
+    the GPU, and refuses shapes whose workspace would not fit its fixed array."""
+    lib = fq.load()
+    f = lib.flexq_gemv_w6a8_noalloc
+    ok = dict(packed=P16, group=0, xq=P16, sx=P16, x=None, M=4, N=128, K=256, y=P16, acc=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["packed"], a["group"], a["xq"], a["sx"], a["x"], a["M"], a["N"], a["K"], a["y"],
+                 a["acc"], None)
+
+    assert call(packed=None) == -1
+    assert call(y=None) == -1
+    assert call(xq=None) == -1
+    assert call(M=0) == -1
+    assert call(group=64) == -1
+    assert call(N=100) == -2
+    assert call(K=200) == -2
+    assert call(y=ODD) == -3
+    limit = 16 << 20
+    assert lib.flexq_workspace_bytes(64, 8192, 28672) <= limit      # every 70B layer at 64 tokens
+    assert lib.flexq_workspace_bytes(64, 57344, 8192) <= limit
+    assert lib.flexq_workspace_bytes(1024, 8192, 8192) > limit
+    assert call(M=1024, N=8192, K=8192) == -5
 
 
 def test_dev_entry_points_argument_errors():

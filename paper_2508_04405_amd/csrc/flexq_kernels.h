@@ -90,20 +90,26 @@ bool skinny_can_fuse(int M, int K, int split_k);
 // 256x256 form, the number of runs its tail was cut into.
 hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen = nullptr,
                        int *tail_runs = nullptr);
-// 256x256 tiles with both operands through LDS: per-channel scales, no K split.
-// tail_wgs = 0: one workgroup per tile.  tail_wgs > 0: persistent form of 256 workgroups;
-// the tiles beyond the last whole round of 256 are cut along K into tail_wgs equal runs
-// of 128-k stages, whose partial sums meet in the partial-sum area (it must hold
-// streamk_plan().partial_bytes; with less, the call falls back to one workgroup per tile).
+// 256-row tiles with both operands through LDS: per-channel scales, no K split.  The
+// tiles beyond the last whole round of 256 ("the tail") run in one of three forms:
+// tail_form 0: as whole 256x256 tiles; 1: as twice as many 256x128 tiles; 2: cut along K
+// into tail_wgs equal runs of 128-k stages, whose partial sums meet in the partial-sum
+// area (it must hold streamk_plan().partial_bytes; with less, and on a device that is not
+// 256 CUs wide, form 0 runs instead).  Every launch is persistent: at most one workgroup
+// per CU.
 constexpr int kStreamKGrid = 256;   // workgroups of the persistent form: one per CU of an MI355X
 struct StreamKPlan {
     int tiles, full_tiles, tail_tiles;   // 256x256 tiles: all, those in whole rounds, the rest
     size_t partial_bytes;                // workspace for the partial sums of the rest
 };
 StreamKPlan streamk_plan(int M, int N, int K);
-// Estimated time (microseconds) of the better of the two forms (of the first, if the tail
-// may not be cut), and that form's tail_wgs.
-double gemm_wlds_estimate_us(int M, int N, int K, bool may_cut, int *tail_wgs);
-hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_wgs, hipStream_t st);
+// The launch form estimated to be fastest (tail never cut if !may_cut), its estimated time
+// in microseconds, and, for a cut tail, the number of runs (for half tiles: their number).
+struct WldsChoice {
+    double us;
+    int tail_form, tail_wgs;
+};
+WldsChoice gemm_wlds_choose(int M, int N, int K, bool may_cut);
+hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_form, int tail_wgs, hipStream_t st);
 
 }  // namespace flexq

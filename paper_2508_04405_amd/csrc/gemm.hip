@@ -644,32 +644,33 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
             t_best = t8 < t7 ? t8 : t7;
         }
         if (a.M > 128) {
-            int tail_wgs = 0;
             const bool may_cut = a.partial_bytes >= streamk_plan(a.M, a.N, a.K).partial_bytes &&
                                  device_cu_count() == kStreamKGrid;
-            double t = gemm_wlds_estimate_us(a.M, a.N, a.K, may_cut, &tail_wgs);
+            WldsChoice c = gemm_wlds_choose(a.M, a.N, a.K, may_cut);
             // a cut tail must promise 5 % (it adds workspace traffic the estimate is unsure
-            // of); else the tiles run whole, if that is the fastest
-            if (tail_wgs > 0 && t >= 0.95 * t_best)
-                t = gemm_wlds_estimate_us(a.M, a.N, a.K, false, &tail_wgs);
-            if (t < t_best) {
+            // of); else the best form that leaves the workspace alone
+            if (c.tail_form == 2 && c.us >= 0.95 * t_best) c = gemm_wlds_choose(a.M, a.N, a.K, false);
+            if (c.us < t_best) {
                 LinearArgs b = a;
                 b.split_k = 1;
-                *chosen = tail_wgs > 0 ? 13 : 12;
-                *tail_runs = tail_wgs;
-                return launch_gemm_wlds(b, tail_wgs, st);
+                *chosen = 12 + (c.tail_form == 2 ? 1 : c.tail_form == 1 ? 2 : 0);
+                *tail_runs = c.tail_wgs;
+                return launch_gemm_wlds(b, c.tail_form, c.tail_wgs, st);
             }
         }
     }
     *chosen = cfg;
-    if (cfg == 12 && a.split_k == 1) return launch_gemm_wlds(a, 0, st);
+    if (cfg == 12 && a.split_k == 1) return launch_gemm_wlds(a, 0, 0, st);
     if (cfg == 13 && a.split_k == 1) {
-        int tail_wgs = 0;
-        gemm_wlds_estimate_us(a.M, a.N, a.K, true, &tail_wgs);
-        // forced: cut the tail also where whole tiles are estimated to be faster
-        if (tail_wgs == 0) tail_wgs = kStreamKGrid;
+        // forced: cut the tail also where another form is estimated to be faster
+        const WldsChoice c = gemm_wlds_choose(a.M, a.N, a.K, true);
+        const int tail_wgs = c.tail_form == 2 ? c.tail_wgs : kStreamKGrid;
         *tail_runs = tail_wgs;
-        return launch_gemm_wlds(a, tail_wgs, st);
+        return launch_gemm_wlds(a, 2, tail_wgs, st);
+    }
+    if (cfg == 14 && a.split_k == 1) {
+        *tail_runs = 2 * streamk_plan(a.M, a.N, a.K).tail_tiles;
+        return launch_gemm_wlds(a, 1, 0, st);
     }
     switch (cfg) {
 #ifdef FLEXQ_DEV   // shapes the dispatch never picks: kept selectable for comparisons

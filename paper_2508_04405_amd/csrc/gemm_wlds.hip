@@ -1,36 +1,46 @@
-// Tiled i8-MFMA GEMM, 256x256 tile, BOTH operands through LDS.
+// Tiled i8-MFMA GEMM with BOTH operands through LDS: 256x256 tiles, or 256x128.
 //
 // The 128x256 kernel is limited by power, and what costs power besides the
 // MFMAs is every byte a wavefront brings in through the vector-memory path:
 // timing probes put the packed-weight loads at about a fifth of its run time
 // and the activation DMA at a tenth, while doubling the LDS operand reads
 // costs 3 %.  This kernel therefore trades vector-memory bytes for LDS reads:
-// one workgroup of eight wavefronts (2 along m x 4 along n, 128x64 each) owns a
-// 256x256 tile, and a packed weight tile is brought into LDS ONCE per
-// workgroup (by DMA, like the activations) and read from there by the two
+// one workgroup of eight wavefronts (2 along m x 4 along n, 128 x 32 NT each)
+// owns a 256 x (128 NT) tile, and a packed weight tile is brought into LDS ONCE
+// per workgroup (by DMA, like the activations) and read from there by the two
 // wavefronts that share its columns: 0.875 KB through the vector-memory path
-// per 32x32x128 block instead of 1.25.
+// per 32x32x128 block at NT = 2 instead of 1.25.
 //
 //   LDS: three activation stages of 32 KiB (two stages ahead) and two weight
-//   stages of 24 KiB (one stage ahead: a weight stage is consumed -- copied to
-//   registers -- right at the start of its stage, so its buffer is free for the
-//   stage after next as soon as every wavefront has passed the next barrier);
-//   144 KiB, one workgroup per CU, two wavefronts per SIMD.
-//   Per stage and wavefront: 3 weight DMA loads, then 4 activation DMA loads;
+//   stages of 12 NT KiB (one stage ahead: a weight stage is consumed -- copied
+//   to registers -- right at the start of its stage, so its buffer is free for
+//   the stage after next as soon as every wavefront has passed the next
+//   barrier); one workgroup per CU, two wavefronts per SIMD.
+//   Per stage and wavefront: its weight DMA loads, then 4 activation DMA loads;
 //   the hand-over waits until at most the 4 youngest are outstanding.
 //
-// Per-channel scales only: this is the kernel for large M and N.  Inner loop and
-// epilogue follow the 128x256 kernel.
+// Per-channel scales only: this is the kernel for large M and N.
 //
-// Two launch forms.  One workgroup per tile, when the tiles come in whole rounds
-// of the 256 CUs.  Otherwise a persistent form (SK) of 256 workgroups: each takes
-// its share of the whole rounds tile by tile, and the tiles of the last, partial
-// round are cut along K into equal contiguous runs of 128-k stages, one run per
-// workgroup, so that every CU is busy to the end.  A run that is not a whole tile
+// A launch is PERSISTENT: at most one workgroup per CU, each taking its items
+// (tiles) one after the other, and the operands of the next item's first stages
+// are already on their way into LDS while the finished tile is scaled and
+// stored, so neither the first loads' latency nor the store burst stands
+// between two tiles' MFMAs.  The wavefronts accumulate D^T (channels down the
+// registers, one token per lane): a lane's four consecutive registers are four
+// consecutive channels of one token, so the epilogue scales and converts in
+// registers and sends 8-byte pieces of finished fp16 through a small LDS
+// transpose, from which whole 128-byte lines are stored (Section 4.3.2's
+// coalesced write-back, Section 4.3.4's fused dequantization).
+//
+// Three launch forms.  Whole tiles (NT = 2).  Half tiles, 256x128 (NT = 1): the
+// tiles left over after the last whole round of 256, as twice as many items of
+// half the work, so a round of up to 128 leftover tiles costs half a round.
+// And the cut tail (SK): the leftover tiles cut along K into equal contiguous
+// runs of 128-k stages, one run per workgroup; a run that is not a whole tile
 // leaves its int32 sums in the workspace (exact, so the order of addition does
-// not matter); the workgroups of a tile add their stage counts to the tile's
-// counter, and the one that completes the count adds the others' sums to its own
-// registers and runs the epilogue.  Nobody waits for anybody.
+// not matter), the workgroups of a tile add their stage counts to the tile's
+// counter, and the one that completes the count adds the others' sums to its
+// own registers and runs the epilogue.  Nobody waits for anybody.
 #include "flexq_device.h"
 #include "flexq_kernels.h"
 #include "gemm_common.h"
@@ -38,128 +48,188 @@
 
 namespace {
 
-constexpr int BM = 256, BN = 256, WAVES = 8, MT = 4, NT = 2;
+constexpr int BM = 256, WAVES = 8;
 constexpr int XSTAGE = BM * 128;               // bytes of one activation stage
-constexpr int WSTAGE = (BN / 32) * FLEXQ_TILE_BYTES;
-constexpr int WBASE = 3 * XSTAGE;
-constexpr int LDS_BYTES = WBASE + 2 * WSTAGE;
 constexpr int XDMA = BM / 8 / WAVES;           // 1 KiB activation DMA loads per wavefront and stage
-constexpr int WDMA = 3;                        // each wavefront fetches one weight tile (3 planes)
-static_assert(BN / 32 == WAVES, "one weight tile per wavefront");
+constexpr int SLOT_BYTES = BM * 256 * 4;       // one workgroup's int32 sums of a 256x256 tile
 
-constexpr int SLOT_BYTES = BM * BN * 4;         // one workgroup's int32 sums of a tile
+// The eight wavefronts share a tile 2 along m (MT = 4 row blocks of 32 each) x 4 along n
+// (NT column blocks of 32 each): NT = 2 is the whole 256x256 tile, NT = 1 the half tile.
+// (A layout of 1 x 8 wavefronts owning 256 x 32 each halves the expansion work per MFMA,
+// an expanded operand then feeding eight of them, for twice the activation reads from
+// LDS: measured 2-5 % slower on every layer.)
+template <int NT>
+struct Shape {
+    static constexpr int WN = 4;
+    static constexpr int MT = 4;
+    static constexpr int BN = WN * NT * 32;
+    static_assert(BN == 256 || BN == 128, "whole or half tiles");
+    static constexpr int WTILES = BN / 32;                        // packed tiles per stage
+    static constexpr int WSTAGE = WTILES * FLEXQ_TILE_BYTES;
+    static constexpr int WBASE = 3 * XSTAGE;
+    // Epilogue staging, 32 rows of fp16 per wavefront: it begins where the SECOND weight
+    // stage does.  While a tile is stored, the next item's first stages are landing in the
+    // activation stages 0 and 1 and in weight stage 0; weight stage 1 and what lies beyond
+    // it are free until the next item's stage 0 asks for its successor's weights, after
+    // the barrier that ends the epilogue.
+    static constexpr int STG = WBASE + WSTAGE;
+    static constexpr int ESTRIDE = NT * 64 + 16;
+    static constexpr int STG_END = STG + WAVES * 32 * ESTRIDE;
+    static constexpr int LDS_BYTES = STG_END > WBASE + 2 * WSTAGE ? STG_END : WBASE + 2 * WSTAGE;
+    static_assert(LDS_BYTES + 1024 <= 160 * 1024, "LDS of one CU (plus the static part)");
+};
 
-template <bool SK>
-__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_tiles, int tail_tiles,
-                      int tail_wgs)
+// One item of a workgroup's list: stages [ks, ke) of the 256-wide tile `t256`
+// (its half `half` when the items are half tiles); `tj` numbers the tile within a cut tail.
+struct Item {
+    int t256, half, ks, ke, tj;
+};
+
+// One phase of a launch: this workgroup's share of `item_count` items that begin at the
+// 256-wide tile `item_begin` -- whole tiles (NT = 2), half tiles (NT = 1: two items per
+// tile), or, with SK, the stages of `item_count` tiles cut into `tail_wgs` runs.
+template <int NT, bool SK>
+__device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *lds, int &s_last, int tiles_m,
+                                          int tiles_n, int item_begin, int item_count, int tail_wgs)
 {
 #if defined(__HIP_DEVICE_COMPILE__)  // buffer-resource builtins exist in the device pass only
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
-    __shared__ int s_last;
+    using S = Shape<NT>;
+    constexpr int MT = S::MT;
+    constexpr bool WHOLE = S::BN == 256;
+    static_assert(!SK || WHOLE, "the tail is cut in whole-width tiles");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave / S::WN, wn = wave % S::WN;
     const int M = a.M, N = a.N, K = a.K;
     const int KT = K / FLEXQ_TILE_K;
-    const int nblk = tiles_m * tiles_n;
 
-    // SK: workgroups 8 apart share an XCD; v numbers them XCD by XCD, so that the
-    // workgroups of one XCD work on neighbouring tiles (and neighbouring runs of the tail)
+    // Workgroups 8 apart share an XCD.  Every XCD takes a contiguous share of the items
+    // (or of the tail's runs), so the workgroups of one XCD work on neighbouring tiles
+    // and find each other's operand panels in their L2.
     const int G = (int)gridDim.x;
-    const int v = SK ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : 0;
-    const int rounds = SK ? full_tiles / G : 0;
-    const long U = (long)tail_tiles * KT;           // 128-k stages of the tail
-    // the tail's runs are numbered so that every XCD takes a contiguous share of them,
-    // also when there are fewer runs than workgroups
+    const int xcd = (int)(blockIdx.x % 8), slot = (int)(blockIdx.x / 8);
+    int j_next = 0, j_end = 0;                      // !SK: this workgroup's items j_next, j_next + G/8, ...
+    long u0 = 0, u1 = 0;                            // SK: this workgroup's run of stages
     int vt = -1;
-    if (SK) {
-        const int x = (int)(blockIdx.x % 8), slot = (int)(blockIdx.x / 8);
+    const long U = (long)item_count * KT;           // SK: 128-k stages of the tail
+    if (!SK) {
+        j_next = (int)((long)xcd * item_count / 8) + slot;
+        j_end = (int)((long)(xcd + 1) * item_count / 8);
+    } else {
         const int per = tail_wgs / 8, rem = tail_wgs % 8;
-        if (slot < per + (x < rem ? 1 : 0)) vt = x * per + min(x, rem) + slot;
-    }
-    long u0 = 0, u1 = 0;                            // this workgroup's run of stages
-    if (vt >= 0) {
-        u0 = (long)vt * U / tail_wgs;
-        u1 = (long)(vt + 1) * U / tail_wgs;
+        if (slot < per + (xcd < rem ? 1 : 0)) vt = xcd * per + min(xcd, rem) + slot;
+        if (vt >= 0) {
+            u0 = (long)vt * U / tail_wgs;
+            u1 = (long)(vt + 1) * U / tail_wgs;
+        }
     }
     const long run_begin = u0;
+    // the next item of this workgroup, if any (all values wavefront-uniform)
+    auto take = [&](Item &it) -> bool {
+        if (!SK) {
+            if (j_next >= j_end) return false;
+            const int j = j_next;
+            j_next += G / 8;
+            it.t256 = item_begin + (WHOLE ? j : j >> 1);
+            it.half = WHOLE ? 0 : (j & 1);
+            it.ks = 0;
+            it.ke = KT;
+            it.tj = 0;
+            return true;
+        } else {
+            if (u0 >= u1) return false;
+            it.tj = (int)(u0 / KT);
+            it.ks = (int)(u0 - (long)it.tj * KT);
+            it.ke = (int)min((long)KT, it.ks + (u1 - u0));
+            it.t256 = item_begin + it.tj;
+            it.half = 0;
+            u0 += it.ke - it.ks;
+            return true;
+        }
+    };
 
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)a.xq, 0, (unsigned)((long)M * K), 0x00020000);
     const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)a.packed, 0, (unsigned)((long)N * K / 4 * 3), 0x00020000);
 
-    for (int it = 0;; ++it) {
-        // ---- which tile, which stages [ks, ke) of it ---------------------------
-        int bid, ks = 0, ke = KT, tj = 0;
-        if (!SK) {
-            if (it) break;
-            // XCD-aware tile choice: blocks 8 apart share an XCD
-            bid = blockIdx.x;
-            const int per = nblk / 8, rem = nblk % 8;
-            const int xcd = bid % 8, slot = bid / 8;
-            bid = xcd * per + (xcd < rem ? xcd : rem) + slot;
-        } else if (it < rounds) {
-            bid = (v / (G / 8)) * (full_tiles / 8) + it * (G / 8) + v % (G / 8);
-        } else {
-            if (u0 >= u1) break;
-            tj = (int)(u0 / KT);
-            ks = (int)(u0 - (long)tj * KT);
-            ke = (int)min((long)KT, ks + (u1 - u0));
-            bid = full_tiles + tj;
-            u0 += ke - ks;
-        }
-        const int KN = ke - ks;
-        // The 32 tiles an XCD works on at a time share operand panels in its L2: a block of
-        // 4 tiles along m x 8 along n fetches the fewest bytes (4 activation panels of 2 MB
-        // per 8192 of K + 8 weight panels of 1.5 MB).
+    // ---- where an item's operands are, and the DMA loads of one stage -----------
+    // The 32 tiles an XCD works on at a time share operand panels in its L2: a block of
+    // 4 tiles along m x 8 along n fetches the fewest bytes (4 activation panels of 2 MB
+    // per 8192 of K + 8 weight panels of 1.5 MB).
+    struct Where {
+        int bm0, bn0;
+        unsigned xoff[XDMA];
+    };
+    auto locate = [&](const Item &it, Where &w) {
         constexpr int SUP_M = 4;  // super-block: 4 tiles along m, then next n
+        const int bid = it.t256;
         const int sup = bid / (SUP_M * tiles_n);
         const int first_m = sup * SUP_M;
         const int span_m = min(SUP_M, tiles_m - first_m);
         const int in_sup = bid - sup * SUP_M * tiles_n;
-        const int tile_m = first_m + in_sup % span_m;
-        const int tile_n = in_sup / span_m;
-        const int bm0 = tile_m * BM, bn0 = tile_n * BN;
-
-        // ---- activations: global -> LDS by DMA; rows beyond M read as zero -----
-        // (stage numbers below count from ks)
-        unsigned xoff[XDMA];
+        w.bm0 = (first_m + in_sup % span_m) * BM;
+        w.bn0 = (in_sup / span_m) * 256 + it.half * S::BN;
 #pragma unroll
         for (int i = 0; i < XDMA; ++i) {
             const int q = wave * XDMA + i;
             const int row = 8 * q + (lane >> 3);
             const int c = (lane & 7) ^ ((row >> 1) & 7);
-            xoff[i] = (unsigned)(bm0 + row) * (unsigned)K + 16u * c;
+            w.xoff[i] = (unsigned)(w.bm0 + row) * (unsigned)K + 16u * c;
         }
-        auto dma_x = [&](int kb, int buf) {
+    };
+    // activations: global -> LDS by DMA; rows beyond M read as zero (stage numbers count from ks)
+    auto dma_x = [&](const Where &w, int ks, int kb, int buf) {
 #pragma unroll
-            for (int i = 0; i < XDMA; ++i) {
-                uint8_t *dst = lds + buf * XSTAGE + (wave * XDMA + i) * 1024;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    xrsrc, (void __attribute__((address_space(3))) *)dst, 16, xoff[i],
-                    (ks + kb) * FLEXQ_TILE_K, 0, 0);
-            }
-        };
-
-        // ---- packed weights: wavefront w brings tile w of the workgroup's eight
-        // column tiles into LDS, plane by plane, exactly as it lies in memory ------
-        // the SGPR offset is not range-checked: tiles past the last row block
-        // re-read the last one and are never stored
-        const int wtile = min(bn0 / 32 + wave, N / 32 - 1);
-        const unsigned wlane = (unsigned)lane * 16u;
-        auto dma_w = [&](int kb, int buf) {
+        for (int i = 0; i < XDMA; ++i) {
+            uint8_t *dst = lds + buf * XSTAGE + (wave * XDMA + i) * 1024;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                xrsrc, (void __attribute__((address_space(3))) *)dst, 16, w.xoff[i],
+                (ks + kb) * FLEXQ_TILE_K, 0, 0);
+        }
+    };
+    // packed weights: the stage's WTILES tiles of three 1 KiB planes go into LDS exactly as
+    // they lie in memory; plane p of the stage is fetched by wavefront p % 8.  The SGPR
+    // offset is not range-checked: tiles past the last row block re-read the last one and
+    // are never stored.
+    const unsigned wlane = (unsigned)lane * 16u;
+    auto dma_w = [&](const Where &w, int ks, int kb, int buf) {
 #pragma unroll
-            for (int p = 0; p < WDMA; ++p) {
-                uint8_t *dst = lds + WBASE + buf * WSTAGE + wave * FLEXQ_TILE_BYTES + p * 1024;
+        for (int p0 = 0; p0 < 3 * S::WTILES; p0 += WAVES) {
+            const int p = p0 + wave;
+            if (p < 3 * S::WTILES) {
+                const int t = p / 3, plane = p - 3 * t;
+                const int wtile = min(w.bn0 / 32 + t, N / 32 - 1);
+                uint8_t *dst = lds + S::WBASE + buf * S::WSTAGE + p * 1024;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     wrsrc, (void __attribute__((address_space(3))) *)dst, 16, wlane,
-                    (unsigned)(wtile * KT + ks + kb) * FLEXQ_TILE_BYTES + 1024u * p, 0, 0);
+                    (unsigned)(wtile * KT + ks + kb) * FLEXQ_TILE_BYTES + 1024u * plane, 0, 0);
             }
-        };
+        }
+    };
+    // weights and activations of an item's stage 0, activations of its stage 1
+    auto issue_prologue = [&](const Item &it, const Where &w) {
+        dma_w(w, it.ks, 0, 0);
+        dma_x(w, it.ks, 0, 0);
+        if (it.ke - it.ks > 1) dma_x(w, it.ks, 1, 1);
+    };
+
+    const int arow = (wm * MT) * 32 + (lane & 31);
+    const int ahalf = lane >> 5;
+    const int wfrag = S::WBASE + (wn * NT) * FLEXQ_TILE_BYTES + lane * 16;   // this lane's piece of tile nt = 0
+
+    Item cur;
+    Where at;
+    if (!take(cur)) return;
+    locate(cur, at);
+    issue_prologue(cur, at);
+    wait_vmcnt<0>();
+    lds_barrier();
+
+    for (;;) {
+        const int ks = cur.ks, KN = cur.ke - cur.ks;
 
         v16i acc[MT][NT];
 #pragma unroll
@@ -168,17 +238,6 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_ti
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0;
-
-        // prologue: weights and activations of stage 0, activations of stage 1
-        dma_w(0, 0);
-        dma_x(0, 0);
-        if (KN > 1) dma_x(1, 1);
-        wait_vmcnt<0>();
-        lds_barrier();
-
-        const int arow = (wm * MT) * 32 + (lane & 31);
-        const int ahalf = lane >> 5;
-        const int wfrag = WBASE + (wn * NT) * FLEXQ_TILE_BYTES + lane * 16;   // this lane's piece of tile nt = 0
 
         // operands that live across stages: the stage's packed tiles, the activation
         // operands of two consecutive k-steps, the first weight operand of a stage
@@ -197,84 +256,124 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_ti
         v4i bf_first = unpack_kstep(wreg[0], 0);
 
         // One 128-k stage.  CUR = kb % 3 names the activation buffer; kb & 1 the weight buffer.
+        // The MFMA takes the WEIGHT fragment as its row operand: the accumulators hold D^T.
         auto stage = [&](int kb, auto cur_tag) {
             constexpr int CUR = decltype(cur_tag)::value;
             constexpr int NXT2 = (CUR + 2) % 3;
             const bool more1 = kb + 1 < KN, more2 = kb + 2 < KN;
             // weights first: the hand-over waits for them and for everything older,
             // while the activation loads issued after them may stay in flight
-            if (more1) dma_w(kb + 1, (kb + 1) & 1);
-            if (more2) dma_x(kb + 2, NXT2);
+            if (more1) dma_w(at, ks, kb + 1, (kb + 1) & 1);
+            if (more2) dma_x(at, ks, kb + 2, NXT2);
 
             const uint8_t *xs = lds + CUR * XSTAGE;
             const uint8_t *xn = lds + ((CUR + 1) % 3) * XSTAGE;
-            const uint8_t *wnb = lds + wfrag + ((kb + 1) & 1) * WSTAGE;
+            const uint8_t *wnb = lds + wfrag + ((kb + 1) & 1) * S::WSTAGE;
             // Flat software pipeline over the 4 * NT (k-step, column tile) steps: LDS
             // operand reads a k-step ahead, weight operands expanded one dword per MFMA in
             // the shadow of the MFMA just issued.  The two wavefronts of a SIMD belong to
             // the same workgroup and reach the stage boundary together, so nothing would
             // cover the operand fetch of a new stage: the hand-over therefore sits BEFORE
             // the last k-step.  By then this wavefront has read all it needs of stage kb
-            // (the operands of k-step 3 are in registers: activations were read during
-            // k-step 2, the weight operands expanded during steps 3 and 4), so after the
-            // barrier the packed tiles and first activation operands of stage kb + 1 are
-            // fetched from LDS while k-step 3's MFMAs run.
-            static_assert(NT == 2 && MT == 4, "the step table below is written for 4 x 2 blocks");
-            v4i bfc = bf_first, bf6, bf7;
+            // (the operands of k-step 3 are in registers), so after the barrier the packed
+            // tiles and first activation operands of stage kb + 1 are fetched from LDS
+            // while k-step 3's MFMAs run.
+            // At the hand-over stage kb + 1 (weights and activations, every wavefront's
+            // share) must have landed; the activations of stage kb + 2 may be in flight.
+            auto hand_over = [&] {
+                if (more2)
+                    wait_vmcnt<XDMA>();
+                else
+                    wait_vmcnt<0>();
+                lds_barrier();
+                if (more1) {
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const int j = s >> 1, nt = s & 1;
-                if (nt == 0) {
-                    if (j < 3) {
+                    for (int n2 = 0; n2 < NT; ++n2) {
+                        const v4i *t = reinterpret_cast<const v4i *>(wnb + n2 * FLEXQ_TILE_BYTES);
+                        wreg[n2].q0 = t[0];
+                        wreg[n2].q1 = t[64];
+                        wreg[n2].q2 = t[128];
+                    }
 #pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-                            af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
-                                xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
-                    } else {
-                        // stage kb + 1 (weights and activations, every wavefront's share) must
-                        // have landed; the activations of stage kb + 2 may be in flight
-                        if (more2)
-                            wait_vmcnt<XDMA>();
-                        else
-                            wait_vmcnt<0>();
-                        lds_barrier();
-                        if (more1) {
+                    for (int mt = 0; mt < MT; ++mt)
+                        af[0][mt] = *reinterpret_cast<const v4i *>(xn + lds_off(arow + 32 * mt, ahalf));
+                }
+            };
+            static_assert(MT == 4 && (NT == 1 || NT == 2), "the step tables below are written for 4 x NT blocks");
+            if constexpr (NT == 2) {
+                v4i bfc = bf_first, bf6, bf7;
 #pragma unroll
-                            for (int n2 = 0; n2 < NT; ++n2) {
-                                const v4i *t = reinterpret_cast<const v4i *>(wnb + n2 * FLEXQ_TILE_BYTES);
-                                wreg[n2].q0 = t[0];
-                                wreg[n2].q1 = t[64];
-                                wreg[n2].q2 = t[128];
-                            }
+                for (int s = 0; s < 8; ++s) {
+                    const int j = s >> 1, nt = s & 1;
+                    if (nt == 0) {
+                        if (j < 3) {
 #pragma unroll
                             for (int mt = 0; mt < MT; ++mt)
-                                af[0][mt] = *reinterpret_cast<const v4i *>(xn + lds_off(arow + 32 * mt, ahalf));
+                                af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
+                                    xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
+                        } else {
+                            hand_over();
                         }
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                const v4i cur = s == 6 ? bf6 : s == 7 ? bf7 : bfc;
-                v4i nxt = bfc;
+                    const v4i cur_b = s == 6 ? bf6 : s == 7 ? bf7 : bfc;
+                    v4i nxt = bfc;
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    acc[mt][nt] = mfma_i8(af[j & 1][mt], cur, acc[mt][nt]);
-                    // shadow work of this MFMA: one dword of an operand that is due later
-                    if (s < 5) nxt[mt] = unpack_kstep_dword(wreg[(s + 1) & 1], (s + 1) >> 1, mt);
-                    if (s == 3) bf6[mt] = unpack_kstep_dword(wreg[0], 3, mt);
-                    if (s == 4) bf7[mt] = unpack_kstep_dword(wreg[1], 3, mt);
-                    if (s == 7) nxt[mt] = unpack_kstep_dword(wreg[0], 0, mt);   // the next stage's first
-                    {
-                        int p0 = nxt[mt], p1 = bf6[mt], p2 = bf7[mt];
-                        asm volatile("" : "+v"(p0), "+v"(p1), "+v"(p2));   // pins the expansion here
-                        nxt[mt] = p0;
-                        bf6[mt] = p1;
-                        bf7[mt] = p2;
+                    for (int mt = 0; mt < MT; ++mt) {
+                        acc[mt][nt] = mfma_i8(cur_b, af[j & 1][mt], acc[mt][nt]);
+                        // shadow work of this MFMA: one dword of an operand that is due later
+                        if (s < 5) nxt[mt] = unpack_kstep_dword(wreg[(s + 1) & 1], (s + 1) >> 1, mt);
+                        if (s == 3) bf6[mt] = unpack_kstep_dword(wreg[0], 3, mt);
+                        if (s == 4) bf7[mt] = unpack_kstep_dword(wreg[1], 3, mt);
+                        if (s == 7) nxt[mt] = unpack_kstep_dword(wreg[0], 0, mt);   // the next stage's first
+                        {
+                            int p0 = nxt[mt], p1 = bf6[mt], p2 = bf7[mt];
+                            asm volatile("" : "+v"(p0), "+v"(p1), "+v"(p2));   // pins the expansion here
+                            nxt[mt] = p0;
+                            bf6[mt] = p1;
+                            bf7[mt] = p2;
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    bfc = nxt;
+                }
+                bf_first = bfc;
+            } else {
+                // one column tile: step s is k-step s; the operand of k-step s + 1 is expanded
+                // during step s, the next stage's first one at the end of step 3, three MFMAs
+                // after its packed tile was asked from LDS
+                v4i bfc = bf_first;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    if (s < 3) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            af[(s + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
+                                xs + lds_off(arow + 32 * mt, 2 * (s + 1) + ahalf));
+                    } else {
+                        hand_over();
                     }
                     __builtin_amdgcn_sched_barrier(0);
+                    v4i nxt = bfc;
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        acc[mt][0] = mfma_i8(bfc, af[s & 1][mt], acc[mt][0]);
+                        if (s < 3) nxt[mt] = unpack_kstep_dword(wreg[0], s + 1, mt);
+                        if (s == 3 && mt == MT - 1) nxt = unpack_kstep(wreg[0], 0);
+                        {
+                            int p0 = nxt[0], p1 = nxt[1], p2 = nxt[2], p3 = nxt[3];
+                            asm volatile("" : "+v"(p0), "+v"(p1), "+v"(p2), "+v"(p3));
+                            nxt[0] = p0;
+                            nxt[1] = p1;
+                            nxt[2] = p2;
+                            nxt[3] = p3;
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    bfc = nxt;
                 }
-                bfc = nxt;
+                bf_first = bfc;
             }
-            bf_first = bfc;
         };
 
         int kb = 0;
@@ -285,8 +384,11 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_ti
         }
         if (kb < KN) stage(kb, std::integral_constant<int, 0>{});
         if (kb + 1 < KN) stage(kb + 1, std::integral_constant<int, 1>{});
+        // (every wavefront has passed the last stage's barrier with its LDS reads done: the
+        // stage buffers are free)
 
         // ---- a run that is not a whole tile: leave the sums, or collect the others' ----
+        bool finish = true;                              // this workgroup stores the tile
         if (SK && KN != KT) {
             // [slot][wavefront][block mt, nt][quarter][lane] 16-byte pieces: every store and
             // load below is one contiguous KiB per wavefront.  Cache policy bit 4 = sc1 =
@@ -295,6 +397,7 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_ti
             const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
                 a.partial, 0, (unsigned)(2 * tail_wgs) * (unsigned)SLOT_BYTES, 0x00020000);
             const unsigned in_slot = (unsigned)(wave * (SLOT_BYTES / WAVES) + lane * 16);
+            const int tj = cur.tj;
             const long tile_begin = (long)tj * KT;
             // a run leaves at most two partial tiles: slot 2 vt for the one it begins in,
             // 2 vt + 1 for the one it ends in
@@ -341,134 +444,156 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_ti
                         __hip_atomic_store(&a.counters[tj], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
                 lds_barrier();
-                if (!__builtin_amdgcn_readfirstlane(s_last)) continue;   // scalar branch: barriers follow
+                finish = __builtin_amdgcn_readfirstlane(s_last) != 0;   // wavefront-uniform
             }
-            // the runs that meet this tile: the one holding its first stage through the one
-            // holding its last (run w is [w U / W, (w + 1) U / W))
-            const long W = tail_wgs;
-            const int va = (int)(((tile_begin + 1) * W + U - 1) / U) - 1;
-            const int vb = (int)(((tile_begin + KT) * W + U - 1) / U) - 1;
-            for (int w2 = va; w2 <= vb; ++w2) {
-                if (w2 == vt) continue;
-                const long begin2 = (long)w2 * U / W;
-                const unsigned theirs =
-                    (unsigned)(2 * w2 + (begin2 < tile_begin ? 1 : 0)) * SLOT_BYTES + in_slot;
+            if (finish) {
+                // the runs that meet this tile: the one holding its first stage through the one
+                // holding its last (run w is [w U / W, (w + 1) U / W))
+                const long W = tail_wgs;
+                const int va = (int)(((tile_begin + 1) * W + U - 1) / U) - 1;
+                const int vb = (int)(((tile_begin + KT) * W + U - 1) / U) - 1;
+                for (int w2 = va; w2 <= vb; ++w2) {
+                    if (w2 == vt) continue;
+                    const long begin2 = (long)w2 * U / W;
+                    const unsigned theirs =
+                        (unsigned)(2 * w2 + (begin2 < tile_begin ? 1 : 0)) * SLOT_BYTES + in_slot;
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    v4u got[NT * 4];
+                    for (int mt = 0; mt < MT; ++mt) {
+                        v4u got[NT * 4];
 #pragma unroll
-                    for (int i = 0; i < NT * 4; ++i)
-                        got[i] = __builtin_amdgcn_raw_buffer_load_b128(
-                            prsrc, theirs + (unsigned)((mt * NT * 4 + i) * 1024), 0, kScopeAgent);
+                        for (int i = 0; i < NT * 4; ++i)
+                            got[i] = __builtin_amdgcn_raw_buffer_load_b128(
+                                prsrc, theirs + (unsigned)((mt * NT * 4 + i) * 1024), 0, kScopeAgent);
 #pragma unroll
-                    for (int i = 0; i < NT * 4; ++i)
+                        for (int i = 0; i < NT * 4; ++i)
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) acc[mt][i >> 2][4 * (i & 3) + c] += (int)got[i][c];
+                            for (int c = 0; c < 4; ++c) acc[mt][i >> 2][4 * (i & 3) + c] += (int)got[i][c];
+                    }
                 }
             }
         }
 
-        // ---- epilogue: as in the 128x256 kernel -----------------------------------
-        // After the last barrier nobody reads the stage buffers again, so each
-        // wavefront transposes its 32-row slabs through a region of its own (row
-        // stride NT*32 + 8 dwords), then every lane owns four consecutive columns of
-        // one row, applies sx[m] * sw[n] in fp32, and the lanes of a row store whole
-        // 128-byte runs of fp16.
-        constexpr int ESTRIDE = (NT * 32 + 8) * 4;
-        static_assert(3 * XSTAGE >= WAVES * 32 * ESTRIDE, "epilogue staging must fit the stage buffers");
-        constexpr int LPR = NT * 8;
-        constexpr int RPI = 64 / LPR;
-        uint8_t *stg = lds + wave * (32 * ESTRIDE);
-        const int ecol = (lane % LPR) * 4;
-        const int erow = lane / LPR;
-        const int n_lane = bn0 + wn * NT * 32 + ecol;
-        const bool cvalid = n_lane < N;
-        float swv[4];
+        // ---- the next item's first stages set out now, before this tile is stored ----
+        Item nxt_item;
+        Where nxt_at;
+        const bool has_next = take(nxt_item);
+        if (has_next) {
+            locate(nxt_item, nxt_at);
+            issue_prologue(nxt_item, nxt_at);
+        }
+
+        // ---- epilogue --------------------------------------------------------------
+        // Register r of block (mt, nt) at lane l is token 32 mt' + (l & 31), channel
+        // 32 nt' + 8 (r / 4) + 4 (l >> 5) + r % 4: four consecutive channels per register
+        // quarter.  Scale (sx[m] * sw[n] in fp32, exact; the 1/4 of the 4x weights folded
+        // into sx, a power of two) and convert in registers, pass 8-byte pieces of fp16
+        // through this wavefront's own LDS rows (stride NT * 64 + 16 bytes), read 16-byte
+        // pieces back so that the lanes of a row hold consecutive pieces, and store whole
+        // lines.  Rows beyond M and column blocks beyond N are never stored.
+        if (finish) {
+            const int bm0 = at.bm0, bn0 = at.bn0;
+            const int ml = lane & 31, hh = lane >> 5;
+            const int n_wave = bn0 + wn * NT * 32;
+            float swf[NT][4][4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) swv[c] = h2f(a.scales[cvalid ? n_lane + c : 0]);
-        // Whole slabs (every row below M, every column below N, no int32 copy wanted) take a
-        // path without per-row branches or 64-bit address arithmetic: the output is addressed
-        // as a buffer from this wavefront's corner, a lane's offset is fixed, the row offset is
-        // an SGPR; and the accumulators are staged as they are (4x the sum), the factor 1/4
-        // folded into the weight scale (a power of two: the rounded result is identical).
-        const bool cols_whole = bn0 + (wn + 1) * NT * 32 <= N;
-        const long corner = (long)(bm0 + wm * MT * 32) * N + bn0 + wn * NT * 32;
-        const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(a.y + corner), 0, (unsigned)(((long)(MT * 32 - 1) * N + NT * 32) * 2), 0x00020000);
-        const unsigned yoff = (unsigned)((erow * N + ecol) * 2);
-        float swq[4];
+            for (int nt = 0; nt < NT; ++nt) {
+                const bool cvalid = n_wave + nt * 32 < N;                 // uniform; N is a multiple of 32
 #pragma unroll
-        for (int c = 0; c < 4; ++c) swq[c] = 0.25f * swv[c];
-        // every token scale this wavefront will need, fetched in one go: a load per row
-        // inside the store loop would wait a memory round trip each time (the compiler cannot
-        // move it above the stores, which might alias), a batch per slab once per slab
-        float sxall[MT][32 / RPI];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int i = 0; i < 32 / RPI; ++i) {
-                const int m = bm0 + (wm * MT + mt) * 32 + i * RPI + erow;
-                sxall[mt][i] = m < M ? h2f(a.sx[m]) : 0.0f;
-            }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int m_slab = bm0 + (wm * MT + mt) * 32;
-            if (m_slab >= M) break;                          // uniform: nothing below is stored
-            const bool whole = cols_whole && m_slab + 32 <= M && !a.acc_out;   // uniform
-            const float *sxv = sxall[mt];
-            if (whole) {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        *reinterpret_cast<int *>(stg + mfma_row(r, lane) * ESTRIDE +
-                                                 (nt * 32 + (lane & 31)) * 4) = acc[mt][nt][r];
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own region only: no barrier
-#pragma unroll
-                for (int i = 0; i < 32 / RPI; ++i) {
-                    const v4i q = *reinterpret_cast<const v4i *>(stg + (i * RPI + erow) * ESTRIDE + ecol * 4);
-                    uint16_t h[4];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) h[c] = f2h((float)q[c] * (sxv[i] * swq[c]));
-                    typedef unsigned v2u __attribute__((ext_vector_type(2)));
-                    v2u out2;
-                    out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
-                    out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
-                    __builtin_amdgcn_raw_buffer_store_b64(out2, yrsrc, yoff,
-                                                          (unsigned)((mt * 32 + i * RPI) * N * 2), 0);
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n_wave + nt * 32 + 8 * q + 4 * hh;
+                    const uint2 four = cvalid ? *reinterpret_cast<const uint2 *>(a.scales + n) : make_uint2(0u, 0u);
+                    swf[nt][q][0] = h2f((uint16_t)(four.x & 0xffffu));
+                    swf[nt][q][1] = h2f((uint16_t)(four.x >> 16));
+                    swf[nt][q][2] = h2f((uint16_t)(four.y & 0xffffu));
+                    swf[nt][q][3] = h2f((uint16_t)(four.y >> 16));
                 }
-            } else {
+            }
+            float sxq[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int m = bm0 + (wm * MT + mt) * 32 + ml;
+                sxq[mt] = m < M ? 0.25f * h2f(a.sx[m]) : 0.0f;
+            }
+            uint8_t *stg = lds + S::STG + wave * (32 * S::ESTRIDE);
+            constexpr int LPR = NT * 4;                 // lanes per staged row, 16 bytes (8 channels) each
+            constexpr int RPI = 64 / LPR;               // rows per read instruction
+            const int erow = lane / LPR, echunk = lane % LPR;
+            const bool ecvalid = n_wave + echunk * 8 < N;
+            // the output as a buffer from this wavefront's corner: a lane's offset is fixed,
+            // the row offset is an SGPR
+            const long corner = (long)(bm0 + wm * MT * 32) * N + n_wave;
+            const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(a.y + corner), 0, (unsigned)(((long)(MT * 32 - 1) * N + NT * 32) * 2), 0x00020000);
+            const unsigned yoff = (unsigned)((erow * N + echunk * 8) * 2);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int m_slab = bm0 + (wm * MT + mt) * 32;
+                if (m_slab >= M) break;                          // uniform: nothing below is stored
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        *reinterpret_cast<int *>(stg + mfma_row(r, lane) * ESTRIDE +
-                                                 (nt * 32 + (lane & 31)) * 4) = acc[mt][nt][r] >> 2;
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-                for (int i = 0; i < 32 / RPI; ++i) {
-                    const int row = i * RPI + erow;
-                    const v4i q = *reinterpret_cast<const v4i *>(stg + row * ESTRIDE + ecol * 4);
-                    const int m = m_slab + row;
-                    if (m < M && cvalid) {
-                        const float sxm = sxv[i];
+                    for (int q = 0; q < 4; ++q) {
                         uint16_t h[4];
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) h[c] = f2h((float)q[c] * (sxm * swv[c]));
+                        for (int c = 0; c < 4; ++c)
+                            h[c] = f2h((float)acc[mt][nt][4 * q + c] * (sxq[mt] * swf[nt][q][c]));
                         uint2 out2;
                         out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
                         out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
-                        *reinterpret_cast<uint2 *>(a.y + (long)m * N + n_lane) = out2;
-                        if (a.acc_out) *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n_lane) = q;
+                        *reinterpret_cast<uint2 *>(stg + ml * S::ESTRIDE + (nt * 32 + 8 * q + 4 * hh) * 2) = out2;
                     }
+                if (a.acc_out) {     // the exact int32 sums, straight from the registers
+                    const int m = m_slab + ml;
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int n = n_wave + nt * 32 + 8 * q + 4 * hh;
+                            if (m < M && n < N) {
+                                const v4i four = {acc[mt][nt][4 * q] >> 2, acc[mt][nt][4 * q + 1] >> 2,
+                                                  acc[mt][nt][4 * q + 2] >> 2, acc[mt][nt][4 * q + 3] >> 2};
+                                *reinterpret_cast<v4i *>(a.acc_out + (long)m * N + n) = four;
+                            }
+                        }
                 }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own region only: no barrier
+#pragma unroll
+                for (int i = 0; i < 32 / RPI; ++i) {
+                    const int row = i * RPI + erow;
+                    const v4u piece = *reinterpret_cast<const v4u *>(stg + row * S::ESTRIDE + echunk * 16);
+                    if (m_slab + row < M && ecvalid)
+                        __builtin_amdgcn_raw_buffer_store_b128(piece, yrsrc, yoff,
+                                                               (unsigned)((mt * 32 + i * RPI) * N * 2), 0);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next slab overwrites
             }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next slab overwrites
         }
-        if (!SK) break;
-        lds_barrier();   // every wavefront is done with its staging region before the next run's DMA
+        if (!has_next) break;
+        // the next item's first stages (every wavefront's share) have landed
+        wait_vmcnt<0>();
+        lds_barrier();
+        cur = nxt_item;
+        at = nxt_at;
     }
 #endif
+}
+
+// FORM 0: `full_count` whole tiles.  FORM 1: then the `tail_count` tiles that follow them as
+// 2 * tail_count half tiles.  FORM 2: then those tiles cut along K into `tail_wgs` runs.
+// One launch: a second launch for the tail would cost the first one's drain and the
+// end-of-kernel cache write-back in between (about 20 us, measured).
+template <int FORM>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_count, int tail_count,
+                      int tail_wgs)
+{
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    __shared__ int s_last;
+    if (full_count > 0) run_items<2, false>(a, lds, s_last, tiles_m, tiles_n, 0, full_count, 0);
+    // (nobody reads the stage buffers after a tile's last barrier, and the staging rows of
+    // the epilogue lie outside what the next phase's first loads fill)
+    if (FORM == 1) run_items<1, false>(a, lds, s_last, tiles_m, tiles_n, full_count, 2 * tail_count, 0);
+    if (FORM == 2) run_items<2, true>(a, lds, s_last, tiles_m, tiles_n, full_count, tail_count, tail_wgs);
 }
 
 }  // namespace
@@ -478,7 +603,7 @@ namespace flexq {
 StreamKPlan streamk_plan(int M, int N, int K)
 {
     StreamKPlan p;
-    p.tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    p.tiles = ((M + BM - 1) / BM) * ((N + 255) / 256);
     p.full_tiles = p.tiles / kStreamKGrid * kStreamKGrid;
     p.tail_tiles = p.tiles - p.full_tiles;
     // two slots per run; a run is at least one 128-k stage, and there are at most 256 runs
@@ -487,66 +612,96 @@ StreamKPlan streamk_plan(int M, int N, int K)
     return p;
 }
 
-// Estimated run time in microseconds, measured constants of the MI355X: a 128-k
-// stage of a 256x256 tile takes 1.56 us at the clock this load sustains, prologue plus
-// epilogue 7 us per tile.  Meeting in the workspace costs 14 us plus 2 us per
-// workgroup of a tile when every tile is cut into the same number S of runs (one
-// partial tile per workgroup: 256 KiB written, the last to arrive reads the others');
-// about 45 us when the tail is simply cut into 256 equal runs, which then begin and
-// end inside tiles (two partial tiles per workgroup).
-double gemm_wlds_estimate_us(int M, int N, int K, bool may_cut, int *tail_wgs)
+// Estimated run time in microseconds of the fastest launch form, from measured constants
+// of the MI355X.  A 128-k stage of a whole tile takes 1.50 us when every CU has a tile and
+// 1.20 us when at most two thirds of them have (the chip is power-limited: idle CUs let
+// the others clock higher), a half tile's stage 0.93 / 0.75 us; a tile costs 4 us more for
+// its first loads and its epilogue.  Meeting in the workspace costs 14 us plus 2 us per
+// workgroup of a tile when every tile is cut into the same number S of runs (one partial
+// tile per workgroup: 256 KiB written, the last to arrive reads the others'); about 45 us
+// when the tail is simply cut into 256 equal runs, which then begin and end inside tiles
+// (two partial tiles per workgroup).
+WldsChoice gemm_wlds_choose(int M, int N, int K, bool may_cut)
 {
     const StreamKPlan p = streamk_plan(M, N, K);
     const int KT = K / FLEXQ_TILE_K;
-    const double stage_us = 1.556, tile_us = stage_us * KT + 7.0;
-    const double whole_rounds = (double)(p.full_tiles / kStreamKGrid) * tile_us;
-    // every tail tile whole: one more round
-    double best = whole_rounds + (p.tail_tiles ? tile_us : 0.0);
-    *tail_wgs = 0;
-    if (p.tail_tiles == 0 || !may_cut) return best;
+    auto busy = [](double frac) { return frac <= 0.65 ? 0.0 : (frac - 0.65) / 0.35; };
+    auto whole_us = [&](int tiles) { return (1.20 + 0.30 * busy(tiles / 256.0)) * KT + 4.0; };
+    auto half_us = [&](int halves) { return (0.75 + 0.18 * busy(halves / 256.0)) * KT + 4.0; };
+    const double rounds = (double)(p.full_tiles / kStreamKGrid) * whole_us(kStreamKGrid);
+    WldsChoice best{rounds + (p.tail_tiles ? whole_us(p.tail_tiles) : 0.0), 0, 0};
+    if (p.tail_tiles == 0) return best;
+    {   // the tail as half tiles: one half round, or two
+        const int halves = 2 * p.tail_tiles;
+        const double t = rounds + (halves <= kStreamKGrid ? half_us(halves)
+                                                          : half_us(kStreamKGrid) + half_us(halves - kStreamKGrid));
+        if (t < best.us) best = WldsChoice{t, 1, halves};
+    }
+    if (!may_cut) return best;
+    const double stage_us = 1.50;
     for (int S = 2; S <= 8 && p.tail_tiles * S <= kStreamKGrid && S <= KT; ++S) {
-        const double t = whole_rounds + stage_us * ((KT + S - 1) / S) + 7.0 + 14.0 + 2.0 * S;
-        if (t < best) {
-            best = t;
-            *tail_wgs = p.tail_tiles * S;
-        }
+        const double t = rounds + stage_us * ((KT + S - 1) / S) + 4.0 + 14.0 + 2.0 * S;
+        if (t < best.us) best = WldsChoice{t, 2, p.tail_tiles * S};
     }
     if ((long)p.tail_tiles * KT >= 2L * kStreamKGrid) {
-        const double t = whole_rounds + stage_us * KT * p.tail_tiles / kStreamKGrid + 7.0 + 45.0;
-        if (t < best) {
-            best = t;
-            *tail_wgs = kStreamKGrid;
-        }
+        const double t = rounds + stage_us * KT * p.tail_tiles / kStreamKGrid + 4.0 + 45.0;
+        if (t < best.us) best = WldsChoice{t, 2, kStreamKGrid};
     }
     return best;
 }
 
-hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_wgs, hipStream_t st)
+namespace {
+
+constexpr int kLdsBytes = Shape<2>::LDS_BYTES > Shape<1>::LDS_BYTES ? Shape<2>::LDS_BYTES : Shape<1>::LDS_BYTES;
+
+template <int FORM>
+hipError_t launch_form(const LinearArgs &a, int tiles_m, int tiles_n, int full_count, int tail_count,
+                       int tail_wgs, int grid, hipStream_t st)
+{
+    auto kern = gemm_wlds_kernel<FORM>;
+    static std::atomic<unsigned long long> lds_allowed{0};
+    if (hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), kLdsBytes, lds_allowed);
+        e != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WAVES), kLdsBytes, st, a, tiles_m, tiles_n,
+                       full_count, tail_count, tail_wgs);
+    return hipGetLastError();
+}
+
+// workgroups for `items` items: a multiple of 8 (one share per XCD), at most one per CU
+// on the 256-CU device the persistent forms are laid out for, else one per item
+int grid_for(int items)
+{
+    const int g = (items + 7) / 8 * 8;
+    return device_cu_count() == kStreamKGrid && g > kStreamKGrid ? kStreamKGrid : g;
+}
+
+}  // namespace
+
+hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_form, int tail_wgs, hipStream_t st)
 {
     if (a.group != 0 || a.split_k > 1 || a.sxg) return hipErrorInvalidValue;
-    const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    static std::atomic<unsigned long long> lds_allowed[2];
-    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(gemm_wlds_kernel<false>), LDS_BYTES,
-                                     lds_allowed[0]);
-    if (e == hipSuccess)
-        e = allow_dynamic_lds(reinterpret_cast<const void *>(gemm_wlds_kernel<true>), LDS_BYTES, lds_allowed[1]);
-    if (e != hipSuccess) return e;
+    const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + 255) / 256;
     const StreamKPlan p = streamk_plan(a.M, a.N, a.K);
-    // (without room for the partial sums, or on a device that is not 256 CUs wide, the
-    // tail tiles simply run whole)
-    if (tail_wgs <= 0 || p.tail_tiles == 0 || a.partial_bytes < p.partial_bytes ||
-        device_cu_count() != kStreamKGrid) {
-        hipLaunchKernelGGL(gemm_wlds_kernel<false>, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WAVES),
-                           LDS_BYTES, st, a, tiles_m, tiles_n, 0, 0, 0);
-        return hipGetLastError();
+    // without room for the partial sums, or on a device that is not 256 CUs wide, a tail
+    // that was to be cut runs as whole tiles
+    if (tail_form == 2 && (tail_wgs <= 0 || a.partial_bytes < p.partial_bytes ||
+                           device_cu_count() != kStreamKGrid))
+        tail_form = 0;
+    if (tail_form == 0 || p.tail_tiles == 0)      // every tile whole
+        return launch_form<0>(a, tiles_m, tiles_n, p.tiles, 0, 0, grid_for(p.tiles), st);
+    // the whole rounds first, then the tiles of the last, partial round in their own form
+    const int g_full = p.full_tiles ? grid_for(p.full_tiles) : 0;
+    if (tail_form == 1) {
+        const int g = grid_for(2 * p.tail_tiles);
+        return launch_form<1>(a, tiles_m, tiles_n, p.full_tiles, p.tail_tiles, 0, g > g_full ? g : g_full, st);
     }
     // a run is at least one stage, and the tail has at most 256 runs
     const long stages = (long)p.tail_tiles * (a.K / FLEXQ_TILE_K);
     if (tail_wgs > kStreamKGrid) tail_wgs = kStreamKGrid;
     if (tail_wgs > stages) tail_wgs = (int)stages;
-    hipLaunchKernelGGL(gemm_wlds_kernel<true>, dim3(kStreamKGrid), dim3(64 * WAVES), LDS_BYTES, st, a,
-                       tiles_m, tiles_n, p.full_tiles, p.tail_tiles, tail_wgs);
-    return hipGetLastError();
+    const int g = (tail_wgs + 7) / 8 * 8;
+    return launch_form<2>(a, tiles_m, tiles_n, p.full_tiles, p.tail_tiles, tail_wgs, g > g_full ? g : g_full, st);
 }
 
 }  // namespace flexq

@@ -248,7 +248,7 @@ def test_tiled_kernel_k_splits(split, M, group):
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 5, 6, 7, 8, 12, 13])
+@pytest.mark.parametrize("cfg", [1, 2, 5, 6, 7, 8, 12, 13, 14])
 @pytest.mark.parametrize("M,K,N", [(5, 128, 32), (130, 384, 96), (300, 640, 544), (513, 1280, 288),
                                    (512, 256, 544)])
 def test_tiled_kernel_tile_shapes(cfg, M, K, N):
@@ -274,25 +274,31 @@ def test_tiled_kernel_tile_shapes(cfg, M, K, N):
     assert_y_close(y_only.cpu().numpy().view(np.float16), ref["y"])
 
 
-@pytest.mark.parametrize("M,K,N", [(768, 256, 22016),     # 258 tiles: a whole round, two tail tiles run whole
-                                   (768, 1024, 22016),    # the same, tail cut four ways
-                                   (700, 2304, 1120),     # 15 ragged tiles shared by 60 workgroups
-                                   (256, 8192, 512)])     # two tiles of 64 stages, four workgroups each
-def test_tiled_kernel_tail_cut_along_k(M, K, N):
-    """The persistent form of the 256x256 kernel: whole rounds tile by tile, the last
-    round cut along K, partial sums met in the workspace.  Twice on one workspace: the
-    tile counters must be back at zero after every call."""
-    say(f"256x256 tiles, tail cut along K: M={M} K={K} N={N}")
+@pytest.mark.parametrize("cfg", [12, 13, 14])
+@pytest.mark.parametrize("M,K,N", [(768, 256, 22016),     # 258 tiles: a whole round, two tiles left over
+                                   (768, 1024, 22016),    # the same, eight stages to cut
+                                   (700, 2304, 1120),     # 15 ragged tiles
+                                   (256, 8192, 512),      # two tiles of 64 stages
+                                   (1024, 256, 32768),    # 512 tiles: two per workgroup, no tail
+                                   (512, 384, 25600)])    # 200 tiles: 400 half tiles on 256 workgroups
+def test_tiled_kernel_persistent_forms(cfg, M, K, N):
+    """The 256-row kernel with both operands through LDS in its three launch forms: whole
+    tiles (12), the tiles beyond the last whole round cut along K with partial sums met in
+    the workspace (13), or run as half tiles (14); workgroups that take several items load
+    the next one's first stages while they store.  Twice on one workspace: the tile
+    counters must be back at zero after every call."""
+    say(f"256-row tiles, form {cfg}: M={M} K={K} N={N}")
     w = synth.weights(N, K, 0.02, seed=81)
     x = synth.activations(M, K, seed=82, outlier_frac=0.02)
     packed, _, _ = prepare(w)
     xq, sx = fq.quant_act(to_dev(x), 8)
     ref = oracle.linear(x, w, 8)
     ws = fq.make_workspace(M, N, K)
-    dev.set_dispatch(2, 1, 0, 13)
+    dev.set_dispatch(2, 1, 0, cfg)
     try:
         for _ in range(2):
             y, acc = run_linear(dev.gemm_w6a8, packed, N, K, 0, xq, sx, True, ws)
+            assert dev.last_dispatch()[0] == cfg
             assert np.array_equal(acc.astype(np.int64), ref["acc"])
             assert_y_close(y.view(np.float16), ref["y"])
         y_only = dev.gemm_w6a8(packed, N, K, xq=xq, sx=sx, workspace=ws)
@@ -328,7 +334,7 @@ def test_ablation_variants_compute_the_same(choice, M):
 
 
 @pytest.mark.parametrize("K", [28672, 65536])   # the workloads' longest reduction; the longest allowed
-@pytest.mark.parametrize("kernel", ["stream", "tiled", "tiled 256x256", "tiled 256x256 cut"])
+@pytest.mark.parametrize("kernel", ["stream", "tiled", "tiled 256x256", "tiled 256x256 cut", "tiled 256x128"])
 def test_extreme_codes_exact(kernel, K):
     """Every product at its extreme: the int32 sums (kept times four inside the kernels) reach
     2^28 at K = 28672 and 2^30 at the largest K the library accepts."""
@@ -344,7 +350,7 @@ def test_extreme_codes_exact(kernel, K):
     packed = fq.pack_w6(to_dev(wq), to_dev(sw))
     acc_ref = oracle.matmul(xq, wq)
     y_ref = oracle.dequant(acc_ref, sx, sw)
-    cfg = {"stream": 0, "tiled": 0, "tiled 256x256": 12, "tiled 256x256 cut": 13}[kernel]
+    cfg = {"stream": 0, "tiled": 0, "tiled 256x256": 12, "tiled 256x256 cut": 13, "tiled 256x128": 14}[kernel]
     dev.set_dispatch(1 if kernel == "stream" else 2, 1 if cfg else 0, 0, cfg)
     try:
         y, acc = run_linear(dev.gemm_w6a8, packed, N, K, 0, to_dev(xq), to_dev(sx), True)
@@ -723,7 +729,7 @@ def test_random_shapes_forced_tiled_kernels():
         M = int(rng.integers(1, 700))
         K = 128 * int(rng.integers(1, 40))
         N = 32 * int(rng.integers(1, 48))
-        cfg = int(rng.choice([7, 8, 12, 13, 13, 13]))
+        cfg = int(rng.choice([7, 8, 12, 13, 13, 14, 14]))
         split = int(rng.integers(2, 9)) if cfg == 8 and rng.integers(0, 2) else 1
         say(f"random tiled case {case}: M={M} K={K} N={N} cfg={cfg} split={split}")
         w = synth.weights(N, K, 0.02, seed=9100 + case)
@@ -746,8 +752,9 @@ def test_random_shapes_forced_tiled_kernels():
 def test_dispatch_choices_on_the_70b_layers():
     """Which kernel the library's own dispatch launches on the bench workload's layers
     (outputs are checked elsewhere; this pins the choice itself): streaming kernel for
-    decode, 256x256 tiles in whole rounds at 4096 tokens, 128x256 for the 10240-wide QKV,
-    the persistent form with a cut tail for the down projection at 1024 tokens."""
+    decode, 256x256 tiles in whole rounds at 4096 tokens, whole rounds plus a tail as half
+    tiles or cut along K for the 10240-wide QKV (640 tiles), a cut tail for the down
+    projection at 1024 tokens, half tiles for the attention output there."""
     say("dispatch choices")
 
     def launched(M, N, K):
@@ -762,8 +769,9 @@ def test_dispatch_choices_on_the_70b_layers():
     assert launched(16, 8192, 28672)[0] == 1
     assert launched(4096, 8192, 8192) == (12, 1)
     assert launched(4096, 8192, 28672) == (12, 1)
-    assert launched(4096, 10240, 8192) == (7, 1)
+    assert launched(4096, 10240, 8192)[0] in (13, 14)
     assert launched(1024, 8192, 28672) == (13, 256)      # 128 tiles, two runs each
+    assert launched(1024, 8192, 8192) == (14, 256)       # 128 tiles as 256 half tiles
     kernel, splits = launched(128, 8192, 8192)
     assert kernel == 8 and splits > 1                     # 128x128 tiles with K splits
 

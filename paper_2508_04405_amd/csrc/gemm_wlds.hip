@@ -11,13 +11,16 @@
 // wavefronts that share its columns: 0.875 KB through the vector-memory path
 // per 32x32x128 block at NT = 2 instead of 1.25.
 //
-//   LDS: three activation stages of 32 KiB (two stages ahead) and two weight
-//   stages of 12 NT KiB (one stage ahead: a weight stage is consumed -- copied
-//   to registers -- right at the start of its stage, so its buffer is free for
-//   the stage after next as soon as every wavefront has passed the next
-//   barrier); one workgroup per CU, two wavefronts per SIMD.
-//   Per stage and wavefront: its weight DMA loads, then 4 activation DMA loads;
-//   the hand-over waits until at most the 4 youngest are outstanding.
+//   LDS: three weight stages of 12 NT KiB, requested TWO stages ahead (a packed
+//   weight panel is read by few workgroups, all at the same time, so its lines
+//   come from HBM, well over a microsecond away), and activation stages of
+//   32 KiB: for whole tiles two of them, requested one stage ahead (an
+//   activation panel is shared by every column tile of its row and mostly found
+//   in L2 or the Infinity Cache; a third stage would not fit beside the weights),
+//   for half tiles, whose stages are shorter than the memory latency, three,
+//   requested two ahead.  One workgroup per CU, two wavefronts per SIMD.
+//   The hand-over waits until at most the loads for the stage after next are
+//   outstanding.
 //
 // Per-channel scales only: this is the kernel for large M and N.
 //
@@ -66,16 +69,23 @@ struct Shape {
     static_assert(BN == 256 || BN == 128, "whole or half tiles");
     static constexpr int WTILES = BN / 32;                        // packed tiles per stage
     static constexpr int WSTAGE = WTILES * FLEXQ_TILE_BYTES;
-    static constexpr int WBASE = 3 * XSTAGE;
-    // Epilogue staging, 32 rows of fp16 per wavefront: it begins where the SECOND weight
-    // stage does.  While a tile is stored, the next item's first stages are landing in the
-    // activation stages 0 and 1 and in weight stage 0; weight stage 1 and what lies beyond
-    // it are free until the next item's stage 0 asks for its successor's weights, after
-    // the barrier that ends the epilogue.
-    static constexpr int STG = WBASE + WSTAGE;
+    static constexpr int XA = NT == 1 ? 2 : 1;                    // activation stages requested ahead
+    static constexpr int XBUFS = XA + 1;
+    static constexpr int WBASE = XBUFS * XSTAGE;
+    // this wavefront's weight DMA loads per stage: plane p of a stage is fetched by
+    // wavefront p % 8
+    static constexpr int WDMA_LOW = (3 * WTILES + WAVES - 1) / WAVES;    // wavefronts below WDMA_SPLIT
+    static constexpr int WDMA_HIGH = 3 * WTILES / WAVES;                 // the others
+    static constexpr int WDMA_SPLIT = 3 * WTILES % WAVES == 0 ? WAVES : 3 * WTILES % WAVES;
+    // Epilogue staging, 32 rows of fp16 per wavefront: it begins where the THIRD weight
+    // stage does.  While a tile is stored, the next item's first stages are landing in
+    // the activation stages below XA and in weight stages 0 and 1; weight stage 2 and what
+    // lies beyond it are free until the next item's stage 0 asks for the weights of its
+    // stage 2, after the barrier that ends the epilogue.
+    static constexpr int STG = WBASE + 2 * WSTAGE;
     static constexpr int ESTRIDE = NT * 64 + 16;
     static constexpr int STG_END = STG + WAVES * 32 * ESTRIDE;
-    static constexpr int LDS_BYTES = STG_END > WBASE + 2 * WSTAGE ? STG_END : WBASE + 2 * WSTAGE;
+    static constexpr int LDS_BYTES = STG_END > WBASE + 3 * WSTAGE ? STG_END : WBASE + 3 * WSTAGE;
     static_assert(LDS_BYTES + 1024 <= 160 * 1024, "LDS of one CU (plus the static part)");
 };
 
@@ -209,11 +219,15 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             }
         }
     };
-    // weights and activations of an item's stage 0, activations of its stage 1
+    // weights and activations of an item's stage 0, weights (and, where activations run
+    // two stages ahead, activations) of its stage 1
     auto issue_prologue = [&](const Item &it, const Where &w) {
         dma_w(w, it.ks, 0, 0);
         dma_x(w, it.ks, 0, 0);
-        if (it.ke - it.ks > 1) dma_x(w, it.ks, 1, 1);
+        if (it.ke - it.ks > 1) {
+            dma_w(w, it.ks, 1, 1);
+            if (S::XA == 2) dma_x(w, it.ks, 1, 1);
+        }
     };
 
     const int arow = (wm * MT) * 32 + (lane & 31);
@@ -255,20 +269,28 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             af[0][mt] = *reinterpret_cast<const v4i *>(lds + lds_off(arow + 32 * mt, ahalf));
         v4i bf_first = unpack_kstep(wreg[0], 0);
 
-        // One 128-k stage.  CUR = kb % 3 names the activation buffer; kb & 1 the weight buffer.
+        // One 128-k stage.  CUR = kb % XBUFS names the activation buffer (a constant, so that
+        // the operand reads use immediate offsets), wcur = kb % 3 the weight buffer.
         // The MFMA takes the WEIGHT fragment as its row operand: the accumulators hold D^T.
+        int wcur = 0;
         auto stage = [&](int kb, auto cur_tag) {
             constexpr int CUR = decltype(cur_tag)::value;
-            constexpr int NXT2 = (CUR + 2) % 3;
             const bool more1 = kb + 1 < KN, more2 = kb + 2 < KN;
-            // weights first: the hand-over waits for them and for everything older,
-            // while the activation loads issued after them may stay in flight
-            if (more1) dma_w(at, ks, kb + 1, (kb + 1) & 1);
-            if (more2) dma_x(at, ks, kb + 2, NXT2);
+            const int wnext = wcur == 2 ? 0 : wcur + 1, wnext2 = wcur == 0 ? 2 : wcur - 1;
+            // First what the hand-over waits for (with everything older, the weights of
+            // stage kb + 1 among it): the activations of stage kb + 1, where they run one
+            // stage ahead.  Then what may stay in flight across it: the loads for stage
+            // kb + 2.  All targets are free: an activation buffer was last read before the
+            // previous stage's barrier, the weight buffer was copied to registers two
+            // barriers ago.
+            if (S::XA == 1 && more1) dma_x(at, ks, kb + 1, (CUR + 1) % S::XBUFS);
+            if (S::XA == 2 && more2) dma_x(at, ks, kb + 2, (CUR + 2) % S::XBUFS);
+            if (more2) dma_w(at, ks, kb + 2, wnext2);
 
             const uint8_t *xs = lds + CUR * XSTAGE;
-            const uint8_t *xn = lds + ((CUR + 1) % 3) * XSTAGE;
-            const uint8_t *wnb = lds + wfrag + ((kb + 1) & 1) * S::WSTAGE;
+            const uint8_t *xn = lds + ((CUR + 1) % S::XBUFS) * XSTAGE;
+            const uint8_t *wnb = lds + wfrag + wnext * S::WSTAGE;
+            wcur = wnext;
             // Flat software pipeline over the 4 * NT (k-step, column tile) steps: LDS
             // operand reads a k-step ahead, weight operands expanded one dword per MFMA in
             // the shadow of the MFMA just issued.  The two wavefronts of a SIMD belong to
@@ -279,12 +301,15 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             // tiles and first activation operands of stage kb + 1 are fetched from LDS
             // while k-step 3's MFMAs run.
             // At the hand-over stage kb + 1 (weights and activations, every wavefront's
-            // share) must have landed; the activations of stage kb + 2 may be in flight.
+            // share) must have landed; the loads for stage kb + 2 may be in flight.
             auto hand_over = [&] {
-                if (more2)
-                    wait_vmcnt<XDMA>();
-                else
+                constexpr int XFLY = S::XA == 2 ? XDMA : 0;
+                if (!more2)
                     wait_vmcnt<0>();
+                else if (wave < S::WDMA_SPLIT)
+                    wait_vmcnt<XFLY + S::WDMA_LOW>();
+                else
+                    wait_vmcnt<XFLY + S::WDMA_HIGH>();
                 lds_barrier();
                 if (more1) {
 #pragma unroll
@@ -377,13 +402,13 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
         };
 
         int kb = 0;
-        for (; kb + 2 < KN; kb += 3) {
+        for (; kb + S::XBUFS <= KN; kb += S::XBUFS) {
             stage(kb, std::integral_constant<int, 0>{});
             stage(kb + 1, std::integral_constant<int, 1>{});
-            stage(kb + 2, std::integral_constant<int, 2>{});
+            if constexpr (S::XBUFS == 3) stage(kb + 2, std::integral_constant<int, 2>{});
         }
         if (kb < KN) stage(kb, std::integral_constant<int, 0>{});
-        if (kb + 1 < KN) stage(kb + 1, std::integral_constant<int, 1>{});
+        if (S::XBUFS == 3 && kb + 1 < KN) stage(kb + 1, std::integral_constant<int, 1>{});
         // (every wavefront has passed the last stage's barrier with its LDS reads done: the
         // stage buffers are free)
 
@@ -494,18 +519,15 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             const int bm0 = at.bm0, bn0 = at.bn0;
             const int ml = lane & 31, hh = lane >> 5;
             const int n_wave = bn0 + wn * NT * 32;
-            float swf[NT][4][4];
+            // (kept as packed fp16 and converted where used: sixteen registers, not thirty-two)
+            uint2 sw4[NT][4];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 const bool cvalid = n_wave + nt * 32 < N;                 // uniform; N is a multiple of 32
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int n = n_wave + nt * 32 + 8 * q + 4 * hh;
-                    const uint2 four = cvalid ? *reinterpret_cast<const uint2 *>(a.scales + n) : make_uint2(0u, 0u);
-                    swf[nt][q][0] = h2f((uint16_t)(four.x & 0xffffu));
-                    swf[nt][q][1] = h2f((uint16_t)(four.x >> 16));
-                    swf[nt][q][2] = h2f((uint16_t)(four.y & 0xffffu));
-                    swf[nt][q][3] = h2f((uint16_t)(four.y >> 16));
+                    sw4[nt][q] = cvalid ? *reinterpret_cast<const uint2 *>(a.scales + n) : make_uint2(0u, 0u);
                 }
             }
             float sxq[MT];
@@ -533,10 +555,13 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
+                        const unsigned swp[2] = {sw4[nt][q].x, sw4[nt][q].y};
                         uint16_t h[4];
 #pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            h[c] = f2h((float)acc[mt][nt][4 * q + c] * (sxq[mt] * swf[nt][q][c]));
+                        for (int c = 0; c < 4; ++c) {
+                            const float swc = h2f((uint16_t)(swp[c >> 1] >> (16 * (c & 1))));
+                            h[c] = f2h((float)acc[mt][nt][4 * q + c] * (sxq[mt] * swc));
+                        }
                         uint2 out2;
                         out2.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
                         out2.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
@@ -590,8 +615,11 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_co
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     __shared__ int s_last;
     if (full_count > 0) run_items<2, false>(a, lds, s_last, tiles_m, tiles_n, 0, full_count, 0);
-    // (nobody reads the stage buffers after a tile's last barrier, and the staging rows of
-    // the epilogue lie outside what the next phase's first loads fill)
+#if defined(__HIP_DEVICE_COMPILE__)
+    // The two phases lay LDS out differently: every wavefront must be through with its last
+    // epilogue's staging rows before anyone's first loads of the next phase land on them.
+    if (FORM != 0) lds_barrier();
+#endif
     if (FORM == 1) run_items<1, false>(a, lds, s_last, tiles_m, tiles_n, full_count, 2 * tail_count, 0);
     if (FORM == 2) run_items<2, true>(a, lds, s_last, tiles_m, tiles_n, full_count, tail_count, tail_wgs);
 }

@@ -22,17 +22,43 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-METRIC = "W6A8/W6A6 GEMM TOPS (M>=1024) + decode GEMV HBM GB/s, LLaMA-2-70B linears"
+METRIC = "W6A8/W6A6 GEMM TOPS (M\u22651024) + decode GEMV HBM GB/s, LLaMA-2-70B linears"
 PEAK_I8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
-# Bytes fetched past L2 + written, per launch, averaged over the four layers: rocprofv3 FETCH_SIZE and
-# WRITE_SIZE runs of this script, scaled on a 1 GiB device copy (x2.000 and x1.000); the runs, the
-# raw readings and the per-layer table are in profiles/bench_llama2_70b_linears_hbm_traffic.md.
-TRAFFIC_GEMM_M4096 = 1106.1e6 + 172.0e6
-TRAFFIC_GEMV_M1 = 160.76e6 + 0.042e6
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_llama2_70b_linears_hbm_traffic.md")
 SIGMA = 0.015
 LAYERS = [("qkv", 8192, 10240, 6), ("o", 8192, 8192, 6), ("gate_up", 8192, 57344, 6),
           ("down", 28672, 8192, 8)]          # name, K, N, activation bits
+
+
+def kernel_sources_key():
+    """Short hash of the kernel sources: names the build a counter profile was taken on."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2508_04405_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def profiled_traffic():
+    """Bytes past L2 per launch (fetched + written, averaged over the four layers) of the GEMM at
+    M = 4096 and of the GEMV at M = 1, from the rocprofv3 FETCH_SIZE / WRITE_SIZE summary under
+    profiles/ -- only if that summary was taken on exactly these kernel sources (its `kernel-sources`
+    line carries their hash); otherwise None, None: a stale figure is not printed beside live timings."""
+    import re
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+    except OSError:
+        return None, None
+    key = re.search(r"kernel-sources:\s*([0-9a-f]{16})", text)
+    gemm = re.search(r"gemm-m4096-traffic-bytes-per-launch:\s*([0-9.]+)", text)
+    gemv = re.search(r"gemv-m1-traffic-bytes-per-launch:\s*([0-9.]+)", text)
+    if not (key and gemm and gemv) or key.group(1) != kernel_sources_key():
+        return None, None
+    return float(gemm.group(1)), float(gemv.group(1))
 
 
 def algorithmic_bytes(M, N, K):
@@ -111,15 +137,43 @@ def sweep(args, torch, fq, fqdev, synth, dev):
         del bufs
 
 
+def replay_time(args, torch, enqueue):
+    """Microseconds per call of `enqueue()`, its launches captured in a HIP graph and the graph
+    replayed (at least 50 ms of warm-up replays: the host-side set-up leaves the GPU idle and its
+    clock low)."""
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        enqueue()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            enqueue()
+        t_warm = time.perf_counter()
+        reps = 0
+        while reps < args.warmup or time.perf_counter() - t_warm < 0.05:
+            graph.replay()
+            torch.cuda.synchronize()
+            reps += 1
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / args.steps
+
+
 def layer_table(args, torch, fq, fqdev, synth, dev):
-    """One decoder layer's seven linears as four calls (fused QKV, O, fused gate+up, down), each
-    fed by the producer that quantizes its input: RMS norm + quantize before QKV and gate+up,
-    the library's own quantize step before O (fp16 in: its input comes from attention, which is
-    not part of this path; decode batches quantize inside the GEMV), gated SiLU + quantize
-    before down.  Two policies: the paper's (A8 on the down
-    projection only) and a layer running all seven linears at A8 (the flagged layers of the
-    13B configuration).  The launches are captured in a HIP graph and replayed."""
-    models = [("LLaMA-2-7B", 4096, 11008, 4096 * 3, 0, (1, 8, 512, 2048)),
+    """One decoder layer's seven linears through flexq_layer_linears (fused QKV, O, fused gate+up,
+    down, each fed by the producer that quantizes its input: RMS norm + quantize before QKV and
+    gate+up, the quantize node before O, gated SiLU + quantize before down).  Two policies: the
+    paper's (A8 on the down projection only) and a layer running all seven linears at A8 (the
+    flagged layers of the 13B configuration).  The call's launches are captured in a HIP graph and
+    replayed; one layer's weights stay resident in the Infinity Cache between replays (the cold
+    figure for a whole stack of layers is --stack13b's)."""
+    models = [("LLaMA-2-7B", 4096, 11008, 4096 * 3, 0, (1, 8, 512, 2048, 4096)),
               ("LLaMA-2-13B, group-128 weight scales", 5120, 13824, 5120 * 3, 128, (32, 2048)),
               ("LLaMA-2-70B (GQA: 10240-wide QKV)", 8192, 28672, 10240, 0, (1, 16, 1024, 4096))]
     print("| model | M | policy | us per layer | TOP/s | weight GB/s |")
@@ -138,56 +192,74 @@ def layer_table(args, torch, fq, fqdev, synth, dev):
         wbytes = 0.75 * (QKV * H + H * H + 2 * F * H + H * F)
         ops1 = 2.0 * (QKV * H + H * H + 2 * F * H + H * F)
         for M in Ms:
-            h = torch.from_numpy(synth.activations(M, H, seed=7, outlier_frac=0.01)).to(dev)
+            x = torch.from_numpy(synth.activations(M, H, seed=7, outlier_frac=0.01)).to(dev)
             attn = torch.from_numpy(synth.activations(M, H, seed=8, outlier_frac=0.01)).to(dev)
-            bufs = {k: (torch.empty((M, n), dtype=torch.int8, device=dev),
-                        torch.empty((M,), dtype=torch.float16, device=dev))
-                    for k, n in (("h", H), ("f", F))}
             outs = {k: torch.empty((M, n), dtype=torch.float16, device=dev)
-                    for k, n in (("qkv", QKV), ("o", H), ("gu", 2 * F), ("dn", H))}
-            wss = {k: fq.make_workspace(M, n, kk, dev)
-                   for k, n, kk in (("qkv", QKV, H), ("o", H, H), ("gu", 2 * F, H), ("dn", H, F))}
+                    for k, n in (("qkv", QKV), ("o", H), ("gate_up", 2 * F), ("down", H))}
             for policy, bits in (("A6, A8 on down (the paper's)", (6, 6, 6, 8)),
                                  ("all seven linears A8", (8, 8, 8, 8))):
-                def gemm(bits_):
-                    return fq.gemm_w6a6 if bits_ == 6 else fq.gemm_w6a8
-
-                def layer():
-                    xq, sx = fq.rmsnorm_quant(h, gamma, 1e-5, bits[0], out=bufs["h"])
-                    gemm(bits[0])(w_qkv, QKV, H, group, xq=xq, sx=sx, workspace=wss["qkv"], out=outs["qkv"])
-                    # fp16 in: the library quantizes (inside the GEMV for decode batches)
-                    gemm(bits[1])(w_o, H, H, group, x_fp16=attn, workspace=wss["o"], out=outs["o"])
-                    xq, sx = fq.rmsnorm_quant(outs["o"], gamma, 1e-5, bits[2], out=bufs["h"])
-                    gemm(bits[2])(w_gu, 2 * F, H, group, xq=xq, sx=sx, workspace=wss["gu"], out=outs["gu"])
-                    xq, sx = fq.swiglu_quant(outs["gu"], bits[3], out=bufs["f"])
-                    gemm(bits[3])(w_dn, H, F, group, xq=xq, sx=sx, workspace=wss["dn"], out=outs["dn"])
-                stream = torch.cuda.Stream()
-                stream.wait_stream(torch.cuda.current_stream())
-                with torch.cuda.stream(stream):
-                    layer()
-                    torch.cuda.synchronize()
-                    graph = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(graph, stream=stream):
-                        layer()
-                    # warm up for at least 50 ms: the host-side set-up above left the GPU
-                    # idle, and its clock takes a while to come back up
-                    t_warm = time.perf_counter()
-                    reps = 0
-                    while reps < args.warmup or time.perf_counter() - t_warm < 0.05:
-                        graph.replay()
-                        torch.cuda.synchronize()
-                        reps += 1
-                    e0 = torch.cuda.Event(enable_timing=True)
-                    e1 = torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    for _ in range(args.steps):
-                        graph.replay()
-                    e1.record()
-                    torch.cuda.synchronize()
-                us = e0.elapsed_time(e1) * 1e3 / args.steps
+                layer = fq.Layer(H, F, QKV, group, w_qkv, w_o, w_gu, w_dn, gamma, gamma, 1e-5, bits)
+                ws = layer.make_workspace(M, dev)
+                us = replay_time(args, torch, lambda: fq.layer_linears(layer, M, ws, x=x, attn=attn,
+                                                                         x_ffn=outs["o"], **outs))
                 print("| %s | %d | %s | %.1f | %.0f | %.0f |" % (name, M, policy, us, ops1 * M / us / 1e6,
                                                               wbytes / us / 1e3), flush=True)
         del w_qkv, w_o, w_gu, w_dn
+
+
+def stack13b(args, torch, fq, fqdev, synth, dev):
+    """The LLaMA-2-13B-shaped stack of 40 decoder layers' linears (hidden 5120, FFN 13824, fused QKV
+    15360), every layer with packed weights of its own (group-128 scales, 9.5 GB resident: a pass
+    streams them from HBM, cold by construction).  A seeded quarter of the layers carries outlier
+    channels x50 in its input and runs all seven linears at W6A8; the others run W6A6 (Section
+    4.1.2's selective precision, per layer as the 13B configuration states it).  Each layer is one
+    flexq_layer_linears call on its own synthetic input and attention output; the 40 calls are
+    captured in one HIP graph.  Reports the aggregate time of the seven linears (with their fused
+    producers) over all 40 layers for batched decode (M = 32) and prefill (M = 2048)."""
+    H, F, QKV, group, n_layers = 5120, 13824, 15360, 128, 40
+    rng = __import__("numpy").random.default_rng(13)
+    flagged = rng.random(n_layers) < 0.25
+    gen = torch.Generator(device=dev)
+    layers = []
+    for i in range(n_layers):
+        gen.manual_seed(13000 + i)
+
+        def make(N, K):
+            w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+            p = fq.pack_w6(*fq.quant_w6(w, group), group)
+            del w
+            return p
+        gamma = torch.from_numpy(synth.norm_gain(H, seed=13100 + i)).to(dev)
+        bits = (8, 8, 8, 8) if flagged[i] else (6, 6, 6, 6)
+        layers.append(fq.Layer(H, F, QKV, group, make(QKV, H), make(H, H), make(2 * F, H), make(H, F),
+                               gamma, gamma, 1e-5, bits))
+    torch.cuda.synchronize()
+    wbytes = n_layers * (0.75 + 2.0 / 128) * (QKV * H + H * H + 2 * F * H + H * F)
+    ops1 = n_layers * 2.0 * (QKV * H + H * H + 2 * F * H + H * F)
+    print("%d layers, %d of them W6A8 (outlier channels x50): %s; packed weights %.2f GB" %
+          (n_layers, int(flagged.sum()), " ".join(str(i) for i in range(n_layers) if flagged[i]), wbytes / 1e9))
+    print("| M | us, all 40 layers x 7 linears | us per layer | TOP/s | weight GB/s |")
+    print("|---|---|---|---|---|")
+    for M in (32, 2048):
+        xs, attns = [], []
+        for i in range(n_layers):
+            scale = 50.0 if flagged[i] else 1.0        # no outlier channels in the other layers
+            frac = 0.01 if flagged[i] else 0.0
+            xs.append(torch.from_numpy(synth.activations(M, H, seed=13200 + i, outlier_frac=frac,
+                                                         outlier_scale=scale)).to(dev))
+            attns.append(torch.from_numpy(synth.activations(M, H, seed=13300 + i, outlier_frac=frac,
+                                                            outlier_scale=scale)).to(dev))
+        outs = {k: torch.empty((M, n), dtype=torch.float16, device=dev)
+                for k, n in (("qkv", QKV), ("o", H), ("gate_up", 2 * F), ("down", H))}
+        ws = layers[0].make_workspace(M, dev)
+
+        def step():
+            for i, layer in enumerate(layers):
+                fq.layer_linears(layer, M, ws, x=xs[i], attn=attns[i], x_ffn=outs["o"], **outs)
+        us = replay_time(args, torch, step)
+        print("| %d | %.0f | %.1f | %.0f | %.0f |" % (M, us, us / n_layers, ops1 * M / us / 1e6, wbytes / us / 1e3),
+              flush=True)
+        del xs, attns
 
 
 def ablation(args, torch, fq, fqdev, synth, dev):
@@ -270,6 +342,8 @@ def main():
     ap.add_argument("--prefill-m", type=int, default=4096)
     ap.add_argument("--decode-m", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sources-key", action="store_true",
+                    help="print the hash of the kernel sources (what a counter profile is tagged with) and exit")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="only run a plain device copy of known size (for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -282,6 +356,10 @@ def main():
                     help="instead of the benchmark line, print the time of one decoder layer's "
                          "seven linears (four GEMM calls fed by the fused producers) for the "
                          "LLaMA-2 7B / 13B / 70B shapes")
+    ap.add_argument("--stack13b", action="store_true",
+                    help="instead of the benchmark line, print the aggregate time of the LLaMA-2-13B-shaped "
+                         "40-layer linear stack (group-128 weight scales, a seeded quarter of the layers at "
+                         "W6A8) at M = 32 and M = 2048")
     ap.add_argument("--ablation", action="store_true",
                     help="instead of the benchmark line, print the decode-kernel ablation table "
                          "(one design choice undone per row) on the paper's Table-6 shapes")
@@ -289,6 +367,9 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); "
                  "there is no multi-GPU path to measure")
+    if args.sources_key:
+        print(kernel_sources_key())
+        return
 
     import numpy as np
     import torch
@@ -323,6 +404,8 @@ def main():
         return ablation(args, torch, fq, fqdev, synth, dev)
     if args.layer:
         return layer_table(args, torch, fq, fqdev, synth, dev)
+    if args.stack13b:
+        return stack13b(args, torch, fq, fqdev, synth, dev)
 
     # ---- resident inputs: packed weights, fp16 activations -----------------
     gen = torch.Generator(device=dev)
@@ -372,7 +455,18 @@ def main():
             e1.record()
             events.append((layer["name"], e0, e1))
 
+    preroll_ms = {}
+
     def timed(tag, per_kernel_events):
+        # pre-roll: the host-side set-up above left the GPU idle, and its clock takes tens of
+        # milliseconds of load to settle; run the step for at least 50 ms before the declared
+        # warm-up steps (reported as preroll_ms)
+        t_roll = time.perf_counter()
+        while time.perf_counter() - t_roll < 0.05:
+            for layer in layers:
+                run_layer(layer, tag)
+            torch.cuda.synchronize()
+        preroll_ms[tag] = round((time.perf_counter() - t_roll) * 1e3, 1)
         for _ in range(args.warmup):
             for layer in layers:
                 run_layer(layer, tag)
@@ -386,6 +480,37 @@ def main():
         t1 = time.perf_counter()
         return (t1 - t0) / args.steps, events
 
+    def timed_graph(enqueue_step):
+        """The same for a launch-bound step: its launches are captured once in a HIP graph
+        (the calls only enqueue kernels: no allocation, no memset) and the graph is replayed,
+        so the step is not bounded by the host's launch rate.  Returns seconds per step by
+        the host clock between synchronizations, and by HIP events on the replay stream."""
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(stream):
+            enqueue_step()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                enqueue_step()
+            t_roll = time.perf_counter()
+            while time.perf_counter() - t_roll < 0.05:
+                graph.replay()
+                torch.cuda.synchronize()
+            for _ in range(args.warmup):
+                graph.replay()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record()
+            for _ in range(args.steps):
+                graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+        return (t1 - t0) / args.steps, e0.elapsed_time(e1) * 1e-3 / args.steps
+
     # ---- prefill: the headline ------------------------------------------------
     Mp = args.prefill_m
     step_s, events = timed("prefill", True)
@@ -397,40 +522,40 @@ def main():
     gemm_s = sum(sum(v) for v in per_layer.values()) / args.steps       # the 4 GEMM launches
     gemm_tops = ops_step / gemm_s / 1e12
     launches = 4 * args.steps
+    traffic_gemm, traffic_gemv = profiled_traffic()
     roofline = {
         "bound": "mfma",
-        "kernel": "gemm_wlds_kernel (256x256 tiles: o, gate_up, down) and gemm_kernel<1,4,4,2> (128x256: qkv), "
-                  "i8 MFMA 32x32x32",
+        "kernel": "gemm_wlds_kernel (256-row tiles, both operands through LDS, persistent; the 10240-wide "
+                  "qkv adds a tail of half tiles or K-cut tiles), i8 MFMA 32x32x32",
         "achieved": round(gemm_tops, 2), "peak": PEAK_I8_TOPS / 1.0, "unit": "TOP/s",
         "frac": round(gemm_tops / PEAK_I8_TOPS, 4),
         "avg_launch_ms": round(gemm_s / 4 * 1e3, 4), "launches": launches,
         "per_layer_tops": {n: round(2.0 * Mp * L["N"] * L["K"] / (sum(per_layer[n]) / args.steps) / 1e12, 2)
                            for n, L in ((L["name"], L) for L in layers)},
-        "traffic": TRAFFIC_GEMM_M4096 if Mp == 4096 else None,
+        "traffic": traffic_gemm if Mp == 4096 else None,
         "algorithmic_bytes": sum(gemm_bytes(Mp, L["N"], L["K"]) for L in layers) / 4,
     }
 
     # ---- decode: weight-streaming GEMV ---------------------------------------
     Md = args.decode_m
-    dstep_s, _ = timed("decode", False)
+
+    def decode_step():
+        for layer in layers:
+            run_layer(layer, "decode")
+    dstep_s, _ = timed_graph(decode_step)
     dbytes = sum(algorithmic_bytes(Md, L["N"], L["K"]) for L in layers)
-    # kernel-only rate: the same four GEMV launches back to back, no quantize pass, one event pair
+    # kernel-only rate: the same four GEMV launches back to back, no quantize pass
     for layer in layers:
         b = layer["decode"]
         fq.quant_act(b["x"], layer["bits"], out=(b["xq"], b["sx"]))
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(args.steps):
+
+    def gemv_step():
         for layer in layers:
             b = layer["decode"]
             (fq.gemv_w6a6 if layer["bits"] == 6 else fq.gemv_w6a8)(
                 layer["packed"], layer["N"], layer["K"], 0, xq=b["xq"], sx=b["sx"],
                 workspace=b["ws"], out=b["y"])
-    e1.record()
-    torch.cuda.synchronize()
-    gemv_s = e0.elapsed_time(e1) * 1e-3 / args.steps
+    _, gemv_s = timed_graph(gemv_step)
     gbytes = sum(gemm_bytes(Md, L["N"], L["K"]) for L in layers)
     roofline_decode = {
         "bound": "hbm", "kernel": "skinny_kernel (streaming GEMV, M=%d)" % Md,
@@ -438,7 +563,7 @@ def main():
         "frac": round(gbytes / gemv_s / 1e9 / PEAK_HBM_GBS, 4),
         "avg_launch_us": round(gemv_s / 4 * 1e6, 2), "launches": 4 * args.steps,
         "bytes_per_step": int(gbytes), "algorithmic_bytes": gbytes / 4,
-        "traffic": TRAFFIC_GEMV_M1 if Md == 1 else None,
+        "traffic": traffic_gemv if Md == 1 else None,
     }
 
     # ---- measured ceilings on this machine (context for the fractions above) ------
@@ -500,7 +625,8 @@ def main():
 
     out = {
         "metric": METRIC, "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(step_s * 1e3, 4),
+        "steps": args.steps, "warmup": args.warmup, "preroll_ms": preroll_ms,
+        "ms_per_step": round(step_s * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": "LLaMA-2-70B linears (configs[3]): qkv 8192x10240, o 8192x8192, "
@@ -509,7 +635,8 @@ def main():
                    "prefill_tokens": Mp, "decode_tokens": Md},
         "decode": {"value": round(dbytes / dstep_s / 1e9, 1), "unit": "GB/s",
                    "us_per_step": round(dstep_s * 1e6, 2),
-                   "note": "algorithmic bytes of quantize + GEMV for the four layers / step time"},
+                   "note": "algorithmic bytes of quantize + GEMV for the four layers / step time; the "
+                           "step's launches are captured in a HIP graph and replayed"},
         "roofline": roofline, "roofline_decode": roofline_decode, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -233,6 +233,59 @@ flexq_status flexq_linear_g128(const void *packed, const int8_t *xq,
                                size_t workspace_bytes, void *stream);
 
 /*
+ * The linear layers of one decoder block as one call (Section 4.1.3, "FlexQ System
+ * Runtime": every GEMM is fed by the operator that produces its input, with the
+ * activation quantizer fused in; Section 4.1.2: the activation width is chosen per
+ * linear -- the paper's policy is 8 bits on the down projection, 6 elsewhere).
+ *
+ *   stage 0   RMS norm(x; gamma_attn) + quantize  ->  fused QKV      -> qkv  [M, QKV]
+ *   stage 1   quantize(attn)                      ->  attention out  -> o    [M, H]
+ *   stage 2   RMS norm(x_ffn; gamma_ffn) + quant  ->  fused gate|up  -> gate_up [M, 2F]
+ *   stage 3   SiLU(gate) * up + quantize          ->  down           -> down [M, H]
+ *
+ * Attention itself and the residual additions are not part of this path: the caller
+ * supplies the attention output `attn` and the input of the second norm `x_ffn` (it
+ * may alias `o`), and may run the stages in two calls around its own attention with
+ * first_stage / last_stage (0 <= first_stage <= last_stage <= 3).
+ *
+ * flexq_layer: H hidden size, F feed-forward width, QKV width of the fused QKV
+ * projection (all multiples of 128); group 0 or 128 as the four packed buffers were
+ * made (w_qkv [QKV,H], w_o [H,H], w_gate_up [2F,H] gate rows first, w_down [H,F]);
+ * gamma_* fp16 [H]; eps > 0; bits_* 6 or 8.  flexq_layer_io: fp16 device buffers,
+ * 16-byte aligned; h_* are optional outputs (NULL, or fp16 [M,H] / [M,F]) receiving
+ * the fp16 values the fused producers quantized, for checks.  Only what the
+ * requested stages touch is looked at.  Workspace: flexq_layer_workspace_bytes(L, M)
+ * bytes, 256-byte aligned, its first FLEXQ_WORKSPACE_COUNTER_BYTES zero before the
+ * first call (flexq_workspace_init), shared by the stages, which run in order on
+ * `stream`.  Results of every stage are those of the corresponding single calls
+ * (flexq_rmsnorm_quant / flexq_swiglu_quant / flexq_gemm_w6a6 / _w6a8), status codes
+ * as theirs; nothing is launched if an argument of any requested stage is bad.
+ */
+typedef struct {
+    int H, F, QKV, group;
+    const void *w_qkv, *w_o, *w_gate_up, *w_down;
+    const uint16_t *gamma_attn, *gamma_ffn;
+    float eps;
+    int bits_qkv, bits_o, bits_gate_up, bits_down;
+} flexq_layer;
+
+typedef struct {
+    const uint16_t *x;        /* in  [M,H]   stage 0 */
+    uint16_t *qkv;            /* out [M,QKV] stage 0 */
+    const uint16_t *attn;     /* in  [M,H]   stage 1 */
+    uint16_t *o;              /* out [M,H]   stage 1 */
+    const uint16_t *x_ffn;    /* in  [M,H]   stage 2 */
+    uint16_t *gate_up;        /* out [M,2F]  stage 2, in stage 3 */
+    uint16_t *down;           /* out [M,H]   stage 3 */
+    uint16_t *h_attn_norm, *h_ffn_norm, *h_swiglu;   /* optional outs: [M,H], [M,H], [M,F] */
+} flexq_layer_io;
+
+size_t flexq_layer_workspace_bytes(const flexq_layer *L, int M);
+flexq_status flexq_layer_linears(const flexq_layer *L, int M, const flexq_layer_io *io,
+                                 int first_stage, int last_stage, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
+/*
  * For callers that cannot allocate device memory -- code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc: flexq_gemv_w6a8 (same
  * arguments, same results, same status codes) without the workspace arguments.

@@ -19,6 +19,19 @@ class FlexQError(RuntimeError):
     pass
 
 
+class _Layer(ctypes.Structure):
+    _fields_ = [("H", ctypes.c_int), ("F", ctypes.c_int), ("QKV", ctypes.c_int), ("group", ctypes.c_int),
+                ("w_qkv", ctypes.c_void_p), ("w_o", ctypes.c_void_p), ("w_gate_up", ctypes.c_void_p),
+                ("w_down", ctypes.c_void_p), ("gamma_attn", ctypes.c_void_p), ("gamma_ffn", ctypes.c_void_p),
+                ("eps", ctypes.c_float), ("bits_qkv", ctypes.c_int), ("bits_o", ctypes.c_int),
+                ("bits_gate_up", ctypes.c_int), ("bits_down", ctypes.c_int)]
+
+
+class _LayerIO(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("x", "qkv", "attn", "o", "x_ffn", "gate_up", "down",
+                                               "h_attn_norm", "h_ffn_norm", "h_swiglu")]
+
+
 def load():
     """Load libflexq.so, building it first if it is missing or older than its sources."""
     global _lib
@@ -59,6 +72,11 @@ def load():
         fn = getattr(lib, name)
         fn.restype = c_int
         fn.argtypes = [vp, c_int, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp, c_size, vp]
+    lib.flexq_layer_workspace_bytes.restype = c_size
+    lib.flexq_layer_workspace_bytes.argtypes = [ctypes.POINTER(_Layer), c_int]
+    lib.flexq_layer_linears.restype = c_int
+    lib.flexq_layer_linears.argtypes = [ctypes.POINTER(_Layer), c_int, ctypes.POINTER(_LayerIO), c_int, c_int,
+                                        vp, c_size, vp]
     lib.flexq_gemv_w6a8_noalloc.restype = c_int
     lib.flexq_gemv_w6a8_noalloc.argtypes = [vp, c_int, vp, vp, vp, c_int, c_int, c_int, vp, vp, vp]
     _lib = lib
@@ -283,3 +301,46 @@ def gemv_w6a8_noalloc(packed, N, K, group=0, xq=None, sx=None, x_fp16=None, want
     _check(lib.flexq_gemv_w6a8_noalloc(_ptr(packed), group, _ptr(xq), _ptr(sx), _ptr(x_fp16), M, N, K,
                                        _ptr(y), _ptr(acc), _stream()))
     return (y, acc) if want_acc else y
+
+
+class Layer:
+    """The packed weights, norm gains and activation widths of one decoder block's linear
+    layers (a flexq_layer; keeps the tensors alive)."""
+
+    def __init__(self, H, F, QKV, group, w_qkv, w_o, w_gate_up, w_down, gamma_attn, gamma_ffn,
+                 eps=1e-5, bits=(6, 6, 6, 8)):
+        for w in (w_qkv, w_o, w_gate_up, w_down):
+            _dev(w, torch.uint8)
+        for g in (gamma_attn, gamma_ffn):
+            _dev(g, torch.float16)
+            assert g.shape == (H,)
+        self.tensors = (w_qkv, w_o, w_gate_up, w_down, gamma_attn, gamma_ffn)
+        self.H, self.F, self.QKV, self.group = H, F, QKV, group
+        self.c = _Layer(H, F, QKV, group, w_qkv.data_ptr(), w_o.data_ptr(), w_gate_up.data_ptr(),
+                        w_down.data_ptr(), gamma_attn.data_ptr(), gamma_ffn.data_ptr(), float(eps), *bits)
+
+    def workspace_bytes(self, M):
+        return load().flexq_layer_workspace_bytes(ctypes.byref(self.c), M)
+
+    def make_workspace(self, M, device="cuda"):
+        nbytes = self.workspace_bytes(M)
+        if nbytes == 0:
+            raise FlexQError("flexq: invalid layer shape for workspace")
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        _check(load().flexq_workspace_init(_ptr(ws), nbytes, _stream()))
+        return ws
+
+
+def layer_linears(layer, M, workspace, first_stage=0, last_stage=3, **buffers):
+    """flexq_layer_linears: `buffers` are the fp16 tensors of flexq_layer_io by name (x, qkv, attn,
+    o, x_ffn, gate_up, down, and the optional h_attn_norm, h_ffn_norm, h_swiglu); only those the
+    requested stages touch are needed."""
+    shapes = dict(x=layer.H, qkv=layer.QKV, attn=layer.H, o=layer.H, x_ffn=layer.H, gate_up=2 * layer.F,
+                  down=layer.H, h_attn_norm=layer.H, h_ffn_norm=layer.H, h_swiglu=layer.F)
+    io = _LayerIO()
+    for name, t in buffers.items():
+        _dev(t, torch.float16)
+        assert t.shape == (M, shapes[name]), (name, tuple(t.shape))
+        setattr(io, name, t.data_ptr())
+    _check(load().flexq_layer_linears(ctypes.byref(layer.c), M, ctypes.byref(io), first_stage, last_stage,
+                                      _ptr(workspace), workspace.numel(), _stream()))

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexq.so")
 DEV_LIB = os.path.join(HERE, "libflexq_dev.so")
-SOURCES = ["quant_pack.hip", "producers.hip", "skinny.hip", "gemm.hip", "gemm_wlds.hip", "noalloc.hip",
+SOURCES = ["quant_pack.hip", "producers.hip", "skinny.hip", "gemm.hip", "gemm_wlds.hip", "layer.hip", "noalloc.hip",
            "api.hip"]
 DEV_SOURCES = SOURCES + ["probes.hip", "dev_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fvisibility=hidden",

@@ -189,6 +189,49 @@ def test_noalloc_entry_point_argument_errors():
     assert call(M=1024, N=8192, K=8192) == -5
 
 
+def test_layer_runner_argument_errors():
+    """flexq_layer_linears checks every requested stage's arguments on the host first."""
+    from paper_2508_04405_amd.binding import _Layer, _LayerIO
+    lib = fq.load()
+    p = 0x1000
+
+    def layer(**kw):
+        a = dict(H=256, F=512, QKV=768, group=0, w_qkv=p, w_o=p, w_gate_up=p, w_down=p, gamma_attn=p,
+                 gamma_ffn=p, eps=1e-5, bits_qkv=6, bits_o=6, bits_gate_up=6, bits_down=8)
+        a.update(kw)
+        return _Layer(**a)
+
+    def io(**kw):
+        a = dict(x=p, qkv=p, attn=p, o=p, x_ffn=p, gate_up=p, down=p)
+        a.update(kw)
+        return _LayerIO(**a)
+
+    def call(L, M=4, buffers=None, first=0, last=3, ws=P16, wsb=1 << 30):
+        return lib.flexq_layer_linears(ctypes.byref(L), M, ctypes.byref(buffers or io()), first, last, ws, wsb,
+                                       None)
+
+    need = lib.flexq_layer_workspace_bytes(ctypes.byref(layer()), 4)
+    # the widest GEMM workspace, then the quantized input of a stage: codes [M, max(H, F)], scales [M]
+    assert need == max(lib.flexq_workspace_bytes(4, n, k)
+                       for n, k in ((768, 256), (256, 256), (1024, 256), (256, 512))) + 4 * 512 + 256
+    assert lib.flexq_layer_workspace_bytes(ctypes.byref(layer(H=200)), 4) == 0
+    assert call(layer(), M=0) == -1
+    assert call(layer(), first=2, last=1) == -1
+    assert call(layer(), last=4) == -1
+    assert call(layer(bits_down=7)) == -1
+    assert call(layer(group=64)) == -1
+    assert call(layer(eps=0.0)) == -1
+    assert call(layer(H=200)) == -2
+    assert call(layer(w_down=None)) == -1
+    assert call(layer(), buffers=io(attn=None)) == -1
+    assert call(layer(), buffers=io(attn=None), first=0, last=0, wsb=16) == -5   # attn not needed for stage 0
+    assert call(layer(), buffers=io(x=0x1008)) == -3
+    assert call(layer(), buffers=io(h_swiglu=0x1008)) == -3
+    assert call(layer(), ws=None) == -5
+    assert call(layer(), wsb=need - 1) == -5
+    assert call(layer(), ws=ODD) == -3
+
+
 def test_dev_entry_points_argument_errors():
     d = dev.load()
     assert d.flexq_dev_probe_hbm_read(None, 4096, P16, None) == -1

@@ -128,7 +128,7 @@ def sweep(args, torch, fq, fqdev, synth, dev):
         for i, (name, K, N, bits) in enumerate(LAYERS):
             us = sorted(a.elapsed_time(b) * 1e3 for a, b in times[i])[len(times[i]) // 2]
             kern, splits = kinds[i]
-            label = {1: "s", 5: "h", 7: "a", 8: "b", 12: "c", 13: "p"}.get(kern, "?")
+            label = {1: "s", 5: "h", 7: "a", 8: "b", 12: "c", 13: "p", 14: "t"}.get(kern, "?")
             if splits > 1:
                 label += str(splits)
             cells.append("%.1f %s (%.0f, %.0f)" % (us, label, 2.0 * M * N * K / us / 1e6,
@@ -262,6 +262,56 @@ def stack13b(args, torch, fq, fqdev, synth, dev):
         del xs, attns
 
 
+def probe_table(args, torch, fq, fqdev, synth, dev):
+    """Decode GEMV against a kernel that only reads the same packed buffer (the development
+    library's read probe), layer by layer, the four layers cycled so that every launch streams from
+    HBM: how much of a layer's time is the weight stream itself, launch, ramp-up and drain
+    included."""
+    packs = []
+    for name, K, N, bits in LAYERS:
+        packed = torch.randint(0, 256, (fq.packed_bytes(N, K, 0),), dtype=torch.uint8, device=dev)
+        sw = (torch.rand(N, device=dev) * 1e-3 + 1e-4).half()
+        packed[N * K * 6 // 8: N * K * 6 // 8 + 2 * N] = sw.view(torch.uint8)
+        packs.append(packed)
+    sink = torch.zeros(16, dtype=torch.int32, device=dev)
+    print("| M | layer | packed MB | read probe us (GB/s) | GEMV us (GB/s) | GEMV / probe |")
+    print("|---|---|---|---|---|---|")
+    for M in (1, 16):
+        bufs = []
+        for name, K, N, bits in LAYERS:
+            xq = torch.randint(-31, 32, (M, K), dtype=torch.int8, device=dev)
+            sx = torch.ones(M, dtype=torch.float16, device=dev)
+            bufs.append((xq, sx, torch.empty((M, N), dtype=torch.float16, device=dev),
+                         fq.make_workspace(M, N, K, dev)))
+        tp = [[] for _ in LAYERS]
+        tg = [[] for _ in LAYERS]
+        for rep in range(args.warmup + args.steps):
+            for i, (name, K, N, bits) in enumerate(LAYERS):
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fqdev.probe_hbm_read(packs[i], sink)
+                e1.record()
+                if rep >= args.warmup:
+                    tp[i].append((e0, e1))
+            for i, (name, K, N, bits) in enumerate(LAYERS):
+                xq, sx, y, ws = bufs[i]
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                (fq.gemv_w6a6 if bits == 6 else fq.gemv_w6a8)(packs[i], N, K, 0, xq=xq, sx=sx, workspace=ws, out=y)
+                e1.record()
+                if rep >= args.warmup:
+                    tg[i].append((e0, e1))
+        torch.cuda.synchronize()
+        med = lambda t: sorted(a.elapsed_time(b) * 1e3 for a, b in t)[len(t) // 2]
+        for i, (name, K, N, bits) in enumerate(LAYERS):
+            mb = packs[i].numel() / 1e6
+            p_us, g_us = med(tp[i]), med(tg[i])
+            print("| %d | %s | %.1f | %.1f (%.0f) | %.1f (%.0f) | %.2f |" %
+                  (M, name, mb, p_us, mb / p_us * 1e3, g_us, mb / g_us * 1e3, g_us / p_us), flush=True)
+
+
 def ablation(args, torch, fq, fqdev, synth, dev):
     """GEMV time with one design choice of the streaming kernel undone per row (the paper's
     Table 6 on this machine).  Each shape is replicated until the copies exceed twice the
@@ -356,6 +406,9 @@ def main():
                     help="instead of the benchmark line, print the time of one decoder layer's "
                          "seven linears (four GEMM calls fed by the fused producers) for the "
                          "LLaMA-2 7B / 13B / 70B shapes")
+    ap.add_argument("--probe", action="store_true",
+                    help="instead of the benchmark line, print the decode GEMV against a read-only kernel "
+                         "over the same packed buffers, per layer, at M = 1 and 16")
     ap.add_argument("--stack13b", action="store_true",
                     help="instead of the benchmark line, print the aggregate time of the LLaMA-2-13B-shaped "
                          "40-layer linear stack (group-128 weight scales, a seeded quarter of the layers at "
@@ -406,6 +459,8 @@ def main():
         return layer_table(args, torch, fq, fqdev, synth, dev)
     if args.stack13b:
         return stack13b(args, torch, fq, fqdev, synth, dev)
+    if args.probe:
+        return probe_table(args, torch, fq, fqdev, synth, dev)
 
     # ---- resident inputs: packed weights, fp16 activations -----------------
     gen = torch.Generator(device=dev)
@@ -480,37 +535,6 @@ def main():
         t1 = time.perf_counter()
         return (t1 - t0) / args.steps, events
 
-    def timed_graph(enqueue_step):
-        """The same for a launch-bound step: its launches are captured once in a HIP graph
-        (the calls only enqueue kernels: no allocation, no memset) and the graph is replayed,
-        so the step is not bounded by the host's launch rate.  Returns seconds per step by
-        the host clock between synchronizations, and by HIP events on the replay stream."""
-        stream = torch.cuda.Stream()
-        stream.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(stream):
-            enqueue_step()
-            torch.cuda.synchronize()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=stream):
-                enqueue_step()
-            t_roll = time.perf_counter()
-            while time.perf_counter() - t_roll < 0.05:
-                graph.replay()
-                torch.cuda.synchronize()
-            for _ in range(args.warmup):
-                graph.replay()
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            e0.record()
-            for _ in range(args.steps):
-                graph.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-        return (t1 - t0) / args.steps, e0.elapsed_time(e1) * 1e-3 / args.steps
-
     # ---- prefill: the headline ------------------------------------------------
     Mp = args.prefill_m
     step_s, events = timed("prefill", True)
@@ -539,12 +563,11 @@ def main():
     # ---- decode: weight-streaming GEMV ---------------------------------------
     Md = args.decode_m
 
-    def decode_step():
-        for layer in layers:
-            run_layer(layer, "decode")
-    dstep_s, _ = timed_graph(decode_step)
+    dstep_s, _ = timed("decode", False)
     dbytes = sum(algorithmic_bytes(Md, L["N"], L["K"]) for L in layers)
-    # kernel-only rate: the same four GEMV launches back to back, no quantize pass
+    # kernel-only rate: the same four GEMV launches back to back, no quantize pass, one event pair
+    # (eager launches: replaying them as a HIP graph was measured 3-4 % slower -- graph nodes start
+    # strictly after one another, eager launches on one stream overlap their ramp-up and drain)
     for layer in layers:
         b = layer["decode"]
         fq.quant_act(b["x"], layer["bits"], out=(b["xq"], b["sx"]))
@@ -555,7 +578,17 @@ def main():
             (fq.gemv_w6a6 if layer["bits"] == 6 else fq.gemv_w6a8)(
                 layer["packed"], layer["N"], layer["K"], 0, xq=b["xq"], sx=b["sx"],
                 workspace=b["ws"], out=b["y"])
-    _, gemv_s = timed_graph(gemv_step)
+    for _ in range(args.warmup):
+        gemv_step()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        gemv_step()
+    e1.record()
+    torch.cuda.synchronize()
+    gemv_s = e0.elapsed_time(e1) * 1e-3 / args.steps
     gbytes = sum(gemm_bytes(Md, L["N"], L["K"]) for L in layers)
     roofline_decode = {
         "bound": "hbm", "kernel": "skinny_kernel (streaming GEMV, M=%d)" % Md,
@@ -635,8 +668,7 @@ def main():
                    "prefill_tokens": Mp, "decode_tokens": Md},
         "decode": {"value": round(dbytes / dstep_s / 1e9, 1), "unit": "GB/s",
                    "us_per_step": round(dstep_s * 1e6, 2),
-                   "note": "algorithmic bytes of quantize + GEMV for the four layers / step time; the "
-                           "step's launches are captured in a HIP graph and replayed"},
+                   "note": "algorithmic bytes of quantize + GEMV for the four layers / step time"},
         "roofline": roofline, "roofline_decode": roofline_decode, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

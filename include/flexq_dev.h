@@ -34,9 +34,12 @@ extern "C" {
  *                once in LDS
  *             (per-channel scales, M <= 32, pre-quantized activations, waves = 8;
  *             other calls return FLEXQ_EHIP while a choice is set)
+ *   fuse      the activation-quantize prologue inside the streaming kernel (fp16 in):
+ *             1 = whenever the kernel can (up to 8 tokens whose K range fits LDS; the
+ *             library's own choice is one token), 2 = never (a quantize launch first)
  */
 typedef struct {
-    int kernel, split_k, waves, gemm_cfg, ablate;
+    int kernel, split_k, waves, gemm_cfg, ablate, fuse;
 } flexq_dev_tuning;
 
 /*
@@ -46,9 +49,10 @@ typedef struct {
  * field out of range -> FLEXQ_EINVAL before anything else happens.  *dispatched
  * (may be NULL) receives what was launched: 1000 * c + s, c = 1 for the streaming
  * kernel, else the tile configuration (5: 64x128, 7: 128x256, 8: 128x128,
- * 12: 256x256 with both operands through LDS, one workgroup per tile,
- * 13: its persistent form), s = the number of K splits (for 13: the number of
- * runs the last, partial round of tiles was cut into).  Results are the same
+ * 12: 256x256 with both operands through LDS, at most one workgroup per CU,
+ * 13: the same with the tiles beyond the last whole round of 256 cut along K,
+ * 14: with those tiles run as 256x128 half tiles), s = the number of K splits
+ * (for 13: the number of runs the tail was cut into; for 14: of half tiles).  Results are the same
  * whatever the overrides.
  */
 flexq_status flexq_dev_linear(const flexq_dev_tuning *tuning, int act_bits, const void *packed,

@@ -208,12 +208,15 @@ flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, i
     if (forced == 1) stream_kernel = true;
     if (forced == 2) stream_kernel = false;
 
-    // Small decode batches: the streaming kernel quantizes the activations itself.
-    // (Each workgroup then scans the token's whole fp16 row, which pays off while a
-    // CU runs only a few workgroups: measured break-even near 1024 workgroups.)
+    // Single-token decode: the streaming kernel quantizes the activations itself.  (Each
+    // workgroup then scans the token's whole fp16 row, which pays off while a CU runs only
+    // a few workgroups -- measured break-even near 1024 workgroups -- and for one token
+    // only: over the four LLaMA-2-70B layers the fused form takes 120 us against 122 us for
+    // quantize launch + GEMV at one token, but 132 against 125 at two and 157 against 131
+    // at eight.  The kernel can do up to eight; tune.fuse = 1 asks for that.)
     const int ks0 = choose_split(M, N, K, tune.split_k);
-    const bool fuse = x_fp16 && stream_kernel && (long)(N / 32) * ks0 <= 1024 &&
-                      flexq::skinny_can_fuse(M, K, ks0);
+    const bool fuse = x_fp16 && stream_kernel && tune.fuse != 2 && flexq::skinny_can_fuse(M, K, ks0) &&
+                      (tune.fuse == 1 || (M == 1 && (long)(N / 32) * ks0 <= 1024));
     if (x_fp16 && !fuse) {
         if (flexq::launch_quant_act(x_fp16, M, K, act_bits, ws.xq, ws.sx, st) != hipSuccess)
             return FLEXQ_EHIP;

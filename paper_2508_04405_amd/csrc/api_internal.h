@@ -13,6 +13,7 @@ struct Tuning {
     int waves = 0;      // wavefronts per workgroup of the streaming kernel: 4, 8, 16
     int gemm_cfg = 0;   // tile configuration of the tiled kernels
     int ablate = 0;     // development build: one design choice of the streaming kernel undone
+    int fuse = 0;       // quantize prologue inside the streaming kernel: 1 = whenever it can, 2 = never
 };
 
 // The argument checks of linear_impl alone (host only, launches nothing).

@@ -18,13 +18,15 @@ flexq_status flexq_dev_linear(const flexq_dev_tuning *tuning, int act_bits, cons
         // every field is checked before any is used
         if (tuning->kernel < 0 || tuning->kernel > 2 || tuning->split_k < 0 || tuning->split_k > 64 ||
             (tuning->waves != 0 && tuning->waves != 4 && tuning->waves != 8 && tuning->waves != 16) ||
-            tuning->gemm_cfg < 0 || tuning->gemm_cfg > 32 || tuning->ablate < 0 || tuning->ablate > 4)
+            tuning->gemm_cfg < 0 || tuning->gemm_cfg > 32 || tuning->ablate < 0 || tuning->ablate > 4 ||
+            tuning->fuse < 0 || tuning->fuse > 2)
             return FLEXQ_EINVAL;
         t.kernel = tuning->kernel;
         t.split_k = tuning->split_k;
         t.waves = tuning->waves;
         t.gemm_cfg = tuning->gemm_cfg;
         t.ablate = tuning->ablate;
+        t.fuse = tuning->fuse;
     }
     if (act_bits != 6 && act_bits != 8) return FLEXQ_EINVAL;
     if (sxg && group != 128) return FLEXQ_EINVAL;

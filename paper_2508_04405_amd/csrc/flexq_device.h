@@ -78,7 +78,11 @@ __device__ __forceinline__ int unpack_kstep_dword(const PackedTile &t, int j, in
     if (j == 0) return t.q0[d] & top6;
     if (j == 1) return t.q1[d] & top6;
     if (j == 2) return t.q2[d] & top6;
-    return ((t.q0[d] & low2) << 6) | ((t.q1[d] & low2) << 4) | ((t.q2[d] & low2) << 2);
+    // three masks, two shift-ors, one shift (six operations; the flat form above takes seven)
+    int r = t.q0[d] & low2;
+    r = (r << 2) | (t.q1[d] & low2);
+    r = (r << 2) | (t.q2[d] & low2);
+    return r << 2;
 }
 
 // D[32x32] += A[32 x 32k] * B[32k x 32], int8 in, int32 out.  Lane l supplies

@@ -18,7 +18,10 @@
 //   activation panel is shared by every column tile of its row and mostly found
 //   in L2 or the Infinity Cache; a third stage would not fit beside the weights),
 //   for half tiles, whose stages are shorter than the memory latency, three,
-//   requested two ahead.  One workgroup per CU, two wavefronts per SIMD.
+//   requested two ahead.  (Two ahead for both operands of whole tiles too, with
+//   two weight buffers and a second barrier per stage that frees a weight stage
+//   as soon as every wavefront has copied it to registers, was measured 3 %
+//   slower on every layer.)  One workgroup per CU, two wavefronts per SIMD.
 //   The hand-over waits until at most the loads for the stage after next are
 //   outstanding.
 //
@@ -174,6 +177,8 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
         unsigned xoff[XDMA];
     };
     auto locate = [&](const Item &it, Where &w) {
+        int lane_l = lane;        // (opaque: recomputed per item rather than kept live, see the epilogue)
+        asm volatile("" : "+v"(lane_l));
         constexpr int SUP_M = 4;  // super-block: 4 tiles along m, then next n
         const int bid = it.t256;
         const int sup = bid / (SUP_M * tiles_n);
@@ -185,8 +190,8 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
 #pragma unroll
         for (int i = 0; i < XDMA; ++i) {
             const int q = wave * XDMA + i;
-            const int row = 8 * q + (lane >> 3);
-            const int c = (lane & 7) ^ ((row >> 1) & 7);
+            const int row = 8 * q + (lane_l >> 3);
+            const int c = (lane_l & 7) ^ ((row >> 1) & 7);
             w.xoff[i] = (unsigned)(w.bm0 + row) * (unsigned)K + 16u * c;
         }
     };
@@ -517,7 +522,12 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
         // lines.  Rows beyond M and column blocks beyond N are never stored.
         if (finish) {
             const int bm0 = at.bm0, bn0 = at.bn0;
-            const int ml = lane & 31, hh = lane >> 5;
+            // (the lane number passes through an opaque statement: what the epilogue derives
+            // from it is recomputed per tile, a handful of operations, instead of being kept
+            // in registers -- or spilled -- across the main loop)
+            int lane_e = lane;
+            asm volatile("" : "+v"(lane_e));
+            const int ml = lane_e & 31, hh = lane_e >> 5;
             const int n_wave = bn0 + wn * NT * 32;
             // (kept as packed fp16 and converted where used: sixteen registers, not thirty-two)
             uint2 sw4[NT][4];
@@ -539,7 +549,7 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             uint8_t *stg = lds + S::STG + wave * (32 * S::ESTRIDE);
             constexpr int LPR = NT * 4;                 // lanes per staged row, 16 bytes (8 channels) each
             constexpr int RPI = 64 / LPR;               // rows per read instruction
-            const int erow = lane / LPR, echunk = lane % LPR;
+            const int erow = lane_e / LPR, echunk = lane_e % LPR;
             const bool ecvalid = n_wave + echunk * 8 < N;
             // the output as a buffer from this wavefront's corner: a lane's offset is fixed,
             // the row offset is an SGPR

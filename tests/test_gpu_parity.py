@@ -352,15 +352,20 @@ def test_quantize_prologue(bits, M):
         x[M - 1, :] = 0                          # a token of zeros: scale 1.0, zero output
     ref = oracle.linear(x, w, bits)
     fn = {6: dev.gemm_w6a6, 8: dev.gemm_w6a8}[bits]
-    for split in (0, 2):                         # M <= 8: quantized inside the streaming kernel
-        dev.set_dispatch(0, split, 0, 0)
-        try:
-            y, acc = fn(packed, N, K, 0, x_fp16=to_dev(x), want_acc=True)
-            torch.cuda.synchronize()
-        finally:
-            dev.set_dispatch(0, 0, 0, 0)
-        assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
-        assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
+    # the library's own choice (inside the streaming kernel for one token, a quantize launch
+    # otherwise), then forced inside the kernel (it can, up to 8 tokens), then forced outside
+    for fuse in (0, 1, 2):
+        for split in (0, 2):
+            dev.set_dispatch(0, split, 0, 0)
+            dev.set_fuse(fuse)
+            try:
+                y, acc = fn(packed, N, K, 0, x_fp16=to_dev(x), want_acc=True)
+                torch.cuda.synchronize()
+            finally:
+                dev.set_dispatch(0, 0, 0, 0)
+                dev.set_fuse(0)
+            assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
+            assert_y_close(y.cpu().numpy().view(np.float16), ref["y"])
     # the two activation widths really differ
     other = oracle.linear(x, w, 14 - bits)
     assert not np.array_equal(other["acc"], ref["acc"])

@@ -312,6 +312,59 @@ def probe_table(args, torch, fq, fqdev, synth, dev):
                   (M, name, mb, p_us, mb / p_us * 1e3, g_us, mb / g_us * 1e3, g_us / p_us), flush=True)
 
 
+def tiles_table(args, torch, fq, fqdev, synth, dev):
+    """Batched decode from fp16 activations, per layer and token count: the quantizer writing
+    row-major int8 codes against the quantizer writing tile order (6-bit activations packed at
+    0.75 byte per value), each followed by the streaming kernel; and what the library picks by
+    itself.  Each figure is the whole call (quantize launch + GEMV), the four layers cycled so
+    that the weights stream from HBM."""
+    packs = []
+    for name, K, N, bits in LAYERS:
+        packed = torch.randint(0, 256, (fq.packed_bytes(N, K, 0),), dtype=torch.uint8, device=dev)
+        sw = (torch.rand(N, device=dev) * 1e-3 + 1e-4).half()
+        packed[N * K * 6 // 8: N * K * 6 // 8 + 2 * N] = sw.view(torch.uint8)
+        packs.append(packed)
+    print("| M | layer | activations | row-major codes us | tile order us | library's choice us (kernel) |")
+    print("|---|---|---|---|---|---|")
+    for M in (4, 8, 12, 16, 20, 24, 28, 32):
+        bufs = []
+        for i, (name, K, N, bits) in enumerate(LAYERS):
+            x = torch.from_numpy(synth.activations(M, K, seed=3001 + 10 * i, outlier_frac=0.01)).to(dev)
+            bufs.append((x, torch.empty((M, N), dtype=torch.float16, device=dev), fq.make_workspace(M, N, K, dev)))
+        res = {}
+        for mode in (2, 1, 0):
+            fqdev.set_tiles(mode)
+            times = [[] for _ in LAYERS]
+
+            def cycle(record):
+                for i, (name, K, N, bits) in enumerate(LAYERS):
+                    x, y, ws = bufs[i]
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    (fqdev.gemv_w6a6 if bits == 6 else fqdev.gemv_w6a8)(packs[i], N, K, 0, x_fp16=x, workspace=ws, out=y)
+                    e1.record()
+                    if record:
+                        times[i].append((e0, e1, fqdev.last_dispatch()))
+
+            t_start = time.perf_counter()
+            while time.perf_counter() - t_start < 0.05:     # the clock settles under load
+                cycle(False)
+                torch.cuda.synchronize()
+            for _ in range(args.warmup):
+                cycle(False)
+            for _ in range(args.steps):                      # back to back, as a decode loop issues them
+                cycle(True)
+            torch.cuda.synchronize()
+            res[mode] = [(sorted(a.elapsed_time(b) * 1e3 for a, b, _ in t)[len(t) // 2], t[0][2]) for t in times]
+        fqdev.set_tiles(0)
+        for i, (name, K, N, bits) in enumerate(LAYERS):
+            kern, code = res[0][i][1]
+            what = ("streaming, tiles" if code >= 500 else "streaming, rows") if kern == 1 else "64x128 tiles GEMM"
+            print("| %d | %s | A%d | %.1f | %.1f | %.1f (%s) |" %
+                  (M, name, bits, res[2][i][0], res[1][i][0], res[0][i][0], what), flush=True)
+
+
 def ablation(args, torch, fq, fqdev, synth, dev):
     """GEMV time with one design choice of the streaming kernel undone per row (the paper's
     Table 6 on this machine).  Each shape is replicated until the copies exceed twice the
@@ -409,6 +462,9 @@ def main():
     ap.add_argument("--probe", action="store_true",
                     help="instead of the benchmark line, print the decode GEMV against a read-only kernel "
                          "over the same packed buffers, per layer, at M = 1 and 16")
+    ap.add_argument("--tiles", action="store_true",
+                    help="instead of the benchmark line, print batched decode (4 to 32 tokens, fp16 in) with the "
+                         "quantized activations row-major against in tile order (6-bit ones packed)")
     ap.add_argument("--stack13b", action="store_true",
                     help="instead of the benchmark line, print the aggregate time of the LLaMA-2-13B-shaped "
                          "40-layer linear stack (group-128 weight scales, a seeded quarter of the layers at "
@@ -461,6 +517,8 @@ def main():
         return stack13b(args, torch, fq, fqdev, synth, dev)
     if args.probe:
         return probe_table(args, torch, fq, fqdev, synth, dev)
+    if args.tiles:
+        return tiles_table(args, torch, fq, fqdev, synth, dev)
 
     # ---- resident inputs: packed weights, fp16 activations -----------------
     gen = torch.Generator(device=dev)

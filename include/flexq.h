@@ -138,7 +138,8 @@ flexq_status flexq_swiglu_quant(const uint16_t *gate_up, int M, int F,
 /*
  * Bytes of workspace the GEMM / GEMV entry points need for (M,N,K): room for
  * split-K partial sums and their arrival counters, and for the quantized
- * activations when the quantize prologue is requested.  Never 0 for a valid
+ * activations when the quantize prologue is requested (M * K bytes, 32 * K for
+ * fewer than 32 tokens: one block of tiles).  Never 0 for a valid
  * shape.  For M > 128, when the 256x256 output tiles do not come in a multiple
  * of 256 (the CUs of an MI355X), it includes up to 128 MiB (512 KiB per 128-k
  * stage of those tiles, at most 256 of them) in which the workgroups sharing a
@@ -200,6 +201,44 @@ flexq_status flexq_gemv_w6a8(const void *packed, int group, const int8_t *xq,
                              int N, int K, uint16_t *y, int32_t *acc_out,
                              void *workspace, size_t workspace_bytes,
                              void *stream);
+
+/*
+ * Activations quantized straight into TILE ORDER for batched decode (Section
+ * 4.3.1 packs the activations online too; Section 5.2's batch sizes).  The
+ * quantizer of flexq_quant_act, same codes and scales, but the codes leave in
+ * tiles of 32 tokens x 128 k laid out the way the streaming kernel's lanes
+ * consume them: act_bits 8 as four 1 KiB planes of int8 (4096 bytes a tile),
+ * act_bits 6 PACKED at 6 bits in the three-plane format of the weight tiles
+ * with tokens in the place of output channels (3072 bytes a tile, 0.75 byte per
+ * value).  Tile (mb, kb) -- tokens 32 mb .., k 128 kb .. -- lies at
+ * (mb * K/128 + kb) * tile bytes; rows of the last block beyond M are never
+ * written and never used.
+ *   flexq_act_tiles_bytes  size of that buffer, 0 for an invalid shape
+ *   flexq_quant_act_tiles  x dev fp16 [M,K] -> xt (dev, out, 16-byte aligned), sx dev fp16 [M]
+ *   flexq_untile_act       xt -> xq dev int8 [M,K] row-major (for checks and for
+ *                          callers that need the codes elsewhere)
+ *   flexq_gemv_tiles       the linear layer of flexq_gemv_w6a6 / _w6a8 (act_bits
+ *                          says which) on such activations: M <= 32 (else
+ *                          FLEXQ_EINVAL), per-channel or group-128 weight scales,
+ *                          same y / acc_out / workspace contract.
+ * What it is for: beyond eight tokens the activations of an 8192-deep layer no
+ * longer fit the kernel's LDS staging, and from row-major codes every lane then
+ * fetches a scattered 128-byte line per token and k-step; from tiles it is
+ * three or four coalesced KiB per tile, whatever the token count (a tile always
+ * carries 32 token rows).  Measured break-even: about 17 tokens (6-bit), 24
+ * (8-bit); the calls that take x_fp16 go this way by themselves from there on,
+ * and below it the row-major calls are the faster ones.
+ */
+size_t flexq_act_tiles_bytes(int act_bits, int M, int K);
+flexq_status flexq_quant_act_tiles(const uint16_t *x, int M, int K, int act_bits,
+                                   void *xt, uint16_t *sx, void *stream);
+flexq_status flexq_untile_act(const void *xt, int M, int K, int act_bits,
+                              int8_t *xq, void *stream);
+flexq_status flexq_gemv_tiles(int act_bits, const void *packed, int group,
+                              const void *xt, const uint16_t *sx, int M, int N,
+                              int K, uint16_t *y, int32_t *acc_out,
+                              void *workspace, size_t workspace_bytes,
+                              void *stream);
 
 /*
  * The paper's full scheme (Section 4.1.1, Eq. 7): BOTH operands carry one fp16

@@ -37,9 +37,13 @@ extern "C" {
  *   fuse      the activation-quantize prologue inside the streaming kernel (fp16 in):
  *             1 = whenever the kernel can (up to 8 tokens whose K range fits LDS; the
  *             library's own choice is one token), 2 = never (a quantize launch first)
+ *   tiles     fp16 activations of up to 32 tokens quantized into tile order (packed at 6
+ *             bits for act_bits 6) for the streaming kernel: 1 = always, 2 = never (the
+ *             library's own choice: 17 to 32 tokens, 24 to 32 with 8-bit activations,
+ *             whose activation slice does not fit the kernel's LDS staging)
  */
 typedef struct {
-    int kernel, split_k, waves, gemm_cfg, ablate, fuse;
+    int kernel, split_k, waves, gemm_cfg, ablate, fuse, tiles;
 } flexq_dev_tuning;
 
 /*
@@ -52,7 +56,8 @@ typedef struct {
  * 12: 256x256 with both operands through LDS, at most one workgroup per CU,
  * 13: the same with the tiles beyond the last whole round of 256 cut along K,
  * 14: with those tiles run as 256x128 half tiles), s = the number of K splits
- * (for 13: the number of runs the tail was cut into; for 14: of half tiles).  Results are the same
+ * (for 13: the number of runs the tail was cut into; for 14: of half tiles; 500 more
+ * when the streaming kernel read its activations in tile order).  Results are the same
  * whatever the overrides.
  */
 flexq_status flexq_dev_linear(const flexq_dev_tuning *tuning, int act_bits, const void *packed,

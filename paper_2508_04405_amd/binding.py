@@ -56,6 +56,14 @@ def load():
     lib.flexq_unpack_w6.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
     lib.flexq_quant_act.restype = c_int
     lib.flexq_quant_act.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
+    lib.flexq_act_tiles_bytes.restype = ctypes.c_size_t
+    lib.flexq_act_tiles_bytes.argtypes = [c_int, c_int, c_int]
+    lib.flexq_quant_act_tiles.restype = c_int
+    lib.flexq_quant_act_tiles.argtypes = [vp, c_int, c_int, c_int, vp, vp, vp]
+    lib.flexq_untile_act.restype = c_int
+    lib.flexq_untile_act.argtypes = [vp, c_int, c_int, c_int, vp, vp]
+    lib.flexq_gemv_tiles.restype = c_int
+    lib.flexq_gemv_tiles.argtypes = [c_int, vp, c_int, vp, vp, c_int, c_int, c_int, vp, vp, vp, ctypes.c_size_t, vp]
     lib.flexq_quant_act_g128.restype = c_int
     lib.flexq_quant_act_g128.argtypes = [vp, c_int, c_int, c_int, vp, vp, c_int, vp]
     lib.flexq_linear_g128.restype = c_int
@@ -157,6 +165,49 @@ def quant_act(x, act_bits, out=None):
         sx = torch.empty((M,), dtype=torch.float16, device=x.device)
     _check(lib.flexq_quant_act(_ptr(x), M, K, act_bits, _ptr(xq), _ptr(sx), _stream()))
     return xq, sx
+
+
+def quant_act_tiles(x, act_bits, out=None):
+    """fp16 X[M,K] -> (activations in tile order, uint8 [flexq_act_tiles_bytes], fp16 scales [M])."""
+    lib = load()
+    _dev(x, torch.float16)
+    M, K = x.shape
+    nbytes = lib.flexq_act_tiles_bytes(act_bits, M, K)
+    if nbytes == 0:
+        raise FlexQError("flexq: invalid shape for activation tiles")
+    if out is not None:
+        xt, sx = _dev(out[0], torch.uint8), _dev(out[1], torch.float16)
+        assert xt.numel() >= nbytes and sx.shape == (M,)
+    else:
+        xt = torch.empty(nbytes, dtype=torch.uint8, device=x.device)
+        sx = torch.empty((M,), dtype=torch.float16, device=x.device)
+    _check(lib.flexq_quant_act_tiles(_ptr(x), M, K, act_bits, _ptr(xt), _ptr(sx), _stream()))
+    return xt, sx
+
+
+def untile_act(xt, M, K, act_bits):
+    """Activations in tile order -> int8 codes [M,K] row-major."""
+    lib = load()
+    _dev(xt, torch.uint8)
+    xq = torch.empty((M, K), dtype=torch.int8, device=xt.device)
+    _check(lib.flexq_untile_act(_ptr(xt), M, K, act_bits, _ptr(xq), _stream()))
+    return xq
+
+
+def gemv_tiles(act_bits, packed, N, K, group, xt, sx, workspace=None, want_acc=False, out=None):
+    """The linear layer on activations in tile order (quant_act_tiles), M <= 32."""
+    lib = load()
+    _dev(packed, torch.uint8)
+    _dev(xt, torch.uint8)
+    _dev(sx, torch.float16)
+    M, dev = sx.shape[0], sx.device
+    if workspace is None:
+        workspace = make_workspace(M, N, K, dev)
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=dev)
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    _check(lib.flexq_gemv_tiles(act_bits, _ptr(packed), group, _ptr(xt), _ptr(sx), M, N, K, _ptr(y), _ptr(acc),
+                                _ptr(workspace), workspace.numel(), _stream()))
+    return (y, acc) if want_acc else y
 
 
 def _producer_out(M, L, device, want_h, out):

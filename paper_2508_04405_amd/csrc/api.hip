@@ -107,9 +107,17 @@ struct Workspace {
     size_t partial_capacity;  // bytes
 };
 
+// quantized activations of the prologue: row-major, or (up to 32 tokens) one block of tiles
+size_t xq_bytes(int M, int K) { return round_up((size_t)(M < 32 ? 32 : M) * K, 256); }
+
 size_t fixed_bytes(int M, int K)
 {
-    return FLEXQ_WORKSPACE_COUNTER_BYTES + round_up((size_t)M * K, 256) + round_up((size_t)M * 2, 256);
+    return FLEXQ_WORKSPACE_COUNTER_BYTES + xq_bytes(M, K) + round_up((size_t)M * 2, 256);
+}
+
+size_t act_tiles_bytes(int act_bits, int M, int K)
+{
+    return (size_t)((M + 31) / 32) * (K / 128) * (act_bits == 6 ? 3072 : 4096);
 }
 
 Workspace carve(void *ws, size_t bytes, int M, int K)
@@ -119,7 +127,7 @@ Workspace carve(void *ws, size_t bytes, int M, int K)
     w.counters = (unsigned *)p;
     p += FLEXQ_WORKSPACE_COUNTER_BYTES;
     w.xq = (int8_t *)p;
-    p += round_up((size_t)M * K, 256);
+    p += xq_bytes(M, K);
     w.sx = (uint16_t *)p;
     p += round_up((size_t)M * 2, 256);
     w.partial = p;
@@ -153,6 +161,50 @@ size_t workspace_bytes_for(int M, int N, int K)
 
 namespace flexq {
 
+namespace {
+
+// the tiled kernel addresses both operands with 32-bit buffer offsets
+bool tiled_addressable(int M, int N, int K)
+{
+    return (long)(M + 256) * K < (1L << 32) && (long)N * K / 4 * 3 < (1L << 32);
+}
+
+// Measured cross-over between the streaming kernel and the tiled kernel with K splits:
+// the streaming kernel re-reads the activations once per 32 output channels (and past
+// 32 tokens needs a second MFMA row tile), while the tiled kernel's time stays flat up
+// to 128 tokens but carries the fixed cost of its K splits on small layers.  So: up to
+// 32 tokens stream (24 on very wide layers: the 57344-wide gate+up is 17 % faster tiled
+// at 32), up to 64 on layers of at most 2^25 weights (2^26 with group-wise scales, which
+// have no 64-row tile), up to 128 on layers of at most 2^24 (LLaMA-2-7B's 4096 x 4096:
+// 24 vs 31 us at 128 tokens).
+bool streams_by_choice(int M, int N, int K, int group)
+{
+    const long weights = (long)N * K;
+    return M <= 24 || (M <= 32 && N < 32768) ||
+           (M <= 64 && weights <= (group == 0 ? (1L << 25) : (1L << 26))) ||
+           (M <= 128 && weights <= (1L << 24)) || (M <= 64 && !tiled_addressable(M, N, K));
+}
+
+// Seventeen to 32 tokens (24 to 32 for 8-bit activations) whose slice of the activations
+// does not fit the streaming kernel's LDS staging: the quantizer writes them in tile
+// order (6-bit activations packed like the weights), which the kernel reads with
+// coalesced loads instead of a scattered 128-byte line per token and k-step.  A tile
+// always carries 32 token rows, so the time no longer depends on the token count
+// (measured on the LLaMA-2-70B layers, quantize + GEMV from fp16: 25 / 19 / 46 us on
+// qkv / o / down for any count up to 32, against 30 / 21 / 52 us row-major at 32 tokens
+// and 23 / 17 / 38 us at 16).
+bool tiles_pay(int act_bits, int M, int K, int split_k)
+{
+    return M <= 32 && M >= (act_bits == 6 ? 17 : 24) && !flexq::skinny_slice_fits(M, K, split_k);
+}
+
+}  // namespace
+
+bool linear_wants_tiles(int act_bits, int M, int N, int K, int group)
+{
+    return streams_by_choice(M, N, K, group) && tiles_pay(act_bits, M, K, choose_split(M, N, K));
+}
+
 flexq_status linear_check(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
                           const uint16_t *x_fp16, int M, int N, int K, const uint16_t *y,
                           const int32_t *acc_out, const void *workspace, size_t workspace_bytes,
@@ -178,9 +230,10 @@ flexq_status linear_check(const void *packed, int group, const int8_t *xq, const
 flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, int group,
                          const int8_t *xq, const uint16_t *sx, const uint16_t *x_fp16, int M, int N, int K,
                          uint16_t *y, int32_t *acc_out, void *workspace, size_t workspace_bytes,
-                         void *stream, const uint16_t *sxg, int sxg_stride, int *dispatched)
+                         void *stream, const uint16_t *sxg, int sxg_stride, int *dispatched, int xt)
 {
     if (dispatched) *dispatched = 0;
+    if (xt != 0 && (xt != act_bits || M > 32 || sxg || x_fp16)) return FLEXQ_EINVAL;
     if (flexq_status s = linear_check(packed, group, xq, sx, x_fp16, M, N, K, y, acc_out, workspace,
                                       workspace_bytes, sxg, sxg_stride);
         s != FLEXQ_OK)
@@ -190,23 +243,13 @@ flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, i
     Workspace ws = carve(workspace, workspace_bytes, M, K);
 
     const int forced = tune.kernel;
-    // Measured cross-over between the streaming kernel and the tiled kernel with K splits:
-    // the streaming kernel re-reads the activations once per 32 output channels (and past
-    // 32 tokens needs a second MFMA row tile), while the tiled kernel's time stays flat up
-    // to 128 tokens but carries the fixed cost of its K splits on small layers.  So: up to
-    // 32 tokens stream (24 on very wide layers: the 57344-wide gate+up is 17 % faster tiled
-    // at 32), up to 64 on layers of at most 2^25 weights (2^26 with group-wise scales, which
-    // have no 64-row tile), up to 128 on layers of at most 2^24 (LLaMA-2-7B's 4096 x 4096:
-    // 24 vs 31 us at 128 tokens).
-    const bool tiled_ok = (long)(M + 256) * K < (1L << 32) && (long)N * K / 4 * 3 < (1L << 32);
-    const long weights = (long)N * K;
-    bool stream_kernel = M <= 24 || (M <= 32 && N < 32768) ||
-                         (M <= 64 && weights <= (group == 0 ? (1L << 25) : (1L << 26))) ||
-                         (M <= 128 && weights <= (1L << 24)) || (M <= 64 && !tiled_ok);
+    const bool tiled_ok = tiled_addressable(M, N, K);
+    bool stream_kernel = streams_by_choice(M, N, K, group);
     // group-wise activation scales reach the tiled kernel by 4-byte DMA loads: even stride
     if (sxg && (sxg_stride % 2 != 0 || !tiled_ok)) stream_kernel = true;
     if (forced == 1) stream_kernel = true;
     if (forced == 2) stream_kernel = false;
+    if (xt != 0) stream_kernel = true;
 
     // Single-token decode: the streaming kernel quantizes the activations itself.  (Each
     // workgroup then scans the token's whole fp16 row, which pays off while a CU runs only
@@ -217,8 +260,11 @@ flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, i
     const int ks0 = choose_split(M, N, K, tune.split_k);
     const bool fuse = x_fp16 && stream_kernel && tune.fuse != 2 && flexq::skinny_can_fuse(M, K, ks0) &&
                       (tune.fuse == 1 || (M == 1 && (long)(N / 32) * ks0 <= 1024));
+    if (x_fp16 && !fuse && stream_kernel && M <= 32 && !sxg && tune.tiles != 2 && tune.ablate == 0 &&
+        (tune.tiles == 1 || tiles_pay(act_bits, M, K, ks0)))
+        xt = act_bits;
     if (x_fp16 && !fuse) {
-        if (flexq::launch_quant_act(x_fp16, M, K, act_bits, ws.xq, ws.sx, st) != hipSuccess)
+        if (flexq::launch_quant_act(x_fp16, M, K, act_bits, ws.xq, ws.sx, st, xt) != hipSuccess)
             return FLEXQ_EHIP;
         xq = ws.xq;
         sx = ws.sx;
@@ -238,6 +284,7 @@ flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, i
     a.sxg = nullptr;
     a.sxg_stride = sxg_stride;
     a.ablate = tune.ablate;
+    a.xt = xt;
 
     if (!stream_kernel) {
         // the tiled kernel addresses both operands with 32-bit buffer offsets
@@ -277,7 +324,7 @@ flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, i
         if (a.split_k < 1) a.split_k = 1;
         if (flexq::launch_skinny(a, choose_waves(rows, N, K, a.split_k, tune.waves), st) != hipSuccess)
             return FLEXQ_EHIP;
-        if (dispatched) *dispatched = 1000 + a.split_k;
+        if (dispatched) *dispatched = 1000 + a.split_k + (xt != 0 ? 500 : 0);
     }
     return FLEXQ_OK;
 }
@@ -360,6 +407,46 @@ flexq_status flexq_quant_act(const uint16_t *x, int M, int K, int act_bits, int8
     return flexq::launch_quant_act(x, M, K, act_bits, xq, sx, (hipStream_t)stream) == hipSuccess
                ? FLEXQ_OK
                : FLEXQ_EHIP;
+}
+
+size_t flexq_act_tiles_bytes(int act_bits, int M, int K)
+{
+    if ((act_bits != 6 && act_bits != 8) || M < 1 || K < 1 || K % 128 != 0 || K > FLEXQ_MAX_K) return 0;
+    return act_tiles_bytes(act_bits, M, K);
+}
+
+flexq_status flexq_quant_act_tiles(const uint16_t *x, int M, int K, int act_bits, void *xt, uint16_t *sx,
+                                   void *stream)
+{
+    if (!x || !xt || !sx || M < 1 || K < 1) return FLEXQ_EINVAL;
+    if (act_bits != 6 && act_bits != 8) return FLEXQ_EINVAL;
+    if (K % 128 != 0 || K > FLEXQ_MAX_K) return FLEXQ_ESHAPE;
+    if (!aligned16(x) || !aligned16(xt)) return FLEXQ_EALIGN;
+    return flexq::launch_quant_act(x, M, K, act_bits, (int8_t *)xt, sx, (hipStream_t)stream, act_bits) ==
+                   hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
+flexq_status flexq_untile_act(const void *xt, int M, int K, int act_bits, int8_t *xq, void *stream)
+{
+    if (!xt || !xq || M < 1 || K < 1) return FLEXQ_EINVAL;
+    if (act_bits != 6 && act_bits != 8) return FLEXQ_EINVAL;
+    if (K % 128 != 0 || K > FLEXQ_MAX_K) return FLEXQ_ESHAPE;
+    if (!aligned16(xt) || !aligned16(xq)) return FLEXQ_EALIGN;
+    return flexq::launch_untile_act((const uint8_t *)xt, act_bits, M, K, xq, (hipStream_t)stream) == hipSuccess
+               ? FLEXQ_OK
+               : FLEXQ_EHIP;
+}
+
+flexq_status flexq_gemv_tiles(int act_bits, const void *packed, int group, const void *xt,
+                              const uint16_t *sx, int M, int N, int K, uint16_t *y, int32_t *acc_out,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (act_bits != 6 && act_bits != 8) return FLEXQ_EINVAL;
+    if (M > 32) return FLEXQ_EINVAL;
+    return flexq::linear_impl(kAuto, act_bits, packed, group, (const int8_t *)xt, sx, nullptr, M, N, K, y,
+                              acc_out, workspace, workspace_bytes, stream, nullptr, 0, nullptr, act_bits);
 }
 
 flexq_status flexq_rmsnorm_quant(const uint16_t *x, const uint16_t *gamma, float eps, int M, int K,

@@ -14,6 +14,7 @@ struct Tuning {
     int gemm_cfg = 0;   // tile configuration of the tiled kernels
     int ablate = 0;     // development build: one design choice of the streaming kernel undone
     int fuse = 0;       // quantize prologue inside the streaming kernel: 1 = whenever it can, 2 = never
+    int tiles = 0;      // fp16 activations of up to 32 tokens quantized into tile order: 1 = always, 2 = never
 };
 
 // The argument checks of linear_impl alone (host only, launches nothing).
@@ -29,6 +30,11 @@ flexq_status linear_check(const void *packed, int group, const int8_t *xq, const
 flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, int group,
                          const int8_t *xq, const uint16_t *sx, const uint16_t *x_fp16, int M, int N, int K,
                          uint16_t *y, int32_t *acc_out, void *workspace, size_t workspace_bytes,
-                         void *stream, const uint16_t *sxg, int sxg_stride, int *dispatched);
+                         void *stream, const uint16_t *sxg, int sxg_stride, int *dispatched, int xt = 0);
+// xt = act_bits: `xq` holds the activations in tile order (flexq_quant_act_tiles), M <= 32.
+
+// True where linear_impl, given fp16 activations, quantizes them into tile order: a caller
+// that runs a fused producer itself makes it write tiles then, and passes xt.
+bool linear_wants_tiles(int act_bits, int M, int N, int K, int group);
 
 }  // namespace flexq

@@ -43,7 +43,8 @@ inline int device_cu_count()
 struct LinearArgs {
     const void *packed;      // tiles, then scales
     const uint16_t *scales;  // = packed + N*K*6/8
-    const int8_t *xq;        // [M,K]
+    const int8_t *xq;        // [M,K]; or, with xt != 0, the activations in tile order
+    int xt;                  // 0; or 6 / 8: activation tiles of 3072 / 4096 bytes (streaming kernel, M <= 32)
     const uint16_t *sx;      // [M]
     int M, N, K;
     int group;               // 0 or 128
@@ -62,8 +63,13 @@ struct LinearArgs {
 
 hipError_t launch_quant_w6(const float *w, int N, int K, int group, int8_t *wq, uint16_t *sw,
                            hipStream_t st);
+// `layout` 0 writes the codes row-major; layout == act_bits writes them in tile order for
+// the streaming kernel (tiles of 32 tokens x 128 k: 4096 bytes of int8, or 3072 bytes in
+// the packed 6-bit format of the weights); K must then be a multiple of 128 and the
+// buffer hold ceil(M / 32) * (K / 128) tiles.
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int act_bits, int8_t *xq,
-                            uint16_t *sx, hipStream_t st);
+                            uint16_t *sx, hipStream_t st, int layout = 0);
+hipError_t launch_untile_act(const uint8_t *xt, int act_bits, int M, int K, int8_t *xq, hipStream_t st);
 // Group-wise (128 along K) activation quantizer; sxg is [K/128][stride], group-major.
 hipError_t launch_quant_act_g128(const uint16_t *x, int M, int K, int act_bits, int8_t *xq,
                                  uint16_t *sxg, int stride, hipStream_t st);
@@ -77,14 +83,16 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
 // producer's output) may be null.
 hipError_t launch_rmsnorm_quant(const uint16_t *x, const uint16_t *gamma, float eps, int M, int K,
                                 int act_bits, int8_t *xq, uint16_t *sx, uint16_t *h_out,
-                                hipStream_t st);
+                                hipStream_t st, int layout = 0);
 hipError_t launch_swiglu_quant(const uint16_t *gate_up, int M, int F, int act_bits, int8_t *xq,
-                               uint16_t *sx, uint16_t *h_out, hipStream_t st);
+                               uint16_t *sx, uint16_t *h_out, hipStream_t st, int layout = 0);
 
 // Streaming kernel, M <= 128 per launch (the caller loops over row chunks).
 hipError_t launch_skinny(const LinearArgs &a, int waves, hipStream_t st);
 // True if the streaming kernel can quantize fp16 activations itself for this shape.
 bool skinny_can_fuse(int M, int K, int split_k);
+// True if the streaming kernel stages this shape's activation slice in LDS.
+bool skinny_slice_fits(int M, int K, int split_k);
 // Tiled MFMA kernel for large M.
 // `chosen` (may be null) receives the tile configuration that ran and, for the persistent
 // 256x256 form, the number of runs its tail was cut into.

@@ -59,20 +59,29 @@ constexpr int XSTAGE = BM * 128;               // bytes of one activation stage
 constexpr int XDMA = BM / 8 / WAVES;           // 1 KiB activation DMA loads per wavefront and stage
 constexpr int SLOT_BYTES = BM * 256 * 4;       // one workgroup's int32 sums of a 256x256 tile
 
-// The eight wavefronts share a tile 2 along m (MT = 4 row blocks of 32 each) x 4 along n
-// (NT column blocks of 32 each): NT = 2 is the whole 256x256 tile, NT = 1 the half tile.
-// (A layout of 1 x 8 wavefronts owning 256 x 32 each halves the expansion work per MFMA,
-// an expanded operand then feeding eight of them, for twice the activation reads from
-// LDS: measured 2-5 % slower on every layer.)
-template <int NT>
+// The eight wavefronts share a whole tile 2 along m x 4 along n, 128 x 64 each (MT = 4 row
+// blocks of 32, NT = 2 column blocks of 32: an expanded weight operand feeds four MFMAs,
+// an activation operand two), and a half tile 4 along m x 2 along n, 64 x 64 each.  LDS
+// delivers 128 bytes a clock to the CU and a 32x32x32 MFMA occupies a SIMD for 32, so a
+// stage reads (MT + 0.75 NT) / (MT NT) KiB per MFMA of at most 1 KiB: 0.69 for the whole
+// tile, 0.875 for 64 x 64.  (The whole tile's 128-row layout on half the columns, 128 x 32
+// per wavefront, would ask for 1.19; measured, it runs the half tiles at the same speed --
+// their stages are not bound by LDS reads -- and the lighter shape was kept.  For whole
+// tiles, 1 x 8 wavefronts of 256 x 32 halve the expansion work per MFMA for twice the
+// activation reads: measured 2-5 % slower on every layer.)
+// TILE names the shape: 2 the whole tile, 1 the half tile
+template <int TILE>
 struct Shape {
-    static constexpr int WN = 4;
-    static constexpr int MT = 4;
+    static_assert(TILE == 1 || TILE == 2, "half or whole tiles");
+    static constexpr int WN = TILE == 1 ? 2 : 4;
+    static constexpr int MT = TILE == 1 ? 2 : 4;
+    static constexpr int NT = 2;
     static constexpr int BN = WN * NT * 32;
     static_assert(BN == 256 || BN == 128, "whole or half tiles");
+    static_assert(WAVES / WN * MT * 32 == BM, "the wavefronts cover the tile's rows");
     static constexpr int WTILES = BN / 32;                        // packed tiles per stage
     static constexpr int WSTAGE = WTILES * FLEXQ_TILE_BYTES;
-    static constexpr int XA = NT == 1 ? 2 : 1;                    // activation stages requested ahead
+    static constexpr int XA = BN == 128 ? 2 : 1;                  // activation stages requested ahead
     static constexpr int XBUFS = XA + 1;
     static constexpr int WBASE = XBUFS * XSTAGE;
     // this wavefront's weight DMA loads per stage: plane p of a stage is fetched by
@@ -99,15 +108,15 @@ struct Item {
 };
 
 // One phase of a launch: this workgroup's share of `item_count` items that begin at the
-// 256-wide tile `item_begin` -- whole tiles (NT = 2), half tiles (NT = 1: two items per
-// tile), or, with SK, the stages of `item_count` tiles cut into `tail_wgs` runs.
-template <int NT, bool SK>
+// 256-wide tile `item_begin` -- whole tiles (TILE = 2), half tiles (two items per tile),
+// or, with SK, the stages of `item_count` tiles cut into `tail_wgs` runs.
+template <int TILE, bool SK>
 __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *lds, int &s_last, int tiles_m,
                                           int tiles_n, int item_begin, int item_count, int tail_wgs)
 {
 #if defined(__HIP_DEVICE_COMPILE__)  // buffer-resource builtins exist in the device pass only
-    using S = Shape<NT>;
-    constexpr int MT = S::MT;
+    using S = Shape<TILE>;
+    constexpr int MT = S::MT, NT = S::NT;
     constexpr bool WHOLE = S::BN == 256;
     static_assert(!SK || WHOLE, "the tail is cut in whole-width tiles");
 
@@ -329,8 +338,55 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                         af[0][mt] = *reinterpret_cast<const v4i *>(xn + lds_off(arow + 32 * mt, ahalf));
                 }
             };
-            static_assert(MT == 4 && (NT == 1 || NT == 2), "the step tables below are written for 4 x NT blocks");
-            if constexpr (NT == 2) {
+            static_assert((MT == 4 || MT == 2) && NT == 2, "the step tables below are written for these blockings");
+            if constexpr (MT == 2) {
+                // 64 x 64 per wavefront: eight steps of two MFMAs, two dwords of the next
+                // step's operand expanded per MFMA; the dearer operands of the fourth k-step
+                // (steps 6 and 7) are spread over steps 2..5, one dword per MFMA
+                v4i bfc = bf_first, bf6 = {0, 0, 0, 0}, bf7 = {0, 0, 0, 0};
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    const int j = s >> 1, nt = s & 1;
+                    if (nt == 0) {
+                        if (j < 3) {
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt)
+                                af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
+                                    xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
+                        } else {
+                            hand_over();
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    const v4i cur_b = s == 6 ? bf6 : s == 7 ? bf7 : bfc;
+                    v4i nxt = bfc;
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        acc[mt][nt] = mfma_i8(cur_b, af[j & 1][mt], acc[mt][nt]);
+#pragma unroll
+                        for (int d = 2 * mt; d < 2 * mt + 2; ++d) {
+                            if (s < 5) nxt[d] = unpack_kstep_dword(wreg[(s + 1) & 1], (s + 1) >> 1, d);
+                            if (s == 7) nxt[d] = unpack_kstep_dword(wreg[0], 0, d);   // the next stage's first
+                        }
+                        if (s == 2) bf6[mt] = unpack_kstep_dword(wreg[0], 3, mt);
+                        if (s == 3) bf6[2 + mt] = unpack_kstep_dword(wreg[0], 3, 2 + mt);
+                        if (s == 4) bf7[mt] = unpack_kstep_dword(wreg[1], 3, mt);
+                        if (s == 5) bf7[2 + mt] = unpack_kstep_dword(wreg[1], 3, 2 + mt);
+                        {
+                            int p0 = nxt[2 * mt], p1 = nxt[2 * mt + 1], p2 = bf6[(s & 1) * 2 + mt],
+                                p3 = bf7[(s & 1) * 2 + mt];
+                            asm volatile("" : "+v"(p0), "+v"(p1), "+v"(p2), "+v"(p3));   // pins the expansion here
+                            nxt[2 * mt] = p0;
+                            nxt[2 * mt + 1] = p1;
+                            bf6[(s & 1) * 2 + mt] = p2;
+                            bf7[(s & 1) * 2 + mt] = p3;
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    bfc = nxt;
+                }
+                bf_first = bfc;
+            } else {
                 v4i bfc = bf_first, bf6, bf7;
 #pragma unroll
                 for (int s = 0; s < 8; ++s) {
@@ -362,41 +418,6 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                             nxt[mt] = p0;
                             bf6[mt] = p1;
                             bf7[mt] = p2;
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    bfc = nxt;
-                }
-                bf_first = bfc;
-            } else {
-                // one column tile: step s is k-step s; the operand of k-step s + 1 is expanded
-                // during step s, the next stage's first one at the end of step 3, three MFMAs
-                // after its packed tile was asked from LDS
-                v4i bfc = bf_first;
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    if (s < 3) {
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-                            af[(s + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
-                                xs + lds_off(arow + 32 * mt, 2 * (s + 1) + ahalf));
-                    } else {
-                        hand_over();
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                    v4i nxt = bfc;
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        acc[mt][0] = mfma_i8(bfc, af[s & 1][mt], acc[mt][0]);
-                        if (s < 3) nxt[mt] = unpack_kstep_dword(wreg[0], s + 1, mt);
-                        if (s == 3 && mt == MT - 1) nxt = unpack_kstep(wreg[0], 0);
-                        {
-                            int p0 = nxt[0], p1 = nxt[1], p2 = nxt[2], p3 = nxt[3];
-                            asm volatile("" : "+v"(p0), "+v"(p1), "+v"(p2), "+v"(p3));
-                            nxt[0] = p0;
-                            nxt[1] = p1;
-                            nxt[2] = p2;
-                            nxt[3] = p3;
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -690,7 +711,8 @@ WldsChoice gemm_wlds_choose(int M, int N, int K, bool may_cut)
 
 namespace {
 
-constexpr int kLdsBytes = Shape<2>::LDS_BYTES > Shape<1>::LDS_BYTES ? Shape<2>::LDS_BYTES : Shape<1>::LDS_BYTES;
+constexpr int kLdsBytes = Shape<2>::LDS_BYTES > Shape<1>::LDS_BYTES ? Shape<2>::LDS_BYTES
+                                                                                   : Shape<1>::LDS_BYTES;
 
 template <int FORM>
 hipError_t launch_form(const LinearArgs &a, int tiles_m, int tiles_n, int full_count, int tail_count,

@@ -41,7 +41,8 @@ size_t flexq_layer_workspace_bytes(const flexq_layer *L, int M)
     const size_t g = gemm_ws_bytes(L, M);
     if (g == 0) return 0;
     const int widest = L->H > L->F ? L->H : L->F;
-    return g + round_up((size_t)M * widest, 256) + round_up((size_t)M * 2, 256);
+    // (fewer than 32 tokens: room for one block of 32-token tiles)
+    return g + round_up((size_t)(M < 32 ? 32 : M) * widest, 256) + round_up((size_t)M * 2, 256);
 }
 
 flexq_status flexq_layer_linears(const flexq_layer *L, int M, const flexq_layer_io *io, int first_stage,
@@ -77,35 +78,43 @@ flexq_status flexq_layer_linears(const flexq_layer *L, int M, const flexq_layer_
     uint8_t *p = (uint8_t *)workspace + c.gemm_bytes;
     const int widest = L->H > L->F ? L->H : L->F;
     c.xq = (int8_t *)p;
-    c.sx = (uint16_t *)(p + round_up((size_t)M * widest, 256));
+    c.sx = (uint16_t *)(p + round_up((size_t)(M < 32 ? 32 : M) * widest, 256));
 
     hipStream_t st = (hipStream_t)stream;
     const flexq::Tuning automatic{};
     auto gemm = [&](int bits, const void *w, const int8_t *xq, const uint16_t *sx, const uint16_t *x_fp16,
-                    int N, int K, uint16_t *y) {
+                    int N, int K, uint16_t *y, int xt) {
         return flexq::linear_impl(automatic, bits, w, L->group, xq, sx, x_fp16, M, N, K, y, nullptr, c.gemm,
-                                  c.gemm_bytes, stream, nullptr, 0, nullptr);
+                                  c.gemm_bytes, stream, nullptr, 0, nullptr, xt);
+    };
+    // batches of 17 to 32 tokens: the producers write their codes in tile order (packed at
+    // 6 bits) where the streaming kernel reads them faster that way
+    auto layout = [&](int bits, int N, int K) {
+        return flexq::linear_wants_tiles(bits, M, N, K, L->group) ? bits : 0;
     };
     for (int s = first_stage; s <= last_stage; ++s) {
         flexq_status r = FLEXQ_OK;
         if (s == 0) {            // RMS norm + quantize -> fused QKV
+            const int lay = layout(L->bits_qkv, L->QKV, L->H);
             if (flexq::launch_rmsnorm_quant(io->x, L->gamma_attn, L->eps, M, L->H, L->bits_qkv, c.xq, c.sx,
-                                            io->h_attn_norm, st) != hipSuccess)
+                                            io->h_attn_norm, st, lay) != hipSuccess)
                 return FLEXQ_EHIP;
-            r = gemm(L->bits_qkv, L->w_qkv, c.xq, c.sx, nullptr, L->QKV, L->H, io->qkv);
+            r = gemm(L->bits_qkv, L->w_qkv, c.xq, c.sx, nullptr, L->QKV, L->H, io->qkv, lay);
         } else if (s == 1) {     // quantize node -> attention output projection (fp16 in: decode
                                  // batches quantize inside the streaming kernel)
-            r = gemm(L->bits_o, L->w_o, nullptr, nullptr, io->attn, L->H, L->H, io->o);
+            r = gemm(L->bits_o, L->w_o, nullptr, nullptr, io->attn, L->H, L->H, io->o, 0);
         } else if (s == 2) {     // RMS norm + quantize -> fused gate | up
+            const int lay = layout(L->bits_gate_up, 2 * L->F, L->H);
             if (flexq::launch_rmsnorm_quant(io->x_ffn, L->gamma_ffn, L->eps, M, L->H, L->bits_gate_up, c.xq,
-                                            c.sx, io->h_ffn_norm, st) != hipSuccess)
+                                            c.sx, io->h_ffn_norm, st, lay) != hipSuccess)
                 return FLEXQ_EHIP;
-            r = gemm(L->bits_gate_up, L->w_gate_up, c.xq, c.sx, nullptr, 2 * L->F, L->H, io->gate_up);
+            r = gemm(L->bits_gate_up, L->w_gate_up, c.xq, c.sx, nullptr, 2 * L->F, L->H, io->gate_up, lay);
         } else {                 // SiLU(gate) * up + quantize -> down projection
-            if (flexq::launch_swiglu_quant(io->gate_up, M, L->F, L->bits_down, c.xq, c.sx, io->h_swiglu, st) !=
-                hipSuccess)
+            const int lay = layout(L->bits_down, L->H, L->F);
+            if (flexq::launch_swiglu_quant(io->gate_up, M, L->F, L->bits_down, c.xq, c.sx, io->h_swiglu, st,
+                                           lay) != hipSuccess)
                 return FLEXQ_EHIP;
-            r = gemm(L->bits_down, L->w_down, c.xq, c.sx, nullptr, L->H, L->F, io->down);
+            r = gemm(L->bits_down, L->w_down, c.xq, c.sx, nullptr, L->H, L->F, io->down, lay);
         }
         if (r != FLEXQ_OK) return r;
     }

@@ -19,6 +19,13 @@
 // Short rows take T = 256; long rows take T = 1024 so that a lane holds few
 // chunks and the compute unit stays fully occupied (rows are at most 65536
 // long, eight chunks per lane).
+//
+// The codes leave either row-major ([M][K] int8) or in TILE ORDER for the
+// streaming kernel (Section 4.3.1 packs the activations online as well): tiles of
+// 32 tokens x 128 k in which a lane of the consuming wavefront finds its MFMA
+// operands as contiguous 16-byte pieces -- four 1 KiB planes of int8 (8-bit
+// activations), or the three planes of the 6-bit weight tile format with tokens
+// in the place of output channels (6-bit activations: 0.75 byte per value).
 #include "flexq_device.h"
 #include "flexq_kernels.h"
 
@@ -72,7 +79,7 @@ __global__ __launch_bounds__(T) void producer_kernel(const uint16_t *__restrict_
                                                        float eps, int L, float qmax,
                                                        int8_t *__restrict__ xq,
                                                        uint16_t *__restrict__ sx,
-                                                       uint16_t *__restrict__ h_out)
+                                                       uint16_t *__restrict__ h_out, int layout)
 {
     __shared__ float red[T / 64];
     const long row = blockIdx.x;
@@ -170,8 +177,35 @@ __global__ __launch_bounds__(T) void producer_kernel(const uint16_t *__restrict_
     uint2 *dst = reinterpret_cast<uint2 *>(xq + row * (long)L);
     uint4 *hdst = h_out ? reinterpret_cast<uint4 *>(h_out + row * (long)L) : nullptr;
     const float rf = 1.0f / sf;
+    // Tile order (layout 6 or 8): chunk c holds the token's codes for k = 8c .. 8c+7, that
+    // is k-step j = (c % 16) / 4, k-half h = (c % 16) / 2 % 2 of tile c / 16, first or second
+    // eight of the lane's sixteen.  The sixteen chunks of a tile sit in sixteen consecutive
+    // lanes (L is a multiple of 128 here), so the 6-bit form fetches the fourth k-step's
+    // codes, whose bits it spreads over the low bits of the other three, by a shuffle.
+    uint8_t *tiles = reinterpret_cast<uint8_t *>(xq);
+    const int lane = threadIdx.x & 63;
     auto emit = [&](const uint4 &v, int c) {
-        dst[c] = quant8(v, sf, rf, qmin, qmax);
+        const uint2 q = quant8(v, sf, rf, qmin, qmax);
+        if (layout == 0) {
+            dst[c] = q;
+        } else {
+            const int cc = c & 15, j = cc >> 2;
+            const long tile = (row >> 5) * (long)(L >> 7) + (c >> 4);
+            const int in_plane = (32 * ((cc >> 1) & 1) + (int)(row & 31)) * 16 + 8 * (cc & 1);
+            if (layout == 8) {
+                *reinterpret_cast<uint2 *>(tiles + tile * 4096 + j * 1024 + in_plane) = q;
+            } else {
+                const int src = (lane & ~15) | 12 | (cc & 3);
+                const unsigned x3 = (unsigned)__shfl((int)q.x, src, 64), y3 = (unsigned)__shfl((int)q.y, src, 64);
+                if (j < 3) {
+                    const int sh = 4 - 2 * j;
+                    uint2 o;
+                    o.x = ((q.x << 2) & 0xFCFCFCFCu) | ((x3 >> sh) & 0x03030303u);
+                    o.y = ((q.y << 2) & 0xFCFCFCFCu) | ((y3 >> sh) & 0x03030303u);
+                    *reinterpret_cast<uint2 *>(tiles + tile * 3072 + j * 1024 + in_plane) = o;
+                }
+            }
+        }
         if (hdst) hdst[c] = v;
     };
 #pragma unroll
@@ -220,13 +254,14 @@ __global__ __launch_bounds__(256) void quant_act_g128_kernel(const uint16_t *__r
 
 template <int MODE>
 hipError_t launch(const uint16_t *in, const uint16_t *gamma, float eps, int M, int L, int act_bits,
-                  int8_t *xq, uint16_t *sx, uint16_t *h_out, hipStream_t st)
+                  int8_t *xq, uint16_t *sx, uint16_t *h_out, int layout, hipStream_t st)
 {
+    if (layout != 0 && (layout != act_bits || L % 128 != 0)) return hipErrorInvalidValue;
     const float qmax = act_bits == 6 ? 31.0f : 127.0f;
     const int chunks = L / 8;
 #define FLEXQ_PRODUCER(CH, T)                                                                   \
     hipLaunchKernelGGL((producer_kernel<MODE, CH, T>), dim3(M), dim3(T), 0, st, in, gamma, eps, \
-                       L, qmax, xq, sx, h_out)
+                       L, qmax, xq, sx, h_out, layout)
     if (chunks <= 256)
         FLEXQ_PRODUCER(1, 256);
     else if (chunks <= 512)
@@ -251,21 +286,21 @@ namespace flexq {
 
 hipError_t launch_rmsnorm_quant(const uint16_t *x, const uint16_t *gamma, float eps, int M, int K,
                                 int act_bits, int8_t *xq, uint16_t *sx, uint16_t *h_out,
-                                hipStream_t st)
+                                hipStream_t st, int layout)
 {
-    return launch<0>(x, gamma, eps, M, K, act_bits, xq, sx, h_out, st);
+    return launch<0>(x, gamma, eps, M, K, act_bits, xq, sx, h_out, layout, st);
 }
 
 hipError_t launch_swiglu_quant(const uint16_t *gate_up, int M, int F, int act_bits, int8_t *xq,
-                               uint16_t *sx, uint16_t *h_out, hipStream_t st)
+                               uint16_t *sx, uint16_t *h_out, hipStream_t st, int layout)
 {
-    return launch<1>(gate_up, nullptr, 0.0f, M, F, act_bits, xq, sx, h_out, st);
+    return launch<1>(gate_up, nullptr, 0.0f, M, F, act_bits, xq, sx, h_out, layout, st);
 }
 
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int act_bits, int8_t *xq, uint16_t *sx,
-                            hipStream_t st)
+                            hipStream_t st, int layout)
 {
-    return launch<2>(x, nullptr, 0.0f, M, K, act_bits, xq, sx, nullptr, st);
+    return launch<2>(x, nullptr, 0.0f, M, K, act_bits, xq, sx, nullptr, layout, st);
 }
 
 hipError_t launch_quant_act_g128(const uint16_t *x, int M, int K, int act_bits, int8_t *xq,

@@ -129,6 +129,41 @@ __global__ __launch_bounds__(256) void unpack_w6_kernel(const uint8_t *__restric
     }
 }
 
+// Activations in tile order (tiles of 32 tokens x 128 k: four 1 KiB planes of int8, or
+// the three planes of the packed 6-bit format) back to row-major int8 codes [M][K].
+__global__ __launch_bounds__(256) void untile_act_kernel(const uint8_t *__restrict__ xt, int bits, int M,
+                                                         int K, int8_t *__restrict__ xq)
+{
+    const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+    const int kt = K / FLEXQ_TILE_K;
+    const long tiles = (long)((M + 31) / 32) * kt;
+    const long tile = gid >> 6;
+    const int lane = (int)(gid & 63);
+    if (tile >= tiles) return;
+    const long mb = tile / kt, kb = tile % kt;
+    const int r = lane & 31, h = lane >> 5;
+    if (mb * 32 + r >= M) return;                       // a padding row of the last block
+    int8_t *row = xq + (mb * 32 + r) * (long)K + kb * FLEXQ_TILE_K + 16 * h;
+    if (bits == 8) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(xt + tile * 4096) + lane;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4 *>(row + 32 * j) = src[64 * j];
+        return;
+    }
+    PackedTile t = load_packed_tile_cached(reinterpret_cast<const v4i *>(xt + tile * FLEXQ_TILE_BYTES), lane);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        v4i d = unpack_kstep(t, j);            // bytes hold 4*x
+        int8_t b[16];
+        __builtin_memcpy(b, &d, 16);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) b[i] = (int8_t)(b[i] >> 2);
+        uint4 v;
+        __builtin_memcpy(&v, b, 16);
+        *reinterpret_cast<uint4 *>(row + 32 * j) = v;
+    }
+}
+
 // Scales into / out of the packed buffer.  group mode reorders [N][K/128] to
 // tile order [N/32][K/128][32].
 __global__ void scales_kernel(const uint16_t *__restrict__ src, int N, int K, int group,
@@ -196,6 +231,14 @@ hipError_t launch_unpack_w6(const void *packed, int N, int K, int group, int8_t 
     const long count = group == 0 ? N : (long)N * (K / 128);
     hipLaunchKernelGGL(scales_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, src,
                        N, K, group, sw, 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_untile_act(const uint8_t *xt, int act_bits, int M, int K, int8_t *xq, hipStream_t st)
+{
+    const long lanes = (long)((M + 31) / 32) * (K / 128) * 64;
+    hipLaunchKernelGGL(untile_act_kernel, dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, st, xt,
+                       act_bits, M, K, xq);
     return hipGetLastError();
 }
 

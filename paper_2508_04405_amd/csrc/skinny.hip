@@ -18,6 +18,14 @@
 // workgroup needs is staged once in LDS (padded rows, conflict-free 16-byte
 // reads) when it fits.
 //
+// Where the slice does not fit (more than eight tokens of an 8192-deep layer) each lane
+// loads its token's operands per tile: from row-major activations that is four loads of
+// 32 scattered lines each, which is what slows batches of 16 to 32 tokens down; from
+// activations in TILE ORDER (XT: the quantizer writes tiles of 32 tokens x 128 k whose
+// planes give a lane its 16 bytes per k-step contiguously -- int8, or 6 bits packed exactly
+// like the weights and expanded the same way, Section 4.3.1) it is three or four
+// coalesced 1 KiB loads.  Packed 6-bit operands are 4x on both sides: the sums are 16x.
+//
 // Partial sums of the wavefronts meet in LDS (the counterpart of the paper's
 // Section 4.3.5 reduction: exact integer sums, in any order).  With more than
 // one K split the workgroups leave partial sums in the workspace and the last
@@ -40,17 +48,29 @@ struct Stage {
 
 // GROUP: 0 = one scale per output channel and per token; 1 = weight scales per 128-k
 // group (Section 4.1.1), one scale per token; 2 = both operands scaled per group (Eq. 7).
-template <int MT, int GROUP, bool XLDS, bool NTW>
+template <int MT, int GROUP, bool XLDS, bool NTW, int XT>
 __device__ __forceinline__ void load_stage(Stage<MT, XLDS> &s, const v4i *packed,
                                            const uint16_t *scales, const int8_t *const (&xrow)[MT],
                                            const bool (&xact)[MT], long tile_index, int t, int lane,
-                                           const uint16_t *sxg, int sxg_stride)
+                                           const uint16_t *sxg, int sxg_stride, int KT)
 {
     // NTW: non-temporal loads, so that the weight stream (used once) does not displace
     // the activations in L2; the cached form exists for the ablation only
     s.w = NTW ? load_packed_tile(packed + tile_index * (FLEXQ_TILE_BYTES / 16), lane)
               : load_packed_tile_cached(packed + tile_index * (FLEXQ_TILE_BYTES / 16), lane);
-    if (!XLDS) {
+    if (XT != 0) {
+        // tile (mt, t) of the activations: plane j gives this lane its 16 bytes of k-step j
+        // (8 bits), or the three planes of a packed 6-bit tile; padding rows hold anything
+        static_assert(XT == 0 || !XLDS, "tile-ordered activations are read straight from memory");
+        constexpr int TB = XT == 6 ? FLEXQ_TILE_BYTES : 4096;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const v4i *tile = reinterpret_cast<const v4i *>(
+                reinterpret_cast<const uint8_t *>(xrow[0]) + ((long)mt * KT + t) * TB);
+#pragma unroll
+            for (int j = 0; j < (XT == 6 ? 3 : 4); ++j) s.a[XLDS ? 0 : mt][XLDS ? 0 : j] = tile[64 * j];
+        }
+    } else if (!XLDS) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             if (xact[mt]) {  // lanes of padding rows load nothing
@@ -86,11 +106,15 @@ __device__ __forceinline__ unsigned prologue_code(uint16_t hbits, float sf, floa
     return (unsigned)((int)q & 0xff);
 }
 
-template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE, bool NTW = true>
+template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE, bool NTW = true, int XT = 0>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void skinny_kernel(flexq::LinearArgs a)
 {
     static_assert(!FUSEQ || (XLDS && MT == 1), "the fused quantizer fills the LDS slice");
+    static_assert(XT == 0 || ((XT == 6 || XT == 8) && !XLDS && !FUSEQ && GROUP != 2), "tile-ordered activations");
+    // packed 6-bit activations enter the MFMA as 4x, like the weights: the sums are 16 x
+    constexpr int SUM_SHIFT = XT == 6 ? 4 : 2;
+    constexpr float SUM_SCALE = XT == 6 ? 0.0625f : 0.25f;
     static_assert(!FUSEQ || GROUP != 2, "the fused quantizer makes one scale per token");
     __shared__ int red[W][4][64];
     __shared__ int s_last;
@@ -119,7 +143,10 @@ void skinny_kernel(flexq::LinearArgs a)
     for (int mt = 0; mt < MT; ++mt) {
         const int row = 32 * mt + (lane & 31);
         xact[mt] = row < M;
-        xrow[mt] = a.xq + (long)(xact[mt] ? row : 0) * a.K + 16 * (lane >> 5);
+        if (XT != 0)   // the lane's 16 bytes of plane 0 of tile (0, 0)
+            xrow[mt] = a.xq + 16 * lane;
+        else
+            xrow[mt] = a.xq + (long)(xact[mt] ? row : 0) * a.K + 16 * (lane >> 5);
     }
     const int span = (t1 - t0) * FLEXQ_TILE_K;  // bytes of k per token in this K range
     const int xstride = span + 16;              // padded LDS row
@@ -161,8 +188,8 @@ void skinny_kernel(flexq::LinearArgs a)
     for (int p = 0; p < P; ++p) {
         const int t = tw + W * p;
         if (t < t1)
-            load_stage<MT, GROUP, XLDS, NTW>(st[p], packed, a.scales, xrow, xact, tile_base + t, t, lane,
-                                        a.sxg, a.sxg_stride);
+            load_stage<MT, GROUP, XLDS, NTW, XT>(st[p], packed, a.scales, xrow, xact, tile_base + t, t, lane,
+                                            a.sxg, a.sxg_stride, KT);
     }
 
     if (FUSEQ) {
@@ -285,11 +312,16 @@ void skinny_kernel(flexq::LinearArgs a)
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        if (XLDS)
+                        if (XLDS) {
                             af[mt][j] = *reinterpret_cast<const v4i *>(
                                 xl + (t - t0) * FLEXQ_TILE_K + 32 * j);
-                        else
+                        } else if (XT == 6) {
+                            const PackedTile xa = {st[p].a[XLDS ? 0 : mt][0], st[p].a[XLDS ? 0 : mt][XLDS ? 0 : 1],
+                                                   st[p].a[XLDS ? 0 : mt][XLDS ? 0 : 2]};
+                            af[mt][j] = unpack_kstep(xa, j);
+                        } else {
                             af[mt][j] = st[p].a[XLDS ? 0 : mt][XLDS ? 0 : j];
+                        }
                     }
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
@@ -330,8 +362,8 @@ void skinny_kernel(flexq::LinearArgs a)
                 }
                 const int tn = t + W * P;
                 if (tn < t1)
-                    load_stage<MT, GROUP, XLDS, NTW>(st[p], packed, a.scales, xrow, xact, tile_base + tn,
-                                                tn, lane, a.sxg, a.sxg_stride);
+                    load_stage<MT, GROUP, XLDS, NTW, XT>(st[p], packed, a.scales, xrow, xact, tile_base + tn,
+                                                    tn, lane, a.sxg, a.sxg_stride, KT);
                 t += W;
             }
         }
@@ -366,10 +398,10 @@ void skinny_kernel(flexq::LinearArgs a)
                     }
                     if (KS == 1) {
                         if (GROUP) {
-                            a.y[(long)m * N + n] = f2h(__int_as_float(v) * 0.25f *
+                            a.y[(long)m * N + n] = f2h(__int_as_float(v) * SUM_SCALE *
                                                        (GROUP == 2 ? 1.0f : FUSEQ ? s_sx[m] : h2f(a.sx[m])));
                         } else {
-                            const int qv = v >> 2;
+                            const int qv = v >> SUM_SHIFT;
                             if (a.acc_out) a.acc_out[(long)m * N + n] = qv;
                             a.y[(long)m * N + n] =
                                 f2h((float)qv * ((FUSEQ ? s_sx[m] : h2f(a.sx[m])) * h2f(a.scales[n])));
@@ -412,24 +444,24 @@ void skinny_kernel(flexq::LinearArgs a)
             for (int k = 0; k < KS; ++k)
                 f += __int_as_float(__hip_atomic_load(&partial_i[((long)k * M + m) * N + n],
                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            a.y[(long)m * N + n] = f2h(f * 0.25f * (GROUP == 2 ? 1.0f : FUSEQ ? s_sx[m] : h2f(a.sx[m])));
+            a.y[(long)m * N + n] = f2h(f * SUM_SCALE * (GROUP == 2 ? 1.0f : FUSEQ ? s_sx[m] : h2f(a.sx[m])));
         } else {
             int v = 0;
             for (int k = 0; k < KS; ++k)
                 v += __hip_atomic_load(&partial_i[((long)k * M + m) * N + n], __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
-            const int q = v >> 2;
+            const int q = v >> SUM_SHIFT;
             if (a.acc_out) a.acc_out[(long)m * N + n] = q;
             a.y[(long)m * N + n] = f2h((float)q * ((FUSEQ ? s_sx[m] : h2f(a.sx[m])) * h2f(a.scales[n])));
         }
     }
 }
 
-template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE, bool NTW = true>
+template <int MT, int GROUP, bool XLDS, bool FUSEQ, int P, int W, int WPE, bool NTW = true, int XT = 0>
 hipError_t launch_one(const flexq::LinearArgs &a, hipStream_t st)
 {
     const unsigned blocks = (unsigned)(a.N / 32) * (unsigned)a.split_k;
-    auto kern = skinny_kernel<MT, GROUP, XLDS, FUSEQ, P, W, WPE, NTW>;
+    auto kern = skinny_kernel<MT, GROUP, XLDS, FUSEQ, P, W, WPE, NTW, XT>;
     size_t dyn = 0;
     if (XLDS) {
         const int KT = a.K / 128;
@@ -451,6 +483,19 @@ hipError_t pick(const flexq::LinearArgs &a, int waves, hipStream_t st)
     const int KT = a.K / 128;
     const int max_tiles = (KT + a.split_k - 1) / a.split_k;
     const bool xlds = a.M <= 32 && (long)a.M * max_tiles * 128 <= kXldsBytes;
+    if (a.xt != 0) {  // activations in tile order: one token block, per-token scales
+        if (a.M > 32 || GROUP == 2 || a.x_fp16 || a.ablate != 0) return hipErrorInvalidValue;
+        constexpr int G = GROUP == 2 ? 1 : GROUP;     // never instantiated for mode 2
+        if (a.xt == 6) {
+            if (waves >= 8) return launch_one<1, G, false, false, 2, 8, 4, true, 6>(a, st);
+            return launch_one<1, G, false, false, 2, 4, 4, true, 6>(a, st);
+        }
+        if (a.xt == 8) {
+            if (waves >= 8) return launch_one<1, G, false, false, 2, 8, 4, true, 8>(a, st);
+            return launch_one<1, G, false, false, 2, 4, 4, true, 8>(a, st);
+        }
+        return hipErrorInvalidValue;
+    }
     if (a.x_fp16) {  // fused quantize prologue: the caller checked skinny_can_fuse()
         if (!xlds || GROUP == 2) return hipErrorInvalidValue;
         constexpr int G = GROUP == 2 ? 1 : GROUP;     // never instantiated for mode 2
@@ -495,6 +540,13 @@ hipError_t pick(const flexq::LinearArgs &a, int waves, hipStream_t st)
 }  // namespace
 
 namespace flexq {
+
+bool skinny_slice_fits(int M, int K, int split_k)
+{
+    const int KT = K / 128;
+    const int max_tiles = (KT + split_k - 1) / split_k;
+    return M <= 32 && (long)M * max_tiles * 128 <= kXldsBytes;
+}
 
 bool skinny_can_fuse(int M, int K, int split_k)
 {

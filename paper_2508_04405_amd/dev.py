@@ -17,12 +17,12 @@ from .binding import _check, _dev, _ptr, _stream, make_workspace
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflexq_dev.so")
 _lib = None
-_tuning = dict(kernel=0, split_k=0, waves=0, gemm_cfg=0, ablate=0, fuse=0)
+_tuning = dict(kernel=0, split_k=0, waves=0, gemm_cfg=0, ablate=0, fuse=0, tiles=0)
 _last = 0
 
 
 class Tuning(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in ("kernel", "split_k", "waves", "gemm_cfg", "ablate", "fuse")]
+    _fields_ = [(n, ctypes.c_int) for n in ("kernel", "split_k", "waves", "gemm_cfg", "ablate", "fuse", "tiles")]
 
 
 def load():
@@ -58,6 +58,12 @@ def set_ablation(choice=0):
 def set_fuse(choice=0):
     """1: quantize inside the streaming kernel whenever it can; 2: never; 0: the library's choice."""
     _tuning.update(fuse=choice)
+
+
+def set_tiles(choice=0):
+    """1: fp16 activations of up to 32 tokens always go through tile order; 2: never; 0: the
+    library's choice."""
+    _tuning.update(tiles=choice)
 
 
 def last_dispatch():

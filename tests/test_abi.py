@@ -162,6 +162,56 @@ def test_other_entry_points_argument_errors():
     assert b"shape" in lib.flexq_status_string(-2)
 
 
+def test_activation_tiles_sizes_and_argument_errors():
+    """Activations in tile order: 3072 bytes (6-bit, packed) or 4096 bytes (8-bit) per tile of
+    32 tokens x 128 k, whole token blocks; bad arguments are refused on the host."""
+    lib = fq.load()
+    size = lib.flexq_act_tiles_bytes
+    assert size(6, 1, 128) == 3072 and size(8, 1, 128) == 4096
+    assert size(6, 32, 8192) == 32 * 8192 * 6 // 8           # exactly 0.75 byte per value
+    assert size(6, 33, 8192) == 2 * 32 * 8192 * 6 // 8
+    assert size(8, 70, 28672) == 3 * 32 * 28672
+    assert size(7, 1, 128) == 0 and size(6, 0, 128) == 0 and size(6, 1, 100) == 0 and size(6, 1, 65536 + 128) == 0
+    # the prologue's area of the workspace holds one block of tiles for fewer than 32 tokens
+    fixed = lambda M, K: 16384 + -(-max(M, 32) * K // 256) * 256 + 256
+    assert lib.flexq_workspace_bytes(1, 57344, 8192) == fixed(1, 8192)        # 1792 row blocks: no K split
+    assert lib.flexq_workspace_bytes(20, 57344, 8192) == fixed(20, 8192)
+    qt, ut, gt = lib.flexq_quant_act_tiles, lib.flexq_untile_act, lib.flexq_gemv_tiles
+    assert qt(None, 1, 128, 6, P16, P16, None) == -1
+    assert qt(P16, 1, 128, 6, None, P16, None) == -1
+    assert qt(P16, 0, 128, 6, P16, P16, None) == -1
+    assert qt(P16, 1, 128, 7, P16, P16, None) == -1
+    assert qt(P16, 1, 192, 6, P16, P16, None) == -2
+    assert qt(P16, 1, 128, 6, ODD, P16, None) == -3
+    assert ut(None, 1, 128, 6, P16, None) == -1
+    assert ut(P16, 1, 128, 5, P16, None) == -1
+    assert ut(P16, 1, 100, 6, P16, None) == -2
+    assert ut(P16, 1, 128, 6, ODD, None) == -3
+    big = 1 << 30
+    ok = dict(bits=6, packed=P16, group=0, xt=P16, sx=P16, M=20, N=128, K=256, y=P16, acc=None, ws=P16, wsb=big)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return gt(a["bits"], a["packed"], a["group"], a["xt"], a["sx"], a["M"], a["N"], a["K"], a["y"], a["acc"],
+                  a["ws"], a["wsb"], None)
+
+    assert call(bits=4) == -1
+    assert call(M=33) == -1                                  # one block of 32 tokens at most
+    assert call(M=0) == -1
+    assert call(xt=None) == -1
+    assert call(sx=None) == -1
+    assert call(group=128, acc=P16) == -1
+    assert call(N=100) == -2
+    assert call(xt=ODD) == -3
+    assert call(ws=None) == -5
+    assert call(wsb=1024) == -5
+    # the development library refuses an unknown choice for the tile order
+    t = dev.Tuning(tiles=3)
+    got = ctypes.c_int(0)
+    assert dev.load().flexq_dev_linear(ctypes.byref(t), 6, P16, 0, P16, P16, None, None, 0, 4, 128, 256, P16, None,
+                                       P16, big, None, ctypes.byref(got)) == -1
+
+
 def test_noalloc_entry_point_argument_errors():
     """The entry point without a workspace checks like flexq_gemv_w6a8, before it touches
     the GPU, and refuses shapes whose workspace would not fit its fixed array."""
@@ -211,9 +261,12 @@ def test_layer_runner_argument_errors():
                                        None)
 
     need = lib.flexq_layer_workspace_bytes(ctypes.byref(layer()), 4)
-    # the widest GEMM workspace, then the quantized input of a stage: codes [M, max(H, F)], scales [M]
+    # the widest GEMM workspace, then the quantized input of a stage: codes [M, max(H, F)] (room
+    # for one block of 32-token tiles when there are fewer tokens), scales [M]
     assert need == max(lib.flexq_workspace_bytes(4, n, k)
-                       for n, k in ((768, 256), (256, 256), (1024, 256), (256, 512))) + 4 * 512 + 256
+                       for n, k in ((768, 256), (256, 256), (1024, 256), (256, 512))) + 32 * 512 + 256
+    assert lib.flexq_layer_workspace_bytes(ctypes.byref(layer()), 40) == max(
+        lib.flexq_workspace_bytes(40, n, k) for n, k in ((768, 256), (256, 256), (1024, 256), (256, 512))) + 40 * 512 + 256
     assert lib.flexq_layer_workspace_bytes(ctypes.byref(layer(H=200)), 4) == 0
     assert call(layer(), M=0) == -1
     assert call(layer(), first=2, last=1) == -1

@@ -312,6 +312,42 @@ def probe_table(args, torch, fq, fqdev, synth, dev):
                   (M, name, mb, p_us, mb / p_us * 1e3, g_us, mb / g_us * 1e3, g_us / p_us), flush=True)
 
 
+def mix_table(args, torch, fq, fqdev, synth, dev):
+    """What the chip sustains on a stream of int8 MFMAs accompanied by the other work of a GEMM
+    wavefront (development library's mix probe: no global loads, no barriers): the context for
+    reading the GEMM's fraction of the published peak on a power-limited machine."""
+    K, N = 8192, 8192
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(3010)
+    w = torch.randn((256, K), generator=gen, device=dev, dtype=torch.float32) * SIGMA
+    wq, sw = fq.quant_w6(w)
+    b_ops = fq.pack_w6(wq, sw)
+    x = torch.from_numpy(synth.activations(64, K, seed=3011, outlier_frac=0.01)).to(dev)
+    a_ops, _ = fq.quant_act(x, 6)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    print("| wavefronts per SIMD | vector operations per MFMA | 16-byte LDS reads per 8 MFMAs | TOP/s | of the 5000 peak |")
+    print("|---|---|---|---|---|")
+    iters = 4000
+    for waves, v, l in ((4, 0, 0), (8, 0, 0), (8, 2, 0), (8, 3, 0), (8, 4, 0), (8, 6, 0), (8, 8, 0), (8, 0, 4), (8, 3, 4),
+                        (8, 3, 8)):
+        t_start = time.perf_counter()
+        while time.perf_counter() - t_start < 0.05:
+            fqdev.probe_mfma_mix(a_ops, b_ops, v, l, 400, 256, waves, sink)
+            torch.cuda.synchronize()
+        best = []
+        for _ in range(5):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fqdev.probe_mfma_mix(a_ops, b_ops, v, l, iters, 256, waves, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            best.append(e0.elapsed_time(e1))
+        ms = sorted(best)[2]
+        tops = 2.0 * 32768 * 8 * iters * waves * 256 / (ms * 1e-3) / 1e12
+        print("| %d | %d | %d | %.0f | %.1f %% |" % (waves // 4, v, l, tops, tops / 50.0), flush=True)
+
+
 def tiles_table(args, torch, fq, fqdev, synth, dev):
     """Batched decode from fp16 activations, per layer and token count: the quantizer writing
     row-major int8 codes against the quantizer writing tile order (6-bit activations packed at
@@ -462,6 +498,9 @@ def main():
     ap.add_argument("--probe", action="store_true",
                     help="instead of the benchmark line, print the decode GEMV against a read-only kernel "
                          "over the same packed buffers, per layer, at M = 1 and 16")
+    ap.add_argument("--mix", action="store_true",
+                    help="instead of the benchmark line, print what the chip sustains on int8 MFMA streams "
+                         "accompanied by vector operations and LDS reads (development library's mix probe)")
     ap.add_argument("--tiles", action="store_true",
                     help="instead of the benchmark line, print batched decode (4 to 32 tokens, fp16 in) with the "
                          "quantized activations row-major against in tile order (6-bit ones packed)")
@@ -519,6 +558,8 @@ def main():
         return probe_table(args, torch, fq, fqdev, synth, dev)
     if args.tiles:
         return tiles_table(args, torch, fq, fqdev, synth, dev)
+    if args.mix:
+        return mix_table(args, torch, fq, fqdev, synth, dev)
 
     # ---- resident inputs: packed weights, fp16 activations -----------------
     gen = torch.Generator(device=dev)

@@ -82,11 +82,25 @@ flexq_status flexq_dev_linear(const flexq_dev_tuning *tuning, int act_bits, cons
  * 2 * 32768 * 16 * iters * 4 * workgroups / its duration is the int8 rate the
  * matrix pipe sustains on such data.
  *
+ * flexq_dev_probe_mfma_mix: the same pipe beside the other work of a GEMM
+ * wavefront.  `workgroups` workgroups of `waves` (4 or 8: one or two per SIMD)
+ * wavefronts each issue iters * 8 MFMAs (iters even), every one followed by
+ * valu_per_mfma vector operations whose results feed later MFMAs (the shape of the
+ * weight expansion), with lds_reads_per_8 16-byte LDS reads per eight MFMAs whose
+ * data the next eight consume; no global loads, no barriers.  Built combinations
+ * (valu_per_mfma, lds_reads_per_8): (0,0) (2,0) (3,0) (4,0) (6,0) (8,0) (0,4) (3,4)
+ * (3,8); others -> FLEXQ_EINVAL.  Operands from the first 16 KiB of each buffer.
+ * 2 * 32768 * 8 * iters * waves * workgroups / its duration is what the chip,
+ * power-limited as it is, sustains on such a stream.
+ *
  * `sink` (dev, 4 bytes) is never written in practice; it keeps the work alive.
  */
 flexq_status flexq_dev_probe_hbm_read(const void *src, size_t bytes, void *sink, void *stream);
 flexq_status flexq_dev_probe_mfma_i8(const void *a_operands, const void *b_operands, int iters,
                                      int workgroups, void *sink, void *stream);
+flexq_status flexq_dev_probe_mfma_mix(const void *a_operands, const void *b_operands, int valu_per_mfma,
+                                      int lds_reads_per_8, int iters, int workgroups, int waves, void *sink,
+                                      void *stream);
 
 #ifdef __cplusplus
 }

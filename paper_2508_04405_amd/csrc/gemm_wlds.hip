@@ -11,19 +11,29 @@
 // wavefronts that share its columns: 0.875 KB through the vector-memory path
 // per 32x32x128 block at NT = 2 instead of 1.25.
 //
-//   LDS: three weight stages of 12 NT KiB, requested TWO stages ahead (a packed
-//   weight panel is read by few workgroups, all at the same time, so its lines
-//   come from HBM, well over a microsecond away), and activation stages of
-//   32 KiB: for whole tiles two of them, requested one stage ahead (an
-//   activation panel is shared by every column tile of its row and mostly found
-//   in L2 or the Infinity Cache; a third stage would not fit beside the weights),
-//   for half tiles, whose stages are shorter than the memory latency, three,
-//   requested two ahead.  (Two ahead for both operands of whole tiles too, with
-//   two weight buffers and a second barrier per stage that frees a weight stage
-//   as soon as every wavefront has copied it to registers, was measured 3 %
-//   slower on every layer.)  One workgroup per CU, two wavefronts per SIMD.
-//   The hand-over waits until at most the loads for the stage after next are
-//   outstanding.
+//   LDS: three weight stages (24 KiB for whole tiles), requested TWO stages ahead (a
+//   packed weight panel is read by few workgroups, all at the same time, so its lines
+//   come from HBM, well over a microsecond away), and activation stages of 32 KiB: for
+//   whole tiles two of them, requested one stage ahead (an activation panel is shared by
+//   every column tile of its row and mostly found in L2 or the Infinity Cache; a third
+//   stage would not fit beside the weights), for half tiles, whose stages are shorter
+//   than the memory latency, three, requested two ahead.  One workgroup per CU, two
+//   wavefronts per SIMD.  The hand-over waits until at most the loads for the stage after
+//   next are outstanding.
+//
+//   Where in a stage the requests are made matters as much as how far ahead (each
+//   measured against the alternative on one box, alternating): everything that every
+//   wavefront does at the same moment -- right after the hand-over's barrier, at the
+//   start of a stage -- is a burst that the matrix pipe waits out.  So only plane 0 of
+//   the next stage's packed tiles is copied to registers after the barrier and planes 1
+//   and 2 a k-step later (+1.4 %, and the shorter register lifetimes end the spilling);
+//   the weight requests leave at the second k-step instead of with the activation
+//   requests at the start (+1.6 %); the activation requests stay at the start (a k-step
+//   later: -1.2 %; right after the barrier, which would free their buffer a k-step
+//   earlier: -1.5 % to -3 %).  Not kept: two weight buffers with a second barrier per
+//   stage to make room for a third activation buffer (-3 %); raising one wavefront's
+//   priority over its SIMD-mate's, for a k-step in turn or for part of a stage (-1 % to
+//   -40 %: a wavefront alone does not keep the pipe busy, the two must interleave).
 //
 // Per-channel scales only: this is the kernel for large M and N.
 //
@@ -274,9 +284,7 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const v4i *t = reinterpret_cast<const v4i *>(lds + wfrag + nt * FLEXQ_TILE_BYTES);
-            wreg[nt].q0 = t[0];
-            wreg[nt].q1 = t[64];
-            wreg[nt].q2 = t[128];
+            wreg[nt].q0 = t[0];          // the other two planes follow at the start of the stage
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -293,18 +301,31 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             const int wnext = wcur == 2 ? 0 : wcur + 1, wnext2 = wcur == 0 ? 2 : wcur - 1;
             // First what the hand-over waits for (with everything older, the weights of
             // stage kb + 1 among it): the activations of stage kb + 1, where they run one
-            // stage ahead.  Then what may stay in flight across it: the loads for stage
-            // kb + 2.  All targets are free: an activation buffer was last read before the
-            // previous stage's barrier, the weight buffer was copied to registers two
-            // barriers ago.
+            // stage ahead.  Then, at the second k-step, what may stay in flight across it:
+            // the loads for stage kb + 2.  All targets are free: an activation buffer was
+            // last read before the previous stage's barrier, and the weight buffer is that
+            // of stage kb - 1, whose last plane went to registers during that stage's first
+            // k-step, before its barrier.
             if (S::XA == 1 && more1) dma_x(at, ks, kb + 1, (CUR + 1) % S::XBUFS);
             if (S::XA == 2 && more2) dma_x(at, ks, kb + 2, (CUR + 2) % S::XBUFS);
-            if (more2) dma_w(at, ks, kb + 2, wnext2);
 
             const uint8_t *xs = lds + CUR * XSTAGE;
             const uint8_t *xn = lds + ((CUR + 1) % S::XBUFS) * XSTAGE;
+            const uint8_t *wcb = lds + wfrag + wcur * S::WSTAGE;
             const uint8_t *wnb = lds + wfrag + wnext * S::WSTAGE;
             wcur = wnext;
+            // The packed planes of this stage's tiles not yet in registers.  Right after the
+            // hand-over every wavefront asks LDS for its first operands at once; only plane 0
+            // (the first k-step) is fetched in that burst, planes 1 and 2 here, a k-step
+            // later, well before the steps that expand them.
+            auto rest_of_tiles = [&] {
+#pragma unroll
+                for (int n2 = 0; n2 < NT; ++n2) {
+                    const v4i *t = reinterpret_cast<const v4i *>(wcb + n2 * FLEXQ_TILE_BYTES);
+                    wreg[n2].q1 = t[64];
+                    wreg[n2].q2 = t[128];
+                }
+            };
             // Flat software pipeline over the 4 * NT (k-step, column tile) steps: LDS
             // operand reads a k-step ahead, weight operands expanded one dword per MFMA in
             // the shadow of the MFMA just issued.  The two wavefronts of a SIMD belong to
@@ -330,8 +351,6 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                     for (int n2 = 0; n2 < NT; ++n2) {
                         const v4i *t = reinterpret_cast<const v4i *>(wnb + n2 * FLEXQ_TILE_BYTES);
                         wreg[n2].q0 = t[0];
-                        wreg[n2].q1 = t[64];
-                        wreg[n2].q2 = t[128];
                     }
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
@@ -353,6 +372,8 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                             for (int mt = 0; mt < MT; ++mt)
                                 af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
                                     xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
+                            if (j == 0) rest_of_tiles();
+                            if (j == 1 && more2) dma_w(at, ks, kb + 2, wnext2);
                         } else {
                             hand_over();
                         }
@@ -397,6 +418,8 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                             for (int mt = 0; mt < MT; ++mt)
                                 af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
                                     xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
+                            if (j == 0) rest_of_tiles();
+                            if (j == 1 && more2) dma_w(at, ks, kb + 2, wnext2);
                         } else {
                             hand_over();
                         }

@@ -6,6 +6,7 @@
 // the linear layer's arithmetic; built into the development library only.
 #include "../../include/flexq_dev.h"
 #include "flexq_device.h"
+#include <type_traits>
 
 namespace {
 
@@ -54,6 +55,74 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const v4i *__restrict__
     if (s == 0x7fffffff) sink[0] = s;
 }
 
+// The matrix pipe beside the other work of a GEMM wavefront, in the GEMM kernels' operand
+// pattern: steps of eight MFMAs on four activation operands and two weight operands (each
+// weight operand held for four MFMAs), the next step's weight operands being rebuilt
+// meanwhile by V vector operations per MFMA (mask operations on packed bytes held in
+// registers, as the weight expansion does), and L 16-byte LDS reads per step fetching the
+// next step's activation operands.  Nothing else: no global loads, no barriers.
+template <int V, int L>
+__global__ __launch_bounds__(512) void mfma_mix_kernel(const v4i *__restrict__ a_src,
+                                                       const v4i *__restrict__ b_src, int iters, int *sink)
+{
+    __shared__ __attribute__((aligned(16))) char lds[65536];
+    const int tid = threadIdx.x;
+    v4i a[4], an[4], p[4], bs[2][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = a_src[(i * 64 + (tid & 63)) & 1023];
+        an[i] = a_src[((i + 4) * 64 + (tid & 63)) & 1023];
+        p[i] = b_src[(i * 64 + (tid & 63)) & 1023];
+        bs[i >> 1][i & 1] = p[i] & (int)0xFCFCFCFC;
+    }
+    for (int i = tid; i < 65536 / 16; i += blockDim.x) reinterpret_cast<v4i *>(lds)[i] = a_src[i & 1023];
+    __syncthreads();
+    v16i c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) c[i][r] = 0;
+    const char *lp = lds + (tid & 63) * 16 + (tid >> 6) * 4096;
+    auto step = [&](int it, auto parity, v4i(&cur)[4], v4i(&nxt)[4]) {
+        constexpr int PAR = decltype(parity)::value;
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            if (L > 0 && m == 0) {
+#pragma unroll
+                for (int q = 0; q < L; ++q)
+                    nxt[q & 3] = *reinterpret_cast<const v4i *>(lp + ((q + it) & 15) * 1024);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            c[m] = mfma_i8(bs[PAR][m >> 2], cur[m & 3], c[m]);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {   // rebuild a dword of the other step's weight operands
+                const int k = m * V + v, nt = (k >> 2) & 1, d = k & 3;
+                int x;
+                asm volatile("v_and_b32 %0, %1, %2" : "=v"(x) : "s"(0xfcfcfcfc), "v"(p[2 * (1 - PAR) + nt][d]));
+                bs[1 - PAR][nt][d] = x;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    for (int it = 0; it < iters; it += 2) {
+        step(it, std::integral_constant<int, 0>{}, a, an);
+        step(it + 1, std::integral_constant<int, 1>{}, an, a);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += c[i][r];
+    if (s == 0x7fffffff) sink[0] = s;
+}
+
+template <int V, int L>
+void launch_mix(const v4i *a, const v4i *b, int iters, int workgroups, int waves, int *sink, hipStream_t st)
+{
+    hipLaunchKernelGGL((mfma_mix_kernel<V, L>), dim3((unsigned)workgroups), dim3(64 * waves), 0, st, a, b, iters,
+                       sink);
+}
+
 }  // namespace
 
 #pragma GCC visibility push(default)
@@ -80,6 +149,33 @@ flexq_status flexq_dev_probe_mfma_i8(const void *a_operands, const void *b_opera
     hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0,
                        (hipStream_t)stream, (const v4i *)a_operands, (const v4i *)b_operands, iters,
                        (int *)sink);
+    return hipGetLastError() == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
+}
+
+flexq_status flexq_dev_probe_mfma_mix(const void *a_operands, const void *b_operands, int valu_per_mfma,
+                                      int lds_reads_per_8, int iters, int workgroups, int waves, void *sink,
+                                      void *stream)
+{
+    if (!a_operands || !b_operands || !sink || iters < 2 || iters % 2 != 0 || workgroups < 1) return FLEXQ_EINVAL;
+    if (waves != 4 && waves != 8) return FLEXQ_EINVAL;
+    if (((reinterpret_cast<uintptr_t>(a_operands) | reinterpret_cast<uintptr_t>(b_operands)) & 15u) != 0)
+        return FLEXQ_EALIGN;
+    const v4i *a = (const v4i *)a_operands, *b = (const v4i *)b_operands;
+    int *sk = (int *)sink;
+    hipStream_t st = (hipStream_t)stream;
+    const int key = valu_per_mfma * 10 + lds_reads_per_8;
+    switch (key) {
+    case 0: launch_mix<0, 0>(a, b, iters, workgroups, waves, sk, st); break;
+    case 20: launch_mix<2, 0>(a, b, iters, workgroups, waves, sk, st); break;
+    case 30: launch_mix<3, 0>(a, b, iters, workgroups, waves, sk, st); break;
+    case 40: launch_mix<4, 0>(a, b, iters, workgroups, waves, sk, st); break;
+    case 60: launch_mix<6, 0>(a, b, iters, workgroups, waves, sk, st); break;
+    case 80: launch_mix<8, 0>(a, b, iters, workgroups, waves, sk, st); break;
+    case 4: launch_mix<0, 4>(a, b, iters, workgroups, waves, sk, st); break;
+    case 34: launch_mix<3, 4>(a, b, iters, workgroups, waves, sk, st); break;
+    case 38: launch_mix<3, 8>(a, b, iters, workgroups, waves, sk, st); break;
+    default: return FLEXQ_EINVAL;
+    }
     return hipGetLastError() == hipSuccess ? FLEXQ_OK : FLEXQ_EHIP;
 }
 

@@ -42,6 +42,8 @@ def load():
     lib.flexq_dev_probe_hbm_read.argtypes = [vp, c_size, vp, vp]
     lib.flexq_dev_probe_mfma_i8.restype = c_int
     lib.flexq_dev_probe_mfma_i8.argtypes = [vp, vp, c_int, c_int, vp, vp]
+    lib.flexq_dev_probe_mfma_mix.restype = c_int
+    lib.flexq_dev_probe_mfma_mix.argtypes = [vp, vp, c_int, c_int, c_int, c_int, c_int, vp, vp]
     _lib = lib
     return lib
 
@@ -130,3 +132,12 @@ def probe_mfma_i8(a_operands, b_operands, iters, workgroups, sink):
     assert b_operands.numel() * b_operands.element_size() >= 16384
     _check(load().flexq_dev_probe_mfma_i8(_ptr(a_operands), _ptr(b_operands), iters, workgroups,
                                           _ptr(sink), _stream()))
+
+
+def probe_mfma_mix(a_operands, b_operands, valu_per_mfma, lds_reads_per_8, iters, workgroups, waves, sink):
+    """Enqueue the MFMA kernel with `valu_per_mfma` vector operations after every MFMA and
+    `lds_reads_per_8` LDS reads per eight MFMAs; `waves` 4 or 8 per workgroup."""
+    assert a_operands.numel() * a_operands.element_size() >= 16384
+    assert b_operands.numel() * b_operands.element_size() >= 16384
+    _check(load().flexq_dev_probe_mfma_mix(_ptr(a_operands), _ptr(b_operands), valu_per_mfma, lds_reads_per_8,
+                                           iters, workgroups, waves, _ptr(sink), _stream()))

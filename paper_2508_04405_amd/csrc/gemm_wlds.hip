@@ -22,18 +22,26 @@
 //   next are outstanding.
 //
 //   Where in a stage the requests are made matters as much as how far ahead (each
-//   measured against the alternative on one box, alternating): everything that every
-//   wavefront does at the same moment -- right after the hand-over's barrier, at the
-//   start of a stage -- is a burst that the matrix pipe waits out.  So only plane 0 of
-//   the next stage's packed tiles is copied to registers after the barrier and planes 1
-//   and 2 a k-step later (+1.4 %, and the shorter register lifetimes end the spilling);
-//   the weight requests leave at the second k-step instead of with the activation
-//   requests at the start (+1.6 %); the activation requests stay at the start (a k-step
-//   later: -1.2 %; right after the barrier, which would free their buffer a k-step
-//   earlier: -1.5 % to -3 %).  Not kept: two weight buffers with a second barrier per
-//   stage to make room for a third activation buffer (-3 %); raising one wavefront's
-//   priority over its SIMD-mate's, for a k-step in turn or for part of a stage (-1 % to
-//   -40 %: a wavefront alone does not keep the pipe busy, the two must interleave).
+//   measured against the alternative on one box, alternating): whatever all eight
+//   wavefronts do at the same moment -- right after the hand-over's barrier, at the
+//   start of a stage -- is a burst that the matrix pipe waits out.  So the work beside
+//   the MFMAs is dealt out over the eight steps of a stage (a step: the four MFMAs of one
+//   k-step and column block):
+//     step 0  activation requests (DMA); LDS reads: activation operands of k-step 1,
+//             plane 1 of the stage's packed tiles
+//     step 1  plane 2            step 2  activation operands of k-step 2
+//     step 3  weight requests (DMA)       step 4  activation operands of k-step 3
+//     step 6  hand-over: counted wait, barrier; plane 0 of the next stage's tiles
+//     step 7  the next stage's first activation operands
+//   Against everything at the stage's start and after the barrier: planes 1 and 2 later
+//   +1.4 % (and the shorter register lifetimes end the spilling), weight requests later
+//   +1.6 %, first activation operands a step after the barrier +0.9 %, one item per step
+//   +1.4 %.  The activation requests stay at the start (a step later: -1.2 %; right after
+//   the barrier, which would free their buffer a k-step earlier: -1.5 % to -3 %).  Not
+//   kept either: two weight buffers with a second barrier per stage to make room for a
+//   third activation buffer (-3 %); raising one wavefront's priority over its SIMD-mate's,
+//   for a k-step in turn or for part of a stage (-1 % to -40 %: a wavefront alone does not
+//   keep the pipe busy, the two must interleave).
 //
 // Per-channel scales only: this is the kernel for large M and N.
 //
@@ -301,8 +309,8 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             const int wnext = wcur == 2 ? 0 : wcur + 1, wnext2 = wcur == 0 ? 2 : wcur - 1;
             // First what the hand-over waits for (with everything older, the weights of
             // stage kb + 1 among it): the activations of stage kb + 1, where they run one
-            // stage ahead.  Then, at the second k-step, what may stay in flight across it:
-            // the loads for stage kb + 2.  All targets are free: an activation buffer was
+            // stage ahead.  Then, during step 3, what may stay in flight across it: the
+            // loads for stage kb + 2.  All targets are free: an activation buffer was
             // last read before the previous stage's barrier, and the weight buffer is that
             // of stage kb - 1, whose last plane went to registers during that stage's first
             // k-step, before its barrier.
@@ -314,27 +322,17 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             const uint8_t *wcb = lds + wfrag + wcur * S::WSTAGE;
             const uint8_t *wnb = lds + wfrag + wnext * S::WSTAGE;
             wcur = wnext;
-            // The packed planes of this stage's tiles not yet in registers.  Right after the
-            // hand-over every wavefront asks LDS for its first operands at once; only plane 0
-            // (the first k-step) is fetched in that burst, planes 1 and 2 here, a k-step
-            // later, well before the steps that expand them.
-            auto rest_of_tiles = [&] {
+            // The packed planes of this stage's tiles not yet in registers: only plane 0 (the
+            // first k-step) is fetched after the hand-over, plane 1 during step 0 and plane 2
+            // during step 1, well before the steps that expand them.
+            auto rest_of_tiles = [&](int plane) {
 #pragma unroll
                 for (int n2 = 0; n2 < NT; ++n2) {
                     const v4i *t = reinterpret_cast<const v4i *>(wcb + n2 * FLEXQ_TILE_BYTES);
-                    wreg[n2].q1 = t[64];
-                    wreg[n2].q2 = t[128];
+                    if (plane == 1) wreg[n2].q1 = t[64];
+                    if (plane == 2) wreg[n2].q2 = t[128];
                 }
             };
-            // Flat software pipeline over the 4 * NT (k-step, column tile) steps: LDS
-            // operand reads a k-step ahead, weight operands expanded one dword per MFMA in
-            // the shadow of the MFMA just issued.  The two wavefronts of a SIMD belong to
-            // the same workgroup and reach the stage boundary together, so nothing would
-            // cover the operand fetch of a new stage: the hand-over therefore sits BEFORE
-            // the last k-step.  By then this wavefront has read all it needs of stage kb
-            // (the operands of k-step 3 are in registers), so after the barrier the packed
-            // tiles and first activation operands of stage kb + 1 are fetched from LDS
-            // while k-step 3's MFMAs run.
             // At the hand-over stage kb + 1 (weights and activations, every wavefront's
             // share) must have landed; the loads for stage kb + 2 may be in flight.
             auto hand_over = [&] {
@@ -352,9 +350,6 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                         const v4i *t = reinterpret_cast<const v4i *>(wnb + n2 * FLEXQ_TILE_BYTES);
                         wreg[n2].q0 = t[0];
                     }
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-                        af[0][mt] = *reinterpret_cast<const v4i *>(xn + lds_off(arow + 32 * mt, ahalf));
                 }
             };
             static_assert((MT == 4 || MT == 2) && NT == 2, "the step tables below are written for these blockings");
@@ -372,11 +367,24 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                             for (int mt = 0; mt < MT; ++mt)
                                 af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
                                     xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
-                            if (j == 0) rest_of_tiles();
-                            if (j == 1 && more2) dma_w(at, ks, kb + 2, wnext2);
+                            if (j == 0) rest_of_tiles(1);
                         } else {
                             hand_over();
                         }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (s == 1) {
+                        rest_of_tiles(2);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (s == 3 && more2) {
+                        dma_w(at, ks, kb + 2, wnext2);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (s == 7 && more1) {   // the next stage's first activation operands
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            af[0][mt] = *reinterpret_cast<const v4i *>(xn + lds_off(arow + 32 * mt, ahalf));
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     const v4i cur_b = s == 6 ? bf6 : s == 7 ? bf7 : bfc;
@@ -418,11 +426,24 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                             for (int mt = 0; mt < MT; ++mt)
                                 af[(j + 1) & 1][mt] = *reinterpret_cast<const v4i *>(
                                     xs + lds_off(arow + 32 * mt, 2 * (j + 1) + ahalf));
-                            if (j == 0) rest_of_tiles();
-                            if (j == 1 && more2) dma_w(at, ks, kb + 2, wnext2);
+                            if (j == 0) rest_of_tiles(1);
                         } else {
                             hand_over();
                         }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (s == 1) {
+                        rest_of_tiles(2);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (s == 3 && more2) {
+                        dma_w(at, ks, kb + 2, wnext2);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (s == 7 && more1) {   // the next stage's first activation operands
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            af[0][mt] = *reinterpret_cast<const v4i *>(xn + lds_off(arow + 32 * mt, ahalf));
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     const v4i cur_b = s == 6 ? bf6 : s == 7 ? bf7 : bfc;

@@ -290,6 +290,12 @@ def test_dev_entry_points_argument_errors():
     assert d.flexq_dev_probe_hbm_read(None, 4096, P16, None) == -1
     assert d.flexq_dev_probe_hbm_read(ODD, 4096, P16, None) == -3
     assert d.flexq_dev_probe_mfma_i8(P16, P16, 0, 1, P16, None) == -1
+    mix = d.flexq_dev_probe_mfma_mix
+    assert mix(None, P16, 3, 4, 100, 256, 8, P16, None) == -1
+    assert mix(P16, P16, 3, 4, 101, 256, 8, P16, None) == -1       # an odd number of steps
+    assert mix(P16, P16, 3, 4, 100, 256, 6, P16, None) == -1       # four or eight wavefronts
+    assert mix(P16, P16, 5, 4, 100, 256, 8, P16, None) == -1       # a combination that is not built
+    assert mix(ODD, P16, 3, 4, 100, 256, 8, P16, None) == -3
     big = 1 << 30
 
     def call(tuning, bits=8, **kw):

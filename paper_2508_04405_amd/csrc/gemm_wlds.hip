@@ -38,7 +38,10 @@
 //   +1.6 %, first activation operands a step after the barrier +0.9 %, one item per step
 //   +1.4 %.  The activation requests stay at the start (a step later: -1.2 %; right after
 //   the barrier, which would free their buffer a k-step earlier: -1.5 % to -3 %), and the
-//   hand-over before the last k-step (a step earlier: -4.5 %, the requests have less time).  Not
+//   hand-over before the last k-step (a step earlier: -4.5 %, the requests have less time).
+//   Letting the two wavefronts that share a pair of packed tiles expand one tile's fourth
+//   k-step each and exchange the operands through LDS (a third fewer vector operations):
+//   -1.4 %, the exchange costs more than the expansion.  Not
 //   kept either: two weight buffers with a second barrier per stage to make room for a
 //   third activation buffer (-3 %); raising one wavefront's priority over its SIMD-mate's,
 //   for a k-step in turn or for part of a stage (-1 % to -40 %: a wavefront alone does not

@@ -7,7 +7,9 @@
  *
  * with Wq signed 6-bit codes in [-32,31] (one fp16 scale per output channel,
  * or per group of 128 consecutive k), Xq signed 6- or 8-bit codes carried in
- * int8 (one fp16 scale per token), the integer product accumulated exactly in
+ * int8 -- or, for batches of up to 32 tokens, in tile order with 6-bit codes
+ * packed at 0.75 byte each -- (one fp16 scale per token, or per token and
+ * group of 128), the integer product accumulated exactly in
  * int32, and the scales applied in the kernel's epilogue.  Weights are
  * quantized and packed once, offline; activations are quantized online
  * (Section 4.1.3, "FlexQ System Runtime").

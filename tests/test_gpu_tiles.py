@@ -78,28 +78,35 @@ def test_linear_on_tiles(M, K, N, bits, group):
 
 @pytest.mark.parametrize("split,waves", [(1, 4), (2, 8), (3, 4), (5, 8)])
 @pytest.mark.parametrize("bits", [6, 8])
-def test_fp16_calls_through_tiles_with_k_splits(split, waves, bits):
+@pytest.mark.parametrize("group", [0, 128])
+def test_fp16_calls_through_tiles_with_k_splits(split, waves, bits, group):
     """The calls that take fp16 activations, made to go through tile order (development
     library), with the streaming kernel's K splits and workgroup sizes forced."""
     M, K, N = 20, 1408, 192                       # 11 tiles along k: uneven splits
-    say(f"fp16 -> tiles -> streaming kernel, split={split} waves={waves} A{bits}")
+    say(f"fp16 -> tiles -> streaming kernel, split={split} waves={waves} A{bits} group={group}")
     w = synth.weights(N, K, 0.02, seed=17)
     x = synth.activations(M, K, seed=18, outlier_frac=0.02)
-    ref = oracle.linear(x, w, bits)
-    packed, _, _ = prepare(w)
+    ref = oracle.linear(x, w, bits, group)
+    packed, _, _ = prepare(w, group)
     ws = fq.make_workspace(M, N, K, extra=split * M * N * 4)
     dev.set_dispatch(1, split, waves)
     dev.set_tiles(1)
     try:
         fn = dev.gemv_w6a6 if bits == 6 else dev.gemv_w6a8
         for _ in range(3):
-            y, acc = fn(packed, N, K, 0, x_fp16=to_dev(x), workspace=ws, want_acc=True)
+            if group == 0:
+                y, acc = fn(packed, N, K, 0, x_fp16=to_dev(x), workspace=ws, want_acc=True)
+            else:
+                y, acc = fn(packed, N, K, group, x_fp16=to_dev(x), workspace=ws), None
             assert dev.last_dispatch() == (1, 500 + split)
-            check_linear(y, acc, ref, 0)
+            check_linear(y, acc, ref, group)
         dev.set_tiles(2)
-        y2 = fn(packed, N, K, 0, x_fp16=to_dev(x), workspace=ws)
+        y2 = fn(packed, N, K, group, x_fp16=to_dev(x), workspace=ws)
         assert dev.last_dispatch() == (1, split)
-        assert torch.equal(y2, y)                 # the same sums, the same epilogue arithmetic
+        if group == 0:
+            assert torch.equal(y2, y)             # the same sums, the same epilogue arithmetic
+        else:                                     # fp32 group sums of 16x and 4x operands: same value, own rounding
+            assert_y_close(y2.cpu().numpy().view(np.float16), ref["y"], slack=group_slack(ref))
     finally:
         dev.set_dispatch(0, 0)
         dev.set_tiles(0)

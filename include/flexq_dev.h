@@ -55,7 +55,8 @@ typedef struct {
  * kernel, else the tile configuration (5: 64x128, 7: 128x256, 8: 128x128,
  * 12: 256x256 with both operands through LDS, at most one workgroup per CU,
  * 13: the same with the tiles beyond the last whole round of 256 cut along K,
- * 14: with those tiles run as 256x128 half tiles), s = the number of K splits
+ * 14: with those tiles run as 256x128 half tiles, 15: 128x256 tiles of the same kernel,
+ * for up to 128 tokens on very wide layers), s = the number of K splits
  * (for 13: the number of runs the tail was cut into; for 14: of half tiles; 500 more
  * when the streaming kernel read its activations in tile order).  Results are the same
  * whatever the overrides.

@@ -602,7 +602,7 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
         return launch_cfg<1, 4, 4, 1, 1, 2>(a, st);
     }
     if (cfg == 0) {
-        // Four candidates: 128x256 tiles (two workgroups per CU), 128x128 (three per CU;
+        // The candidates beyond 128 tokens: 128x256 tiles (two workgroups per CU), 128x128 (three per CU;
         // the only shape with K splits), 256x256 with both operands through LDS (one per
         // CU, the fewest bytes per MFMA through the vector-memory path), and the
         // persistent form of the latter that cuts the tiles beyond the last whole round
@@ -626,6 +626,18 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
         // 1.03) takes 1.556 us per 128-k stage plus 7 us
         const double unit = (1.556 * (a.K / 128) + 7.0) * 1.03 / 65536.0;
         double t_best;
+        // Up to 128 tokens on a layer so wide that 128 x 256 tiles alone fill most of the chip
+        // in one round (LLaMA-2-70B's 57344-wide gate+up: 224 tiles): the 128-row form of the
+        // kernel with both operands through LDS, one tile per workgroup, no K split --
+        // measured 66 / 68 / 73 / 80 us at 33 / 64 / 96 / 128 tokens against 68 / 72 / 85 / 94
+        // for the tiles below.
+        if (a.M > 32 && a.M <= 128 && n256 >= 160 && n256 <= kStreamKGrid &&
+            (long)a.N * a.K / 4 * 3 < (1L << 32)) {
+            LinearArgs b = a;
+            b.split_k = 1;
+            *chosen = 15;
+            return launch_gemm_wlds(b, 3, 0, st);
+        }
         if (a.M <= 64) {
             // every token fits a 64-row tile: half the MFMAs and half the activation bytes
             // of the 128x128 tile, same columns and K splits (5-10 % faster, measured)
@@ -668,6 +680,7 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
         *tail_runs = tail_wgs;
         return launch_gemm_wlds(a, 2, tail_wgs, st);
     }
+    if (cfg == 15 && a.split_k == 1) return launch_gemm_wlds(a, 3, 0, st);
     if (cfg == 14 && a.split_k == 1) {
         *tail_runs = 2 * streamk_plan(a.M, a.N, a.K).tail_tiles;
         return launch_gemm_wlds(a, 1, 0, st);

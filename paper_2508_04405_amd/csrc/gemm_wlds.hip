@@ -76,10 +76,8 @@
 
 namespace {
 
-constexpr int BM = 256, WAVES = 8;
-constexpr int XSTAGE = BM * 128;               // bytes of one activation stage
-constexpr int XDMA = BM / 8 / WAVES;           // 1 KiB activation DMA loads per wavefront and stage
-constexpr int SLOT_BYTES = BM * 256 * 4;       // one workgroup's int32 sums of a 256x256 tile
+constexpr int WAVES = 8;
+constexpr int SLOT_BYTES = 256 * 256 * 4;      // one workgroup's int32 sums of a 256x256 tile
 
 // The eight wavefronts share a whole tile 2 along m x 4 along n, 128 x 64 each (MT = 4 row
 // blocks of 32, NT = 2 column blocks of 32: an expanded weight operand feeds four MFMAs,
@@ -91,19 +89,23 @@ constexpr int SLOT_BYTES = BM * 256 * 4;       // one workgroup's int32 sums of 
 // their stages are not bound by LDS reads -- and the lighter shape was kept.  For whole
 // tiles, 1 x 8 wavefronts of 256 x 32 halve the expansion work per MFMA for twice the
 // activation reads: measured 2-5 % slower on every layer.)
-// TILE names the shape: 2 the whole tile, 1 the half tile
+// TILE names the shape: 2 the whole tile (256 x 256), 1 the half tile (256 x 128), 3 the
+// low tile (128 x 256, 2 x 4 wavefronts of 64 x 64: for up to 128 tokens on wide layers)
 template <int TILE>
 struct Shape {
-    static_assert(TILE == 1 || TILE == 2, "half or whole tiles");
+    static_assert(TILE >= 1 && TILE <= 3, "half, whole or low tiles");
     static constexpr int WN = TILE == 1 ? 2 : 4;
-    static constexpr int MT = TILE == 1 ? 2 : 4;
+    static constexpr int MT = TILE == 2 ? 4 : 2;
     static constexpr int NT = 2;
     static constexpr int BN = WN * NT * 32;
-    static_assert(BN == 256 || BN == 128, "whole or half tiles");
-    static_assert(WAVES / WN * MT * 32 == BM, "the wavefronts cover the tile's rows");
+    static constexpr int BM = WAVES / WN * MT * 32;
+    static_assert(BN == 256 || BN == 128, "whole or half width");
+    static_assert(BM == 256 || BM == 128, "whole or half height");
+    static constexpr int XSTAGE = BM * 128;               // bytes of one activation stage
+    static constexpr int XDMA = BM / 8 / WAVES;           // 1 KiB activation DMA loads per wavefront and stage
     static constexpr int WTILES = BN / 32;                        // packed tiles per stage
     static constexpr int WSTAGE = WTILES * FLEXQ_TILE_BYTES;
-    static constexpr int XA = BN == 128 ? 2 : 1;                  // activation stages requested ahead
+    static constexpr int XA = TILE == 2 ? 1 : 2;                  // activation stages requested ahead
     static constexpr int XBUFS = XA + 1;
     static constexpr int WBASE = XBUFS * XSTAGE;
     // this wavefront's weight DMA loads per stage: plane p of a stage is fetched by
@@ -205,7 +207,7 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
     // per 8192 of K + 8 weight panels of 1.5 MB).
     struct Where {
         int bm0, bn0;
-        unsigned xoff[XDMA];
+        unsigned xoff[S::XDMA];
     };
     auto locate = [&](const Item &it, Where &w) {
         int lane_l = lane;        // (opaque: recomputed per item rather than kept live, see the epilogue)
@@ -216,11 +218,11 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
         const int first_m = sup * SUP_M;
         const int span_m = min(SUP_M, tiles_m - first_m);
         const int in_sup = bid - sup * SUP_M * tiles_n;
-        w.bm0 = (first_m + in_sup % span_m) * BM;
+        w.bm0 = (first_m + in_sup % span_m) * S::BM;
         w.bn0 = (in_sup / span_m) * 256 + it.half * S::BN;
 #pragma unroll
-        for (int i = 0; i < XDMA; ++i) {
-            const int q = wave * XDMA + i;
+        for (int i = 0; i < S::XDMA; ++i) {
+            const int q = wave * S::XDMA + i;
             const int row = 8 * q + (lane_l >> 3);
             const int c = (lane_l & 7) ^ ((row >> 1) & 7);
             w.xoff[i] = (unsigned)(w.bm0 + row) * (unsigned)K + 16u * c;
@@ -229,8 +231,8 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
     // activations: global -> LDS by DMA; rows beyond M read as zero (stage numbers count from ks)
     auto dma_x = [&](const Where &w, int ks, int kb, int buf) {
 #pragma unroll
-        for (int i = 0; i < XDMA; ++i) {
-            uint8_t *dst = lds + buf * XSTAGE + (wave * XDMA + i) * 1024;
+        for (int i = 0; i < S::XDMA; ++i) {
+            uint8_t *dst = lds + buf * S::XSTAGE + (wave * S::XDMA + i) * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 xrsrc, (void __attribute__((address_space(3))) *)dst, 16, w.xoff[i],
                 (ks + kb) * FLEXQ_TILE_K, 0, 0);
@@ -321,8 +323,8 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             if (S::XA == 1 && more1) dma_x(at, ks, kb + 1, (CUR + 1) % S::XBUFS);
             if (S::XA == 2 && more2) dma_x(at, ks, kb + 2, (CUR + 2) % S::XBUFS);
 
-            const uint8_t *xs = lds + CUR * XSTAGE;
-            const uint8_t *xn = lds + ((CUR + 1) % S::XBUFS) * XSTAGE;
+            const uint8_t *xs = lds + CUR * S::XSTAGE;
+            const uint8_t *xn = lds + ((CUR + 1) % S::XBUFS) * S::XSTAGE;
             const uint8_t *wcb = lds + wfrag + wcur * S::WSTAGE;
             const uint8_t *wnb = lds + wfrag + wnext * S::WSTAGE;
             wcur = wnext;
@@ -340,7 +342,7 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             // At the hand-over stage kb + 1 (weights and activations, every wavefront's
             // share) must have landed; the loads for stage kb + 2 may be in flight.
             auto hand_over = [&] {
-                constexpr int XFLY = S::XA == 2 ? XDMA : 0;
+                constexpr int XFLY = S::XA == 2 ? S::XDMA : 0;
                 if (!more2)
                     wait_vmcnt<0>();
                 else if (wave < S::WDMA_SPLIT)
@@ -682,6 +684,7 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
 #endif
 }
 
+// FORM 3: `full_count` low tiles (tiles_m counts 128-row tiles) and nothing else.
 // FORM 0: `full_count` whole tiles.  FORM 1: then the `tail_count` tiles that follow them as
 // 2 * tail_count half tiles.  FORM 2: then those tiles cut along K into `tail_wgs` runs.
 // One launch: a second launch for the tail would cost the first one's drain and the
@@ -693,6 +696,10 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_co
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     __shared__ int s_last;
+    if (FORM == 3) {   // every item a low tile (128 x 256)
+        run_items<3, false>(a, lds, s_last, tiles_m, tiles_n, 0, full_count, 0);
+        return;
+    }
     if (full_count > 0) run_items<2, false>(a, lds, s_last, tiles_m, tiles_n, 0, full_count, 0);
 #if defined(__HIP_DEVICE_COMPILE__)
     // The two phases lay LDS out differently: every wavefront must be through with its last
@@ -710,7 +717,7 @@ namespace flexq {
 StreamKPlan streamk_plan(int M, int N, int K)
 {
     StreamKPlan p;
-    p.tiles = ((M + BM - 1) / BM) * ((N + 255) / 256);
+    p.tiles = ((M + 256 - 1) / 256) * ((N + 255) / 256);
     p.full_tiles = p.tiles / kStreamKGrid * kStreamKGrid;
     p.tail_tiles = p.tiles - p.full_tiles;
     // two slots per run; a run is at least one 128-k stage, and there are at most 256 runs
@@ -759,8 +766,8 @@ WldsChoice gemm_wlds_choose(int M, int N, int K, bool may_cut)
 
 namespace {
 
-constexpr int kLdsBytes = Shape<2>::LDS_BYTES > Shape<1>::LDS_BYTES ? Shape<2>::LDS_BYTES
-                                                                                   : Shape<1>::LDS_BYTES;
+constexpr int kLdsMax(int a, int b) { return a > b ? a : b; }
+constexpr int kLdsBytes = kLdsMax(Shape<2>::LDS_BYTES, kLdsMax(Shape<1>::LDS_BYTES, Shape<3>::LDS_BYTES));
 
 template <int FORM>
 hipError_t launch_form(const LinearArgs &a, int tiles_m, int tiles_n, int full_count, int tail_count,
@@ -789,7 +796,11 @@ int grid_for(int items)
 hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_form, int tail_wgs, hipStream_t st)
 {
     if (a.group != 0 || a.split_k > 1 || a.sxg) return hipErrorInvalidValue;
-    const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + 255) / 256;
+    if (tail_form == 3) {   // low tiles throughout
+        const int low_m = (a.M + 127) / 128, cols = (a.N + 255) / 256;
+        return launch_form<3>(a, low_m, cols, low_m * cols, 0, 0, grid_for(low_m * cols), st);
+    }
+    const int tiles_m = (a.M + 256 - 1) / 256, tiles_n = (a.N + 255) / 256;
     const StreamKPlan p = streamk_plan(a.M, a.N, a.K);
     // without room for the partial sums, or on a device that is not 256 CUs wide, a tail
     // that was to be cut runs as whole tiles

@@ -259,6 +259,36 @@ def test_tiled_kernel_persistent_forms(cfg, M, K, N):
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
+@pytest.mark.parametrize("M,K,N", [(128, 1024, 1024),     # four tiles, eight stages
+                                   (33, 256, 22016),       # 86 column tiles, 95 padding rows
+                                   (100, 2304, 1120),      # ragged rows and columns
+                                   (128, 384, 66048),      # 258 tiles: two workgroups take two
+                                   (300, 640, 1536)])      # three row tiles, the last ragged
+def test_tiled_kernel_low_tiles(M, K, N):
+    """The both-operands-through-LDS kernel on 128-row tiles (form 15), the shape for up to
+    128 tokens on wide layers: int32 sums bit-exact, outputs to the bar, with and without
+    the sums asked for."""
+    say(f"128-row tiles through LDS: M={M} K={K} N={N}")
+    w = synth.weights(N, K, 0.02, seed=91)
+    x = synth.activations(M, K, seed=92, outlier_frac=0.02)
+    packed, _, _ = prepare(w)
+    xq, sx = fq.quant_act(to_dev(x), 6)
+    ref = oracle.linear(x, w, 6)
+    ws = fq.make_workspace(M, N, K)
+    dev.set_dispatch(2, 1, 0, 15)
+    try:
+        for _ in range(2):
+            y, acc = run_linear(dev.gemm_w6a6, packed, N, K, 0, xq, sx, True, ws)
+            assert dev.last_dispatch()[0] == 15
+            assert np.array_equal(acc.astype(np.int64), ref["acc"])
+            assert_y_close(y.view(np.float16), ref["y"])
+        y_only = dev.gemm_w6a6(packed, N, K, xq=xq, sx=sx, workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        dev.set_dispatch(0, 0, 0, 0)
+    assert_y_close(y_only.cpu().numpy().view(np.float16), ref["y"])
+
+
 @pytest.mark.parametrize("choice", [1, 2, 3, 4])
 @pytest.mark.parametrize("M", [1, 8, 32])
 def test_ablation_variants_compute_the_same(choice, M):
@@ -699,6 +729,9 @@ def test_dispatch_choices_on_the_70b_layers():
     assert launched(1024, 8192, 8192) == (14, 256)       # 128 tiles as 256 half tiles
     kernel, splits = launched(128, 8192, 8192)
     assert kernel == 8 and splits > 1                     # 128x128 tiles with K splits
+    assert launched(128, 57344, 8192)[0] == 15            # 224 tiles of 128x256: one round
+    assert launched(64, 57344, 8192)[0] == 15
+    assert launched(32, 57344, 8192)[0] == 5              # 64x128 tiles
 
 
 def test_soak_of_the_hand_offs():

@@ -1,4 +1,4 @@
-// Tiled i8-MFMA GEMM with BOTH operands through LDS: 256x256 tiles, or 256x128.
+// Tiled i8-MFMA GEMM with BOTH operands through LDS: 256x256 tiles, 256x128 or 128x256.
 //
 // The 128x256 kernel is limited by power, and what costs power besides the
 // MFMAs is every byte a wavefront brings in through the vector-memory path:
@@ -60,15 +60,19 @@
 // transpose, from which whole 128-byte lines are stored (Section 4.3.2's
 // coalesced write-back, Section 4.3.4's fused dequantization).
 //
-// Three launch forms.  Whole tiles (NT = 2).  Half tiles, 256x128 (NT = 1): the
-// tiles left over after the last whole round of 256, as twice as many items of
-// half the work, so a round of up to 128 leftover tiles costs half a round.
+// Launch forms.  Whole tiles.  Half tiles, 256x128: the tiles left over after
+// the last whole round of 256, as twice as many items of half the work, so a
+// round of up to 128 leftover tiles costs little more than half a round.
 // And the cut tail (SK): the leftover tiles cut along K into equal contiguous
 // runs of 128-k stages, one run per workgroup; a run that is not a whole tile
 // leaves its int32 sums in the workspace (exact, so the order of addition does
 // not matter), the workgroups of a tile add their stage counts to the tile's
 // counter, and the one that completes the count adds the others' sums to its
-// own registers and runs the epilogue.  Nobody waits for anybody.
+// own registers and runs the epilogue.  Nobody waits for anybody.  And low
+// tiles, 128x256, on their own: up to 128 tokens on a layer wide enough for
+// them to fill the chip in one round, where the time is the one pass over the
+// weights (about 37 GB/s per CU come through the DMA path, here as in the
+// whole tiles).
 #include "flexq_device.h"
 #include "flexq_kernels.h"
 #include "gemm_common.h"

@@ -96,6 +96,12 @@ int choose_waves(int M, int N, int K, int ks, int forced = 0)
     // every row block start at once (measured: 19 vs 21 us at 16 tokens, 26 vs 27 at 32)
     const long wgs = (long)(N / 32) * ks;
     if (M >= 16 && wgs > 256 && wgs < 512 && tiles >= 16) return 4;
+    // wide layers with short rows at one to four tokens (the gate+up projections of
+    // LLaMA-2-7B and 13B: 688 and 864 row blocks of 32 and 40 tiles): with four wavefronts
+    // per workgroup every row block is resident from the start (measured at 640 to 1792
+    // row blocks: 13-20 % faster up to 32 tiles per row at one to four tokens, 17-20 % at
+    // 40 to 56 tiles at one token, 3 % at four; no gain from 64 tiles on or from 8 tokens)
+    if (wgs >= 640 && ((tiles <= 32 && M <= 4) || (tiles < 64 && M <= 2))) return 4;
     return tiles >= 16 ? 8 : 4;
 }
 
@@ -173,14 +179,16 @@ bool tiled_addressable(int M, int N, int K)
 // the streaming kernel re-reads the activations once per 32 output channels (and past
 // 32 tokens needs a second MFMA row tile), while the tiled kernel's time stays flat up
 // to 128 tokens but carries the fixed cost of its K splits on small layers.  So: up to
-// 32 tokens stream (24 on very wide layers: the 57344-wide gate+up is 17 % faster tiled
-// at 32), up to 64 on layers of at most 2^25 weights (2^26 with group-wise scales, which
-// have no 64-row tile), up to 128 on layers of at most 2^24 (LLaMA-2-7B's 4096 x 4096:
-// 24 vs 31 us at 128 tokens).
-bool streams_by_choice(int M, int N, int K, int group)
+// 32 tokens stream (24 on very wide layers unless the activations are, or can be written
+// as, packed 6-bit tiles: the 57344-wide gate+up at 25 to 32 tokens takes 73 us tiled,
+// 77-91 us streaming from row-major codes, 72-75 us from 8-bit tiles and 67-69 us from
+// packed 6-bit tiles), up to 64 on layers of at most 2^25 weights (2^26 with group-wise
+// scales, which have no 64-row tile), up to 128 on layers of at most 2^24 (LLaMA-2-7B's
+// 4096 x 4096: 24 vs 31 us at 128 tokens).
+bool streams_by_choice(int M, int N, int K, int group, bool packed_tiles = false)
 {
     const long weights = (long)N * K;
-    return M <= 24 || (M <= 32 && N < 32768) ||
+    return M <= 24 || (M <= 32 && (N < 32768 || packed_tiles)) ||
            (M <= 64 && weights <= (group == 0 ? (1L << 25) : (1L << 26))) ||
            (M <= 128 && weights <= (1L << 24)) || (M <= 64 && !tiled_addressable(M, N, K));
 }
@@ -202,7 +210,7 @@ bool tiles_pay(int act_bits, int M, int K, int split_k)
 
 bool linear_wants_tiles(int act_bits, int M, int N, int K, int group)
 {
-    return streams_by_choice(M, N, K, group) && tiles_pay(act_bits, M, K, choose_split(M, N, K));
+    return streams_by_choice(M, N, K, group, act_bits == 6) && tiles_pay(act_bits, M, K, choose_split(M, N, K));
 }
 
 flexq_status linear_check(const void *packed, int group, const int8_t *xq, const uint16_t *sx,
@@ -244,7 +252,10 @@ flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, i
 
     const int forced = tune.kernel;
     const bool tiled_ok = tiled_addressable(M, N, K);
-    bool stream_kernel = streams_by_choice(M, N, K, group);
+    // fp16 activations at 6 bits can be written as packed tiles, which the streaming kernel
+    // reads fastest
+    const bool may_tile = x_fp16 && !sxg && tune.tiles != 2 && tune.ablate == 0;
+    bool stream_kernel = streams_by_choice(M, N, K, group, may_tile && act_bits == 6);
     // group-wise activation scales reach the tiled kernel by 4-byte DMA loads: even stride
     if (sxg && (sxg_stride % 2 != 0 || !tiled_ok)) stream_kernel = true;
     if (forced == 1) stream_kernel = true;
@@ -260,8 +271,7 @@ flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, i
     const int ks0 = choose_split(M, N, K, tune.split_k);
     const bool fuse = x_fp16 && stream_kernel && tune.fuse != 2 && flexq::skinny_can_fuse(M, K, ks0) &&
                       (tune.fuse == 1 || (M == 1 && (long)(N / 32) * ks0 <= 1024));
-    if (x_fp16 && !fuse && stream_kernel && M <= 32 && !sxg && tune.tiles != 2 && tune.ablate == 0 &&
-        (tune.tiles == 1 || tiles_pay(act_bits, M, K, ks0)))
+    if (may_tile && !fuse && stream_kernel && M <= 32 && (tune.tiles == 1 || tiles_pay(act_bits, M, K, ks0)))
         xt = act_bits;
     if (x_fp16 && !fuse) {
         if (flexq::launch_quant_act(x_fp16, M, K, act_bits, ws.xq, ws.sx, st, xt) != hipSuccess)

@@ -46,7 +46,7 @@ def check_stage(name, h_gpu, bits, y_gpu, cols, w_cols, group):
 def test_layer_runner_stage_by_stage(model):
     H, F, QKV, sigma, group = MODELS[model]
     # (17 to 32 tokens: the producers hand their codes over in tile order, packed at 6 bits)
-    Ms = (1, 16, 24, 1024) if group == 0 else (32, 300)
+    Ms = (1, 16, 24, 32, 1024) if group == 0 else (32, 300)
     seed = 7000 + H
     say(f"layer runner {model}: packing")
     shapes = {"qkv": (QKV, H), "o": (H, H), "gate_up": (2 * F, H), "down": (H, F)}

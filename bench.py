@@ -128,7 +128,7 @@ def sweep(args, torch, fq, fqdev, synth, dev):
         for i, (name, K, N, bits) in enumerate(LAYERS):
             us = sorted(a.elapsed_time(b) * 1e3 for a, b in times[i])[len(times[i]) // 2]
             kern, splits = kinds[i]
-            label = {1: "s", 5: "h", 7: "a", 8: "b", 12: "c", 13: "p", 14: "t", 15: "l"}.get(kern, "?")
+            label = {1: "s", 5: "h", 7: "a", 8: "b", 12: "c", 13: "p", 14: "t", 15: "l", 16: "k"}.get(kern, "?")
             if splits > 1:
                 label += str(splits)
             cells.append("%.1f %s (%.0f, %.0f)" % (us, label, 2.0 * M * N * K / us / 1e6,

@@ -145,8 +145,10 @@ flexq_status flexq_swiglu_quant(const uint16_t *gate_up, int M, int F,
  * shape.  For M > 128, when the 256x256 output tiles do not come in a multiple
  * of 256 (the CUs of an MI355X), it includes up to 128 MiB (512 KiB per 128-k
  * stage of those tiles, at most 256 of them) in which the workgroups sharing a
- * tile of the last, partial round leave their int32 sums.  It depends on M, N
- * and K only.  The workspace must be 256-byte aligned, and its first
+ * tile of the last, partial round leave their int32 sums; for 65 to 128 tokens
+ * on layers up to 22528 wide with rows of at least 3328, up to 22 MiB for the
+ * same purpose (128 KiB per piece of a 128x256 tile cut along K).  It depends on
+ * M, N and K only.  The workspace must be 256-byte aligned, and its first
  * FLEXQ_WORKSPACE_COUNTER_BYTES bytes must be zero before the first call that
  * uses it (flexq_workspace_init does that); every call leaves them zero again.
  * Calls that share a workspace must be ordered on one stream.

@@ -41,9 +41,15 @@ extern "C" {
  *             bits for act_bits 6) for the streaming kernel: 1 = always, 2 = never (the
  *             library's own choice: 17 to 32 tokens, 24 to 32 with 8-bit activations,
  *             whose activation slice does not fit the kernel's LDS staging)
+ *   spin      gemm_cfg 13 with every tile cut into the same number of pieces: how many
+ *             times a piece polls its tile's counter for the other pieces' sums before
+ *             it gives up and leaves its slabs to the piece that completes the count
+ *             (0 = the library's 2048; -1 = never wait, every piece gives up at once:
+ *             the path a busy or smaller device takes; at most 1 << 20)
+ * With gemm_cfg 13, split_k > 1 asks for that many pieces per tile of the last round.
  */
 typedef struct {
-    int kernel, split_k, waves, gemm_cfg, ablate, fuse, tiles;
+    int kernel, split_k, waves, gemm_cfg, ablate, fuse, tiles, spin;
 } flexq_dev_tuning;
 
 /*
@@ -56,8 +62,10 @@ typedef struct {
  * 12: 256x256 with both operands through LDS, at most one workgroup per CU,
  * 13: the same with the tiles beyond the last whole round of 256 cut along K,
  * 14: with those tiles run as 256x128 half tiles, 15: 128x256 tiles of the same kernel,
- * for up to 128 tokens on very wide layers), s = the number of K splits
- * (for 13: the number of runs the tail was cut into; for 14: of half tiles; 500 more
+ * for up to 128 tokens on very wide layers, 16: those tiles each cut along K into
+ * split_k pieces -- 65 to 128 tokens on narrower layers; 17, forced only: 13 with the
+ * tail cut into 256 runs that cross tile borders), s = the number of K splits
+ * (for 13, 16, 17: the number of runs in all; for 14: of half tiles; 500 more
  * when the streaming kernel read its activations in tile order).  Results are the same
  * whatever the overrides.
  */

@@ -156,6 +156,10 @@ size_t workspace_bytes_for(int M, int N, int K)
         const size_t b = gs > 1 ? (size_t)gs * M * N * 4 : 0;
         if (b > partial) partial = b;
     }
+    if (const int pieces = flexq::low_cut_pieces(M, N, K); pieces != 0) {   // 128x256 tiles cut along K
+        const size_t b = flexq::low_cut_bytes((N + 255) / 256 * pieces);
+        if (b > partial) partial = b;
+    }
     if (M > kSkinnyMaxM) {   // the 256x256 kernel's tail cut along K
         const size_t b = flexq::streamk_plan(M, N, K).partial_bytes;
         if (b > partial) partial = b;
@@ -295,6 +299,7 @@ flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, i
     a.sxg_stride = sxg_stride;
     a.ablate = tune.ablate;
     a.xt = xt;
+    if (tune.spin != 0) a.spin = tune.spin < 0 ? 0 : tune.spin;
 
     if (!stream_kernel) {
         // the tiled kernel addresses both operands with 32-bit buffer offsets
@@ -312,7 +317,10 @@ flexq_status linear_impl(const Tuning &tune, int act_bits, const void *packed, i
         if ((size_t)a.split_k * per_split >= ((size_t)1 << 32)) a.split_k = 1;   // 32-bit buffer offsets
         if (a.split_k < 2) a.split_k = 1;
         int cfg = tune.gemm_cfg;
+        const int kt_max = K / 128;
         if (cfg == 0 && tune.split_k > 0 && a.split_k > 1) cfg = 8;   // a forced split is honoured
+        // (13: a forced split is the number of pieces per cut tile; the bounds above do not apply)
+        if (cfg == 13 || cfg == 16) a.split_k = tune.split_k > 1 ? (tune.split_k < kt_max ? tune.split_k : kt_max) : 1;
         int chosen = 0, tail_runs = 0;
         const hipError_t e = flexq::launch_gemm(a, cfg, st, &chosen, &tail_runs);
         if (dispatched) *dispatched = chosen * 1000 + (chosen >= 13 ? tail_runs : a.split_k);

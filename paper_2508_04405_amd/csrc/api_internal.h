@@ -15,6 +15,7 @@ struct Tuning {
     int ablate = 0;     // development build: one design choice of the streaming kernel undone
     int fuse = 0;       // quantize prologue inside the streaming kernel: 1 = whenever it can, 2 = never
     int tiles = 0;      // fp16 activations of up to 32 tokens quantized into tile order: 1 = always, 2 = never
+    int spin = 0;       // evenly cut tiles of the 256-row kernel: polls before a piece gives up waiting; -1 = none
 };
 
 // The argument checks of linear_impl alone (host only, launches nothing).

@@ -19,7 +19,8 @@ flexq_status flexq_dev_linear(const flexq_dev_tuning *tuning, int act_bits, cons
         if (tuning->kernel < 0 || tuning->kernel > 2 || tuning->split_k < 0 || tuning->split_k > 64 ||
             (tuning->waves != 0 && tuning->waves != 4 && tuning->waves != 8 && tuning->waves != 16) ||
             tuning->gemm_cfg < 0 || tuning->gemm_cfg > 32 || tuning->ablate < 0 || tuning->ablate > 4 ||
-            tuning->fuse < 0 || tuning->fuse > 2 || tuning->tiles < 0 || tuning->tiles > 2)
+            tuning->fuse < 0 || tuning->fuse > 2 || tuning->tiles < 0 || tuning->tiles > 2 ||
+            tuning->spin < -1 || tuning->spin > (1 << 20))
             return FLEXQ_EINVAL;
         t.kernel = tuning->kernel;
         t.split_k = tuning->split_k;
@@ -28,6 +29,7 @@ flexq_status flexq_dev_linear(const flexq_dev_tuning *tuning, int act_bits, cons
         t.ablate = tuning->ablate;
         t.fuse = tuning->fuse;
         t.tiles = tuning->tiles;
+        t.spin = tuning->spin;
     }
     if (act_bits != 6 && act_bits != 8) return FLEXQ_EINVAL;
     if (sxg && group != 128) return FLEXQ_EINVAL;

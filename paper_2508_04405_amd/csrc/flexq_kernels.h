@@ -59,6 +59,7 @@ struct LinearArgs {
     const uint16_t *sxg;     // group-wise activation scales [K/128][sxg_stride] (group-major),
     int sxg_stride;          // or null: one scale per token in sx (sxg needs group == 128)
     int ablate;              // 0, or which design choice of the streaming kernel to undo (measurement)
+    int spin = 2048;         // cut tiles of the 256-row kernel: polls of a tile's counter before a piece gives up waiting
 };
 
 hipError_t launch_quant_w6(const float *w, int N, int K, int group, int8_t *wq, uint16_t *sw,
@@ -103,14 +104,18 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
 // tail_form 0: as whole 256x256 tiles; 1: as twice as many 256x128 tiles; 2: cut along K
 // into tail_wgs equal runs of 128-k stages, whose partial sums meet in the partial-sum
 // area (it must hold streamk_plan().partial_bytes; with less, and on a device that is not
-// 256 CUs wide, form 0 runs instead).  Every launch is persistent: at most one workgroup
-// per CU.
+// 256 CUs wide, form 0 runs instead).  tail_form 3: 128x256 tiles and nothing else; 5:
+// those, each cut along K into tail_wgs / tiles pieces (the area must hold
+// low_cut_bytes(tail_wgs); an error, not another form, if that or the piece count does not
+// fit).  Every launch is persistent: at most one workgroup per CU.
 constexpr int kStreamKGrid = 256;   // workgroups of the persistent form: one per CU of an MI355X
 struct StreamKPlan {
     int tiles, full_tiles, tail_tiles;   // 256x256 tiles: all, those in whole rounds, the rest
     size_t partial_bytes;                // workspace for the partial sums of the rest
 };
 StreamKPlan streamk_plan(int M, int N, int K);
+size_t low_cut_bytes(int pieces_in_all);
+int low_cut_pieces(int M, int N, int K);
 // The launch form estimated to be fastest (tail never cut if !may_cut), its estimated time
 // in microseconds, and, for a cut tail, the number of runs (for half tiles: their number).
 struct WldsChoice {

@@ -638,6 +638,18 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
             *chosen = 15;
             return launch_gemm_wlds(b, 3, 0, st);
         }
+        if (const int pieces = low_cut_pieces(a.M, a.N, a.K); pieces != 0) {
+            // 65 to 128 tokens on a narrower layer: the same tiles, each cut along K
+            const int tail_wgs = (int)n256 * pieces;
+            if (a.partial_bytes >= low_cut_bytes(tail_wgs) && device_cu_count() == kStreamKGrid &&
+                (long)a.N * a.K / 4 * 3 < (1L << 32)) {
+                LinearArgs b = a;
+                b.split_k = 1;
+                *chosen = 16;
+                *tail_runs = tail_wgs;
+                return launch_gemm_wlds(b, 5, tail_wgs, st);
+            }
+        }
         if (a.M <= 64) {
             // every token fits a 64-row tile: half the MFMAs and half the activation bytes
             // of the 128x128 tile, same columns and K splits (5-10 % faster, measured)
@@ -673,14 +685,38 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
     }
     *chosen = cfg;
     if (cfg == 12 && a.split_k == 1) return launch_gemm_wlds(a, 0, 0, st);
-    if (cfg == 13 && a.split_k == 1) {
-        // forced: cut the tail also where another form is estimated to be faster
+    if (cfg == 13) {
+        // forced: cut the tail also where another form is estimated to be faster; a forced
+        // number of K splits is the number of pieces per tile
         const WldsChoice c = gemm_wlds_choose(a.M, a.N, a.K, true);
-        const int tail_wgs = c.tail_form == 2 ? c.tail_wgs : kStreamKGrid;
+        int tail_wgs = c.tail_form == 2 ? c.tail_wgs : kStreamKGrid;
+        if (a.split_k > 1) {
+            tail_wgs = streamk_plan(a.M, a.N, a.K).tail_tiles * a.split_k;
+            if (tail_wgs > kStreamKGrid || a.split_k > a.K / FLEXQ_TILE_K) return hipErrorInvalidValue;
+        }
+        LinearArgs b = a;
+        b.split_k = 1;
+        *tail_runs = tail_wgs;
+        return launch_gemm_wlds(b, 2, tail_wgs, st);
+    }
+    if (cfg == 17 && a.split_k == 1) {
+        // the tail cut into 256 equal runs that begin and end inside tiles (never a whole
+        // number of runs per tile: that would be the even cut)
+        const StreamKPlan p = streamk_plan(a.M, a.N, a.K);
+        const long stages = (long)p.tail_tiles * (a.K / FLEXQ_TILE_K);
+        int tail_wgs = stages < kStreamKGrid ? (int)stages : kStreamKGrid;
+        if (p.tail_tiles > 1 && tail_wgs % p.tail_tiles == 0 && tail_wgs > p.tail_tiles) tail_wgs -= 1;
         *tail_runs = tail_wgs;
         return launch_gemm_wlds(a, 2, tail_wgs, st);
     }
     if (cfg == 15 && a.split_k == 1) return launch_gemm_wlds(a, 3, 0, st);
+    if (cfg == 16) {   // 128x256 tiles, each cut into split_k pieces
+        const int tail_wgs = (int)(((a.M + 127) / 128) * ((a.N + 255) / 256)) * a.split_k;
+        LinearArgs b = a;
+        b.split_k = 1;
+        *tail_runs = tail_wgs;
+        return launch_gemm_wlds(b, 5, tail_wgs, st);
+    }
     if (cfg == 14 && a.split_k == 1) {
         *tail_runs = 2 * streamk_plan(a.M, a.N, a.K).tail_tiles;
         return launch_gemm_wlds(a, 1, 0, st);

@@ -63,16 +63,21 @@
 // Launch forms.  Whole tiles.  Half tiles, 256x128: the tiles left over after
 // the last whole round of 256, as twice as many items of half the work, so a
 // round of up to 128 leftover tiles costs little more than half a round.
-// And the cut tail (SK): the leftover tiles cut along K into equal contiguous
-// runs of 128-k stages, one run per workgroup; a run that is not a whole tile
-// leaves its int32 sums in the workspace (exact, so the order of addition does
-// not matter), the workgroups of a tile add their stage counts to the tile's
-// counter, and the one that completes the count adds the others' sums to its
-// own registers and runs the epilogue.  Nobody waits for anybody.  And low
-// tiles, 128x256, on their own: up to 128 tokens on a layer wide enough for
-// them to fill the chip in one round, where the time is the one pass over the
-// weights (about 37 GB/s per CU come through the DMA path, here as in the
-// whole tiles).
+// And the cut tail (SK): the leftover tiles cut along K into contiguous runs of
+// 128-k stages, one run per workgroup, whose int32 sums (exact, so the order of
+// addition does not matter) meet in the workspace.  EVENLY (SK = 2): every tile
+// into the same number of pieces, which end together and share the tile's
+// reduction -- each piece stores the sums of the slabs it does not own, waits a
+// bounded number of polls for the tile's stage count to be complete and
+// finishes the slabs it owns; a piece whose wait runs out leaves its slabs to
+// the piece that completed the count.  Or into 256 equal runs that begin and
+// end inside tiles (SK = 1): the workgroups of a tile add their stage counts
+// to the tile's counter, and the one that completes the count adds the others'
+// sums to its own registers and runs the epilogue; nobody waits for anybody.
+// And low tiles, 128x256, on their own: up to 128 tokens on a layer wide enough
+// for them to fill the chip in one round, where the time is the one pass over
+// the weights (about 37 GB/s per CU come through the DMA path, here as in the
+// whole tiles); on narrower layers, from 65 tokens, each cut evenly along K.
 #include "flexq_device.h"
 #include "flexq_kernels.h"
 #include "gemm_common.h"
@@ -138,7 +143,7 @@ struct Item {
 // One phase of a launch: this workgroup's share of `item_count` items that begin at the
 // 256-wide tile `item_begin` -- whole tiles (TILE = 2), half tiles (two items per tile),
 // or, with SK, the stages of `item_count` tiles cut into `tail_wgs` runs.
-template <int TILE, bool SK>
+template <int TILE, int SK>
 __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *lds, int &s_last, int tiles_m,
                                           int tiles_n, int item_begin, int item_count, int tail_wgs)
 {
@@ -494,7 +499,135 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
 
         // ---- a run that is not a whole tile: leave the sums, or collect the others' ----
         bool finish = true;                              // this workgroup stores the tile
-        if (SK && KN != KT) {
+        unsigned fin_slabs = ~0u;                        // ... these 32-row slabs of each wavefront's part
+        const int pieces = SK == 2 ? tail_wgs / item_count : 1;
+        if (SK == 2 && KN != KT) {
+            // EVEN CUT: every tile is cut into the same number of pieces, one per workgroup,
+            // which therefore reach the end of their runs together.  The reduction is shared:
+            // slab (wavefront w, row block mt) of the tile belongs to piece (w MT + mt) %
+            // pieces.  A piece stores the sums of the slabs it does not own, adds its
+            // stage count to the tile's counter, waits -- a bounded number of polls -- until
+            // the count is complete, adds the other pieces' sums to the slabs it owns and
+            // stores those.  No workgroup ever waits without a bound: a piece whose wait runs
+            // out (its partners are not resident: a busy or smaller device) stores its own
+            // slabs' sums as well, sets its bit in the tile's flag word and leaves; the piece
+            // that completed the count closes the tile after its own slabs (one atomic OR)
+            // and finishes the slabs of every piece whose bit it finds.  A piece that finds
+            // the tile closed when it sets its bit finishes its slabs itself (all sums are
+            // there by then).  Each piece ends with one add to the flag word's leave count;
+            // the last to leave clears counter and flags for the next call.
+            constexpr int kScopeAgent = 16;
+            constexpr unsigned kClosed = 1u << 16, kLeave = 1u << 20;
+            constexpr int PIECE_BYTES = S::BM * 256 * 4;      // one piece's int32 sums: slot `vt` of the area
+            const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
+                a.partial, 0, (unsigned)tail_wgs * (unsigned)PIECE_BYTES, 0x00020000);
+            // (the lane number passes through an opaque statement so that nothing derived
+            // from it here is computed ahead of the main loop and kept in registers across it)
+            int lane_m = lane;
+            asm volatile("" : "+v"(lane_m));
+            const unsigned in_slot = (unsigned)(wave * (PIECE_BYTES / WAVES) + lane_m * 16);
+            const int tj = cur.tj;
+            const int me = vt - tj * pieces;
+            unsigned *flags = a.counters + 2048;
+            auto owner = [&](int mt) { return (wave * MT + mt) % pieces; };      // uniform
+            auto store_slab = [&](int mt) {
+                const unsigned mine = (unsigned)vt * PIECE_BYTES + in_slot;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v4u piece = {(unsigned)acc[mt][nt][4 * q], (unsigned)acc[mt][nt][4 * q + 1],
+                                           (unsigned)acc[mt][nt][4 * q + 2], (unsigned)acc[mt][nt][4 * q + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            piece, prsrc, mine + (unsigned)(((mt * NT + nt) * 4 + q) * 1024), 0, kScopeAgent);
+                    }
+            };
+            auto add_slab = [&](int mt, int from) {
+                const unsigned theirs = (unsigned)(tj * pieces + from) * PIECE_BYTES + in_slot;
+                v4u got[NT * 4];
+#pragma unroll
+                for (int i = 0; i < NT * 4; ++i)
+                    got[i] = __builtin_amdgcn_raw_buffer_load_b128(
+                        prsrc, theirs + (unsigned)((mt * NT * 4 + i) * 1024), 0, kScopeAgent);
+#pragma unroll
+                for (int i = 0; i < NT * 4; ++i)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[mt][i >> 2][4 * (i & 3) + c] += (int)got[i][c];
+            };
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                if (owner(mt) != me) store_slab(mt);
+            wait_vmcnt<0>();
+            lds_barrier();
+            if (tid == 0) {
+                const unsigned prev = __hip_atomic_fetch_add(&a.counters[tj], (unsigned)KN, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT);
+                bool all = prev + (unsigned)KN == (unsigned)KT;
+                const int completed = all ? 1 : 0;
+                for (int poll = 0; !all && poll < a.spin; ++poll) {
+                    __builtin_amdgcn_s_sleep(8);
+                    all = __hip_atomic_load(&a.counters[tj], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                          (unsigned)KT;
+                }
+                s_last = all ? 1 + completed : 0;
+            }
+            lds_barrier();
+            int state = __builtin_amdgcn_readfirstlane(s_last);   // 0 gave up, 1 all sums there, 2 and this piece completed the count
+            lds_barrier();                                        // (read by all before it is written again)
+            if (state == 0) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    if (owner(mt) == me) store_slab(mt);
+                wait_vmcnt<0>();
+                lds_barrier();
+                if (tid == 0) {
+                    const unsigned old = __hip_atomic_fetch_or(&flags[tj], 1u << me, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+                    s_last = (old & kClosed) ? 1 : 0;
+                }
+                lds_barrier();
+                state = __builtin_amdgcn_readfirstlane(s_last);
+                lds_barrier();
+            }
+            fin_slabs = 0;
+            if (state != 0) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    if (owner(mt) == me) {
+                        for (int from = 0; from < pieces; ++from)
+                            if (from != me) add_slab(mt, from);
+                        fin_slabs |= 1u << mt;
+                    }
+                if (state == 2) {
+                    if (tid == 0) {
+                        const unsigned old = __hip_atomic_fetch_or(&flags[tj], kClosed, __ATOMIC_RELAXED,
+                                                                   __HIP_MEMORY_SCOPE_AGENT);
+                        s_last = (int)(old & 0xffffu);
+                    }
+                    lds_barrier();
+                    const unsigned gone = (unsigned)__builtin_amdgcn_readfirstlane(s_last);
+                    lds_barrier();
+                    if (gone != 0) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            if ((gone >> owner(mt)) & 1u) {
+                                for (int from = 0; from < pieces; ++from)
+                                    if (from != me) add_slab(mt, from);
+                                fin_slabs |= 1u << mt;
+                            }
+                    }
+                }
+            }
+            if (tid == 0) {
+                const unsigned old = __hip_atomic_fetch_add(&flags[tj], kLeave, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+                if ((int)(old >> 20) + 1 == pieces) {
+                    __hip_atomic_store(&a.counters[tj], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&flags[tj], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            finish = fin_slabs != 0;
+        } else if (SK == 1 && KN != KT) {
             // [slot][wavefront][block mt, nt][quarter][lane] 16-byte pieces: every store and
             // load below is one contiguous KiB per wavefront.  Cache policy bit 4 = sc1 =
             // device scope: the access goes to memory all XCDs share.
@@ -636,6 +769,7 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
             for (int mt = 0; mt < MT; ++mt) {
                 const int m_slab = bm0 + (wm * MT + mt) * 32;
                 if (m_slab >= M) break;                          // uniform: nothing below is stored
+                if (SK == 2 && !((fin_slabs >> mt) & 1u)) continue;   // uniform: another piece stores this slab
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -688,9 +822,11 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
 #endif
 }
 
-// FORM 3: `full_count` low tiles (tiles_m counts 128-row tiles) and nothing else.
+// FORM 3: `full_count` low tiles (tiles_m counts 128-row tiles) and nothing else.  FORM 5:
+// `tail_count` low tiles, each cut along K into tail_wgs / tail_count pieces.
 // FORM 0: `full_count` whole tiles.  FORM 1: then the `tail_count` tiles that follow them as
-// 2 * tail_count half tiles.  FORM 2: then those tiles cut along K into `tail_wgs` runs.
+// 2 * tail_count half tiles.  FORM 2: then those tiles cut along K into `tail_wgs` runs
+// across tile borders.  FORM 4: then those tiles each cut into tail_wgs / tail_count pieces.
 // One launch: a second launch for the tail would cost the first one's drain and the
 // end-of-kernel cache write-back in between (about 20 us, measured).
 template <int FORM>
@@ -701,22 +837,45 @@ void gemm_wlds_kernel(flexq::LinearArgs a, int tiles_m, int tiles_n, int full_co
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     __shared__ int s_last;
     if (FORM == 3) {   // every item a low tile (128 x 256)
-        run_items<3, false>(a, lds, s_last, tiles_m, tiles_n, 0, full_count, 0);
+        run_items<3, 0>(a, lds, s_last, tiles_m, tiles_n, 0, full_count, 0);
         return;
     }
-    if (full_count > 0) run_items<2, false>(a, lds, s_last, tiles_m, tiles_n, 0, full_count, 0);
+    if (FORM == 5) {   // every low tile cut evenly along K
+        run_items<3, 2>(a, lds, s_last, tiles_m, tiles_n, 0, tail_count, tail_wgs);
+        return;
+    }
+    if (full_count > 0) run_items<2, 0>(a, lds, s_last, tiles_m, tiles_n, 0, full_count, 0);
 #if defined(__HIP_DEVICE_COMPILE__)
     // The two phases lay LDS out differently: every wavefront must be through with its last
     // epilogue's staging rows before anyone's first loads of the next phase land on them.
     if (FORM != 0) lds_barrier();
 #endif
-    if (FORM == 1) run_items<1, false>(a, lds, s_last, tiles_m, tiles_n, full_count, 2 * tail_count, 0);
-    if (FORM == 2) run_items<2, true>(a, lds, s_last, tiles_m, tiles_n, full_count, tail_count, tail_wgs);
+    if (FORM == 1) run_items<1, 0>(a, lds, s_last, tiles_m, tiles_n, full_count, 2 * tail_count, 0);
+    if (FORM == 2) run_items<2, 1>(a, lds, s_last, tiles_m, tiles_n, full_count, tail_count, tail_wgs);
+    if (FORM == 4) run_items<2, 2>(a, lds, s_last, tiles_m, tiles_n, full_count, tail_count, tail_wgs);
 }
 
 }  // namespace
 
 namespace flexq {
+
+size_t low_cut_bytes(int pieces_in_all) { return (size_t)pieces_in_all * (128 * 256 * 4); }
+
+// 65 to 128 tokens on a layer too narrow to fill the chip with 128x256 tiles: every tile
+// cut along K into this many pieces (0: the form does not apply).  Measured on the
+// LLaMA-2-7B and 70B layers at 96 and 128 tokens: fastest with 130 to 190 pieces in all
+// (beyond that the partial sums of all pieces, which cross the memory system at the same
+// moment, cost more than the shorter runs save) and runs of at least 13 stages; 5-22 %
+// faster than 128x128 tiles with K splits in 11 cells of 12.
+int low_cut_pieces(int M, int N, int K)
+{
+    if (M <= 64 || M > 128) return 0;
+    const int tiles = (N + 255) / 256, KT = K / FLEXQ_TILE_K;
+    int pieces = 176 / tiles;
+    if (pieces > KT / 13) pieces = KT / 13;
+    if (pieces > 8) pieces = 8;
+    return pieces >= 2 ? pieces : 0;
+}
 
 StreamKPlan streamk_plan(int M, int N, int K)
 {
@@ -734,11 +893,11 @@ StreamKPlan streamk_plan(int M, int N, int K)
 // of the MI355X.  A 128-k stage of a whole tile takes 1.50 us when every CU has a tile and
 // 1.20 us when at most two thirds of them have (the chip is power-limited: idle CUs let
 // the others clock higher), a half tile's stage 0.93 / 0.75 us; a tile costs 4 us more for
-// its first loads and its epilogue.  Meeting in the workspace costs 14 us plus 2 us per
-// workgroup of a tile when every tile is cut into the same number S of runs (one partial
-// tile per workgroup: 256 KiB written, the last to arrive reads the others'); about 45 us
-// when the tail is simply cut into 256 equal runs, which then begin and end inside tiles
-// (two partial tiles per workgroup).
+// its first loads and its epilogue.  Meeting in the workspace costs 6 to 24 us when every
+// tile is cut into the same number of pieces (one partial tile per workgroup, the pieces of
+// a tile share its reduction); about 45 us when the tail is simply cut into 256 equal
+// runs, which then begin and end inside tiles (two partial tiles per workgroup, the last
+// to arrive at a tile reads the others').
 WldsChoice gemm_wlds_choose(int M, int N, int K, bool may_cut)
 {
     const StreamKPlan p = streamk_plan(M, N, K);
@@ -757,9 +916,14 @@ WldsChoice gemm_wlds_choose(int M, int N, int K, bool may_cut)
     }
     if (!may_cut) return best;
     const double stage_us = 1.50;
-    for (int S = 2; S <= 8 && p.tail_tiles * S <= kStreamKGrid && S <= KT; ++S) {
-        const double t = rounds + stage_us * ((KT + S - 1) / S) + 4.0 + 14.0 + 2.0 * S;
-        if (t < best.us) best = WldsChoice{t, 2, p.tail_tiles * S};
+    // every tile cut into S pieces that share its reduction: the partial sums of all pieces
+    // cross the memory system at the same moment, so meeting costs by their number
+    // (measured on the 8192- and 28672-deep layers at 256 .. 3072 tokens, 64 .. 256 pieces)
+    for (int S = 2; S <= 16 && p.tail_tiles * S <= kStreamKGrid && S <= KT; ++S) {
+        const int wgs = p.tail_tiles * S;
+        const double meet = 6.0 + 0.03 * wgs + (wgs > 192 ? 0.10 * (wgs - 192) : 0.0);
+        const double t = rounds + (1.15 + 0.35 * busy(wgs / 256.0)) * ((KT + S - 1) / S) + 4.0 + meet;
+        if (t < best.us) best = WldsChoice{t, 2, wgs};
     }
     if ((long)p.tail_tiles * KT >= 2L * kStreamKGrid) {
         const double t = rounds + stage_us * KT * p.tail_tiles / kStreamKGrid + 4.0 + 45.0;
@@ -804,6 +968,15 @@ hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_form, int tail_wgs, hi
         const int low_m = (a.M + 127) / 128, cols = (a.N + 255) / 256;
         return launch_form<3>(a, low_m, cols, low_m * cols, 0, 0, grid_for(low_m * cols), st);
     }
+    if (tail_form == 5) {   // low tiles, each cut into tail_wgs / tiles pieces
+        const int low_m = (a.M + 127) / 128, cols = (a.N + 255) / 256, tiles = low_m * cols;
+        const int pieces = tail_wgs / tiles;
+        if (tail_wgs % tiles != 0 || pieces < 2 || pieces > 16 || pieces > a.K / FLEXQ_TILE_K ||
+            tail_wgs > kStreamKGrid || a.partial_bytes < low_cut_bytes(tail_wgs) ||
+            device_cu_count() != kStreamKGrid)
+            return hipErrorInvalidValue;
+        return launch_form<5>(a, low_m, cols, 0, tiles, tail_wgs, (tail_wgs + 7) / 8 * 8, st);
+    }
     const int tiles_m = (a.M + 256 - 1) / 256, tiles_n = (a.N + 255) / 256;
     const StreamKPlan p = streamk_plan(a.M, a.N, a.K);
     // without room for the partial sums, or on a device that is not 256 CUs wide, a tail
@@ -824,6 +997,11 @@ hipError_t launch_gemm_wlds(const LinearArgs &a, int tail_form, int tail_wgs, hi
     if (tail_wgs > kStreamKGrid) tail_wgs = kStreamKGrid;
     if (tail_wgs > stages) tail_wgs = (int)stages;
     const int g = (tail_wgs + 7) / 8 * 8;
+    // every tile cut into the same number of pieces (each at least one stage): the pieces
+    // of a tile end together and share its reduction
+    const int pieces = tail_wgs / p.tail_tiles;
+    if (tail_wgs % p.tail_tiles == 0 && pieces >= 2 && pieces <= 16 && pieces <= a.K / FLEXQ_TILE_K)
+        return launch_form<4>(a, tiles_m, tiles_n, p.full_tiles, p.tail_tiles, tail_wgs, g > g_full ? g : g_full, st);
     return launch_form<2>(a, tiles_m, tiles_n, p.full_tiles, p.tail_tiles, tail_wgs, g > g_full ? g : g_full, st);
 }
 

@@ -17,12 +17,12 @@ from .binding import _check, _dev, _ptr, _stream, make_workspace
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflexq_dev.so")
 _lib = None
-_tuning = dict(kernel=0, split_k=0, waves=0, gemm_cfg=0, ablate=0, fuse=0, tiles=0)
+_tuning = dict(kernel=0, split_k=0, waves=0, gemm_cfg=0, ablate=0, fuse=0, tiles=0, spin=0)
 _last = 0
 
 
 class Tuning(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in ("kernel", "split_k", "waves", "gemm_cfg", "ablate", "fuse", "tiles")]
+    _fields_ = [(n, ctypes.c_int) for n in ("kernel", "split_k", "waves", "gemm_cfg", "ablate", "fuse", "tiles", "spin")]
 
 
 def load():
@@ -66,6 +66,12 @@ def set_tiles(choice=0):
     """1: fp16 activations of up to 32 tokens always go through tile order; 2: never; 0: the
     library's choice."""
     _tuning.update(tiles=choice)
+
+
+def set_spin(polls=0):
+    """Evenly cut tiles (gemm_cfg 13): polls before a piece stops waiting for the others;
+    -1: none (every piece gives up at once); 0: the library's choice."""
+    _tuning.update(spin=polls)
 
 
 def last_dispatch():

@@ -198,7 +198,7 @@ def test_tiled_kernel_k_splits(split, M, group):
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 5, 6, 7, 8, 12, 13, 14])
+@pytest.mark.parametrize("cfg", [1, 2, 5, 6, 7, 8, 12, 13, 14, 17])
 @pytest.mark.parametrize("M,K,N", [(5, 128, 32), (130, 384, 96), (300, 640, 544), (513, 1280, 288),
                                    (512, 256, 544)])
 def test_tiled_kernel_tile_shapes(cfg, M, K, N):
@@ -224,7 +224,7 @@ def test_tiled_kernel_tile_shapes(cfg, M, K, N):
     assert_y_close(y_only.cpu().numpy().view(np.float16), ref["y"])
 
 
-@pytest.mark.parametrize("cfg", [12, 13, 14])
+@pytest.mark.parametrize("cfg", [12, 13, 14, 17])
 @pytest.mark.parametrize("M,K,N", [(768, 256, 22016),     # 258 tiles: a whole round, two tiles left over
                                    (768, 1024, 22016),    # the same, eight stages to cut
                                    (700, 2304, 1120),     # 15 ragged tiles
@@ -234,7 +234,8 @@ def test_tiled_kernel_tile_shapes(cfg, M, K, N):
 def test_tiled_kernel_persistent_forms(cfg, M, K, N):
     """The 256-row kernel with both operands through LDS in its three launch forms: whole
     tiles (12), the tiles beyond the last whole round cut along K with partial sums met in
-    the workspace (13), or run as half tiles (14); workgroups that take several items load
+    the workspace (13: as the estimator cuts them, 17: into 256 runs that cross tile borders),
+    or run as half tiles (14); workgroups that take several items load
     the next one's first stages while they store.  Twice on one workspace: the tile
     counters must be back at zero after every call."""
     say(f"256-row tiles, form {cfg}: M={M} K={K} N={N}")
@@ -255,6 +256,43 @@ def test_tiled_kernel_persistent_forms(cfg, M, K, N):
         torch.cuda.synchronize()
     finally:
         dev.set_dispatch(0, 0, 0, 0)
+    assert_y_close(y_only.cpu().numpy().view(np.float16), ref["y"])
+    assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
+
+
+@pytest.mark.parametrize("spin", [0, -1, 1])
+@pytest.mark.parametrize("pieces", [2, 3, 5, 8, 16])
+@pytest.mark.parametrize("M,K,N,tail", [(300, 2048, 544, 6),       # six ragged tiles of sixteen stages
+                                        (256, 8192, 512, 2),       # two tiles of 64 stages
+                                        (768, 1152, 22016, 2)])    # a whole round first, nine stages to cut
+def test_tiled_kernel_even_cut(M, K, N, tail, pieces, spin):
+    """The tiles of the last round each cut into the same number of pieces, which share the
+    tile's reduction: every piece waits (a bounded number of polls) for the others' sums and
+    finishes its own slabs.  spin = -1: nobody waits, every piece but the one that completes
+    the count gives up and leaves its slabs to that one (what happens when the pieces are
+    not resident together); spin = 1: one poll, a mix of both.  Twice on one workspace."""
+    if pieces > K // 128:
+        pytest.skip("a piece is at least one 128-k stage")
+    say(f"256-row tiles, even cut: M={M} K={K} N={N} pieces={pieces} spin={spin}")
+    w = synth.weights(N, K, 0.02, seed=83)
+    x = synth.activations(M, K, seed=84, outlier_frac=0.02)
+    packed, _, _ = prepare(w)
+    xq, sx = fq.quant_act(to_dev(x), 8)
+    ref = oracle.linear(x, w, 8)
+    ws = fq.make_workspace(M, N, K)
+    dev.set_dispatch(2, pieces, 0, 13)
+    dev.set_spin(spin)
+    try:
+        for _ in range(2):
+            y, acc = run_linear(dev.gemm_w6a8, packed, N, K, 0, xq, sx, True, ws)
+            assert dev.last_dispatch() == (13, tail * pieces)
+            assert np.array_equal(acc.astype(np.int64), ref["acc"])
+            assert_y_close(y.view(np.float16), ref["y"])
+        y_only = dev.gemm_w6a8(packed, N, K, xq=xq, sx=sx, workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        dev.set_dispatch(0, 0, 0, 0)
+        dev.set_spin(0)
     assert_y_close(y_only.cpu().numpy().view(np.float16), ref["y"])
     assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
@@ -287,6 +325,41 @@ def test_tiled_kernel_low_tiles(M, K, N):
     finally:
         dev.set_dispatch(0, 0, 0, 0)
     assert_y_close(y_only.cpu().numpy().view(np.float16), ref["y"])
+
+
+@pytest.mark.parametrize("spin", [0, -1])
+@pytest.mark.parametrize("pieces", [2, 3, 8, 16])
+@pytest.mark.parametrize("M,K,N,tiles", [(128, 2048, 1024, 4),     # four tiles of sixteen stages
+                                         (33, 1152, 1120, 5),      # ragged columns, 95 padding rows, nine stages
+                                         (200, 4096, 544, 6)])     # two row tiles, the second ragged
+def test_tiled_kernel_low_tiles_even_cut(M, K, N, tiles, pieces, spin):
+    """128-row tiles of the both-operands-through-LDS kernel, each cut along K into the same
+    number of pieces that share its reduction (form 16): for up to 128 tokens on layers too
+    narrow to fill the chip with whole tiles.  With the bounded wait and without it."""
+    if pieces > K // 128:
+        pytest.skip("a piece is at least one 128-k stage")
+    say(f"128-row tiles, even cut: M={M} K={K} N={N} pieces={pieces} spin={spin}")
+    w = synth.weights(N, K, 0.02, seed=93)
+    x = synth.activations(M, K, seed=94, outlier_frac=0.02)
+    packed, _, _ = prepare(w)
+    xq, sx = fq.quant_act(to_dev(x), 6)
+    ref = oracle.linear(x, w, 6)
+    ws = fq.make_workspace(M, N, K, extra=tiles * pieces * 128 * 256 * 4)
+    dev.set_dispatch(2, pieces, 0, 16)
+    dev.set_spin(spin)
+    try:
+        for _ in range(2):
+            y, acc = run_linear(dev.gemm_w6a6, packed, N, K, 0, xq, sx, True, ws)
+            assert dev.last_dispatch() == (16, tiles * pieces)
+            assert np.array_equal(acc.astype(np.int64), ref["acc"])
+            assert_y_close(y.view(np.float16), ref["y"])
+        y_only = dev.gemm_w6a6(packed, N, K, xq=xq, sx=sx, workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        dev.set_dispatch(0, 0, 0, 0)
+        dev.set_spin(0)
+    assert_y_close(y_only.cpu().numpy().view(np.float16), ref["y"])
+    assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0
 
 
 @pytest.mark.parametrize("choice", [1, 2, 3, 4])
@@ -684,7 +757,7 @@ def test_random_shapes_forced_tiled_kernels():
         M = int(rng.integers(1, 700))
         K = 128 * int(rng.integers(1, 40))
         N = 32 * int(rng.integers(1, 48))
-        cfg = int(rng.choice([7, 8, 12, 13, 13, 14, 14]))
+        cfg = int(rng.choice([7, 8, 12, 13, 13, 14, 14, 17, 17]))
         split = int(rng.integers(2, 9)) if cfg == 8 and rng.integers(0, 2) else 1
         say(f"random tiled case {case}: M={M} K={K} N={N} cfg={cfg} split={split}")
         w = synth.weights(N, K, 0.02, seed=9100 + case)
@@ -727,22 +800,28 @@ def test_dispatch_choices_on_the_70b_layers():
     assert launched(4096, 10240, 8192)[0] in (13, 14)
     assert launched(1024, 8192, 28672) == (13, 256)      # 128 tiles, two runs each
     assert launched(1024, 8192, 8192) == (14, 256)       # 128 tiles as 256 half tiles
-    kernel, splits = launched(128, 8192, 8192)
+    assert launched(128, 8192, 8192) == (16, 128)         # 32 tiles of 128x256, four pieces each
+    kernel, splits = launched(128, 8192, 3072)            # (rows too short to cut that way)
     assert kernel == 8 and splits > 1                     # 128x128 tiles with K splits
+    assert launched(256, 10240, 8192) == (13, 160)        # 40 tiles of 256x256, four pieces each
     assert launched(128, 57344, 8192)[0] == 15            # 224 tiles of 128x256: one round
     assert launched(64, 57344, 8192)[0] == 15
     assert launched(32, 57344, 8192)[0] == 5              # 64x128 tiles
 
 
 def test_soak_of_the_hand_offs():
-    """The three paths whose workgroups hand partial sums to one another through the
-    workspace (K splits of the streaming kernel, K splits of the 128x128 tiles, the cut tail
-    of the persistent 256x256 kernel): 2000 back-to-back calls each on one workspace, every
+    """The paths whose workgroups hand partial sums to one another through the workspace (K
+    splits of the streaming kernel, K splits of the 128x128 tiles, the persistent kernel's
+    tiles cut along K: into runs across tiles, and evenly with the shared reduction, 256- and
+    128-row tiles): 2000 back-to-back calls each on one workspace, every
     result compared bit for bit with the first (itself checked against the oracle), stopping
     at the first mismatch; the counters end at zero."""
     paths = [("streaming kernel, 4 K splits", 9, 2048, 192, dict(which=1, split_k=4, waves=8)),
              ("128x128 tiles, 3 K splits", 130, 1536, 288, dict(which=2, split_k=3, gemm_cfg=8)),
-             ("256x256 tiles, tail cut along K", 300, 1152, 544, dict(which=2, split_k=1, gemm_cfg=13))]
+             ("256x256 tiles, tail cut along K into runs across tiles", 300, 1152, 544,
+              dict(which=2, split_k=1, gemm_cfg=17)),
+             ("256x256 tiles, each cut into four pieces", 300, 2048, 544, dict(which=2, split_k=4, gemm_cfg=13)),
+             ("128x256 tiles, each cut into three pieces", 100, 2304, 1120, dict(which=2, split_k=3, gemm_cfg=16))]
     for name, M, K, N, force in paths:
         say(f"soak: {name}: M={M} K={K} N={N}")
         w = synth.weights(N, K, 0.02, seed=91)
@@ -750,7 +829,7 @@ def test_soak_of_the_hand_offs():
         ref = oracle.linear(x, w, 8)
         packed, _, _ = prepare(w)
         xq, sx = fq.quant_act(to_dev(x), 8)
-        ws = fq.make_workspace(M, N, K, extra=force["split_k"] * M * N * 4)
+        ws = fq.make_workspace(M, N, K, extra=max(force["split_k"] * M * N * 4, 8 << 20))
         y = torch.empty((M, N), dtype=torch.float16, device=DEV)
         dev.set_dispatch(**force)
         try:

@@ -44,7 +44,7 @@ extern "C" {
  *   spin      gemm_cfg 13 with every tile cut into the same number of pieces: how many
  *             times a piece polls its tile's counter for the other pieces' sums before
  *             it gives up and leaves its slabs to the piece that completes the count
- *             (0 = the library's 2048; -1 = never wait, every piece gives up at once:
+ *             (0 = the library's 128; -1 = never wait, every piece gives up at once:
  *             the path a busy or smaller device takes; at most 1 << 20)
  * With gemm_cfg 13, split_k > 1 asks for that many pieces per tile of the last round.
  */

@@ -59,7 +59,9 @@ struct LinearArgs {
     const uint16_t *sxg;     // group-wise activation scales [K/128][sxg_stride] (group-major),
     int sxg_stride;          // or null: one scale per token in sx (sxg needs group == 128)
     int ablate;              // 0, or which design choice of the streaming kernel to undo (measurement)
-    int spin = 2048;         // cut tiles of the 256-row kernel: polls of a tile's counter before a piece gives up waiting
+    int spin = 128;          // evenly cut tiles: polls of a tile's counter (a microsecond or two each) before a piece
+                             // gives up waiting -- the pieces of a tile end within microseconds of each other when they
+                             // are resident together; when they are not, a short bound costs the least
 };
 
 hipError_t launch_quant_w6(const float *w, int N, int K, int group, int8_t *wq, uint16_t *sw,

@@ -309,7 +309,8 @@ def test_dev_entry_points_argument_errors():
 
     zero = dict(kernel=0, split_k=0, waves=0, gemm_cfg=0, ablate=0, fuse=0)
     for bad in (dict(kernel=3), dict(waves=5), dict(split_k=65), dict(gemm_cfg=33), dict(ablate=5),
-                dict(ablate=-1), dict(kernel=-1), dict(fuse=3)):
+                dict(ablate=-1), dict(kernel=-1), dict(fuse=3), dict(tiles=3), dict(spin=-2),
+                dict(spin=(1 << 20) + 1)):
         assert call(dict(zero, **bad)) == -1, bad
     assert call(zero, bits=7) == -1
     assert call(zero, y=None) == -1              # the same checks as the product call, host side

@@ -656,10 +656,10 @@ hipError_t launch_gemm(const LinearArgs &a, int cfg, hipStream_t st, int *chosen
             *chosen = 5;
             return launch_cfg<1, 4, 2, 1, 0, 4>(a, st);
         }
-        if (a.split_k > 1) {   // K splits were chosen for 128x128 tiles; meeting costs about 11 us
+        if (a.split_k > 1) {   // K splits were chosen for 128x128 tiles; meeting costs about 16 us
             cfg = 8;
             const double *thr8 = m128 * n128 * a.split_k <= 256 ? thr8_sparse : thr8_busy;
-            t_best = busiest_cu(m128 * n128 * a.split_k, 128.0 * 128 / a.split_k, 3, thr8) * unit + 11.0;
+            t_best = busiest_cu(m128 * n128 * a.split_k, 128.0 * 128 / a.split_k, 3, thr8) * unit + 16.0;
         } else {
             const double t7 = busiest_cu(m128 * n256, 128.0 * 256, 2, thr7) * unit;
             const double *thr8 = m128 * n128 <= 256 ? thr8_sparse : thr8_busy;

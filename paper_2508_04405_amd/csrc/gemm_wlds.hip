@@ -542,17 +542,39 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
                             piece, prsrc, mine + (unsigned)(((mt * NT + nt) * 4 + q) * 1024), 0, kScopeAgent);
                     }
             };
-            auto add_slab = [&](int mt, int from) {
+            auto load_slab = [&](v4u (&got)[NT * 4], int mt, int from) {
                 const unsigned theirs = (unsigned)(tj * pieces + from) * PIECE_BYTES + in_slot;
-                v4u got[NT * 4];
 #pragma unroll
                 for (int i = 0; i < NT * 4; ++i)
                     got[i] = __builtin_amdgcn_raw_buffer_load_b128(
                         prsrc, theirs + (unsigned)((mt * NT * 4 + i) * 1024), 0, kScopeAgent);
+            };
+            auto sum_slab = [&](const v4u (&got)[NT * 4], int mt) {
 #pragma unroll
                 for (int i = 0; i < NT * 4; ++i)
 #pragma unroll
                     for (int c = 0; c < 4; ++c) acc[mt][i >> 2][4 * (i & 3) + c] += (int)got[i][c];
+            };
+            // every other piece's sums of slab mt, the next piece's loads in flight while one
+            // piece's sums are added (one round trip in all instead of one per piece)
+            auto gather_slab = [&](int mt) {
+                auto following = [&](int from) {
+                    const int n = from + 1;
+                    return n == me ? n + 1 : n;
+                };
+                v4u got_a[NT * 4], got_b[NT * 4];
+                int from = following(-1);
+                load_slab(got_a, mt, from);
+                for (;;) {
+                    int nxt = following(from);
+                    if (nxt < pieces) load_slab(got_b, mt, nxt);
+                    sum_slab(got_a, mt);
+                    if (nxt >= pieces) break;
+                    from = following(nxt);
+                    if (from < pieces) load_slab(got_a, mt, from);
+                    sum_slab(got_b, mt);
+                    if (from >= pieces) break;
+                }
             };
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -594,8 +616,7 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     if (owner(mt) == me) {
-                        for (int from = 0; from < pieces; ++from)
-                            if (from != me) add_slab(mt, from);
+                        gather_slab(mt);
                         fin_slabs |= 1u << mt;
                     }
                 if (state == 2) {
@@ -611,8 +632,7 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
 #pragma unroll
                         for (int mt = 0; mt < MT; ++mt)
                             if ((gone >> owner(mt)) & 1u) {
-                                for (int from = 0; from < pieces; ++from)
-                                    if (from != me) add_slab(mt, from);
+                                gather_slab(mt);
                                 fin_slabs |= 1u << mt;
                             }
                     }
@@ -893,7 +913,7 @@ StreamKPlan streamk_plan(int M, int N, int K)
 // of the MI355X.  A 128-k stage of a whole tile takes 1.50 us when every CU has a tile and
 // 1.20 us when at most two thirds of them have (the chip is power-limited: idle CUs let
 // the others clock higher), a half tile's stage 0.93 / 0.75 us; a tile costs 4 us more for
-// its first loads and its epilogue.  Meeting in the workspace costs 6 to 24 us when every
+// its first loads and its epilogue.  Meeting in the workspace costs 7 to 27 us when every
 // tile is cut into the same number of pieces (one partial tile per workgroup, the pieces of
 // a tile share its reduction); about 45 us when the tail is simply cut into 256 equal
 // runs, which then begin and end inside tiles (two partial tiles per workgroup, the last
@@ -916,12 +936,13 @@ WldsChoice gemm_wlds_choose(int M, int N, int K, bool may_cut)
     }
     if (!may_cut) return best;
     const double stage_us = 1.50;
-    // every tile cut into S pieces that share its reduction: the partial sums of all pieces
-    // cross the memory system at the same moment, so meeting costs by their number
-    // (measured on the 8192- and 28672-deep layers at 256 .. 3072 tokens, 64 .. 256 pieces)
+    // every tile cut into S pieces that share its reduction: meeting costs by the pieces
+    // per tile (a piece adds S - 1 others' sums) and by their number in all (the partial sums
+    // of all pieces cross the memory system at the same moment); measured on the 8192- and
+    // 28672-deep layers at 256 .. 3072 tokens, 2 .. 8 pieces per tile, 64 .. 256 in all
     for (int S = 2; S <= 16 && p.tail_tiles * S <= kStreamKGrid && S <= KT; ++S) {
         const int wgs = p.tail_tiles * S;
-        const double meet = 6.0 + 0.03 * wgs + (wgs > 192 ? 0.10 * (wgs - 192) : 0.0);
+        const double meet = 1.0 + 2.0 * S + 0.03 * wgs + (wgs > 192 ? 0.03 * (wgs - 192) : 0.0);
         const double t = rounds + (1.15 + 0.35 * busy(wgs / 256.0)) * ((KT + S - 1) / S) + 4.0 + meet;
         if (t < best.us) best = WldsChoice{t, 2, wgs};
     }

@@ -81,9 +81,15 @@ def test_workspace_covers_the_partial_sums():
     assert lib.flexq_workspace_bytes(200, 256, 256) == fixed(200, 256) + 4 * 256 * 256 * 4
     # the answer depends on the shape alone (nothing a caller did before changes it)
     assert lib.flexq_workspace_bytes(1024, 8192, 28672) == dev.load().flexq_workspace_bytes(1024, 8192, 28672)
-    # up to 128 tokens only the K splits of the streaming and 128x128 kernels count
+    # up to 128 tokens only the K splits of the streaming and 128x128 kernels count, and,
+    # from 65 tokens, the pieces of 128x256 tiles cut along K (128 KiB each): 40 tiles in
+    # four pieces on the 10240-wide layer, nothing of the kind on the 57344-wide one (224
+    # tiles fill the chip uncut) or with rows too short to cut (16 stages)
     small = lib.flexq_workspace_bytes(128, 8192, 8192)
     assert fixed(128, 8192) < small < fixed(128, 8192) + 64 * 128 * 8192 * 4
+    assert lib.flexq_workspace_bytes(128, 10240, 8192) == fixed(128, 8192) + 40 * 4 * 128 * 256 * 4
+    assert lib.flexq_workspace_bytes(100, 57344, 8192) < fixed(100, 8192) + 16 * 128 * 256 * 4
+    assert lib.flexq_workspace_bytes(128, 2048, 2048) < fixed(128, 2048) + 16 * 128 * 256 * 4
     # monotone enough for a caller that sizes one workspace for its largest batch
     assert lib.flexq_workspace_bytes(1, 8192, 8192) <= small
 

@@ -117,11 +117,18 @@ struct Shape {
     static constexpr int XA = TILE == 2 ? 1 : 2;                  // activation stages requested ahead
     static constexpr int XBUFS = XA + 1;
     static constexpr int WBASE = XBUFS * XSTAGE;
-    // this wavefront's weight DMA loads per stage: plane p of a stage is fetched by
-    // wavefront p % 8
-    static constexpr int WDMA_LOW = (3 * WTILES + WAVES - 1) / WAVES;    // wavefronts below WDMA_SPLIT
-    static constexpr int WDMA_HIGH = 3 * WTILES / WAVES;                 // the others
-    static constexpr int WDMA_SPLIT = 3 * WTILES % WAVES == 0 ? WAVES : 3 * WTILES % WAVES;
+    // This wavefront's weight DMA loads per stage: plane p of a stage is fetched by
+    // wavefront p % 4.  Wavefronts 0 .. 3 fetch all the weights: the two wavefronts of a SIMD
+    // do not advance alike -- the older one (0 .. 3) wins the arbitration, runs ahead and
+    // waits at the stage's barrier for the younger one, whose instruction stream sets the
+    // pace -- and these loads are work that can move to the wavefronts that have the time
+    // (measured A/B: about 1 % at 2048 and 4096 tokens, 3 % on the half tiles; moving the
+    // activations' loads as well loses 1.3 %: eight more loads in a row per wavefront).
+    static constexpr int WISSUERS = 4;
+    static_assert(3 * WTILES % WISSUERS == 0, "equal shares");
+    static constexpr int WDMA_LOW = 3 * WTILES / WISSUERS;               // wavefronts below WDMA_SPLIT
+    static constexpr int WDMA_HIGH = 0;                                  // the others
+    static constexpr int WDMA_SPLIT = WISSUERS;
     // Epilogue staging, 32 rows of fp16 per wavefront: it begins where the THIRD weight
     // stage does.  While a tile is stored, the next item's first stages are landing in
     // the activation stages below XA and in weight stages 0 and 1; weight stage 2 and what
@@ -248,15 +255,15 @@ __device__ __forceinline__ void run_items(const flexq::LinearArgs &a, uint8_t *l
         }
     };
     // packed weights: the stage's WTILES tiles of three 1 KiB planes go into LDS exactly as
-    // they lie in memory; plane p of the stage is fetched by wavefront p % 8.  The SGPR
+    // they lie in memory; plane p of the stage is fetched by wavefront p % 4.  The SGPR
     // offset is not range-checked: tiles past the last row block re-read the last one and
     // are never stored.
     const unsigned wlane = (unsigned)lane * 16u;
     auto dma_w = [&](const Where &w, int ks, int kb, int buf) {
 #pragma unroll
-        for (int p0 = 0; p0 < 3 * S::WTILES; p0 += WAVES) {
+        for (int p0 = 0; p0 < 3 * S::WTILES; p0 += S::WISSUERS) {
             const int p = p0 + wave;
-            if (p < 3 * S::WTILES) {
+            if (wave < S::WISSUERS) {
                 const int t = p / 3, plane = p - 3 * t;
                 const int wtile = min(w.bn0 / 32 + t, N / 32 - 1);
                 uint8_t *dst = lds + S::WBASE + buf * S::WSTAGE + p * 1024;
